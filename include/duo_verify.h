@@ -1,0 +1,179 @@
+/*
+ * duo_verify.h -- C ABI of the MI355X (gfx950) target-side verification step of DuoDecoding
+ * (arxiv 2503.00784).
+ *
+ * One call scores n draft sequences of k tokens with the target model in a single forward
+ * pass (Alg. 1, right column: p <- M_p(x); Sec. 1 "evaluates all candidate tokens in a single
+ * forward pass"), the sequences being independent branches of a shared prefix (Sec. 3.2,
+ * Fig. 2), then verifies them by speculative sampling (Alg. 2, Sec. 3.3) and commits the
+ * accepted tokens' keys and values to the cache.  The draft model, the draft budget and the
+ * CPU/GPU scheduling of Alg. 1 are host work and not part of this library: draft tokens,
+ * draft distributions and the uniform random numbers of Alg. 2 are inputs.
+ *
+ * Conventions
+ *   - Every pointer below is a DEVICE pointer unless it is marked HOST.  The library never
+ *     allocates, frees or keeps caller memory; scratch space is the caller's `workspace`.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = default
+ *     stream) without host synchronisation.  Arguments are validated on the host before
+ *     anything is enqueued; a negative return code means nothing was enqueued.
+ *   - bf16 values are passed as uint16_t bit patterns.  Matrices are row-major [out][in]
+ *     (y = x W^T), 16-byte aligned, with `in` a multiple of 32.
+ *   - A call with the same inputs and the same `host_prefix_len` is repeatable: cache slots
+ *     below the prefix length are only read, slots at and above it are scratch.
+ */
+#ifndef DUO_VERIFY_H
+#define DUO_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DUO_OK               0
+#define DUO_ERR_NULL        -1  /* a required pointer is NULL */
+#define DUO_ERR_SHAPE       -2  /* unsupported model geometry or n, k out of range */
+#define DUO_ERR_CAPACITY    -3  /* prefix + rows of this call exceed max_seq */
+#define DUO_ERR_ALIGN       -4  /* a pointer is not 16-byte aligned */
+#define DUO_ERR_WORKSPACE   -5  /* workspace smaller than duo_workspace_bytes() */
+#define DUO_ERR_TOKEN_RANGE -6  /* root_token >= vocab */
+#define DUO_ERR_HIP         -7  /* a HIP call failed; see duo_last_hip_error() */
+#define DUO_ERR_ARG         -8  /* temperature <= 0, unknown select_mode, ... */
+
+/* Most rows one call can score: n*k (+1 with a root token). */
+#define DUO_MAX_ROWS 80
+
+/* Bits of the device-side status word (duo_result.status), set by kernels that cannot be
+ * checked on the host without a synchronisation. */
+#define DUO_STATUS_TOKEN_CLAMPED   1  /* a draft token id was outside [0, vocab) and was clamped */
+#define DUO_STATUS_PREFIX_MISMATCH 2  /* *cache.prefix_len differed from call.host_prefix_len */
+
+#define DUO_SELECT_INDEPENDENT_LONGEST 0
+#define DUO_SELECT_PAPER_SEQUENTIAL    1
+
+/* Geometry of the Llama-shaped target (the architecture of the paper's targets, Sec. 4.1
+ * "Models").  head_dim is 64 or 128; d_model, n_q_heads*head_dim and d_ff are multiples of
+ * 32; n_q_heads is a multiple of n_kv_heads; max_seq is a multiple of 8. */
+typedef struct duo_model_config {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, max_seq;
+    float   rope_theta; /* rotary base; pair (d, d + head_dim/2) turns by pos * theta^(-2d/head_dim) */
+    float   rms_eps;
+} duo_model_config;
+
+/* Parameters, bf16.  The nine per-layer tables are HOST arrays of n_layers DEVICE pointers. */
+typedef struct duo_weights {
+    const uint16_t *embed;                    /* [vocab][d_model] */
+    const uint16_t *const *wq;                /* [n_q_heads*head_dim][d_model] */
+    const uint16_t *const *wk, *const *wv;    /* [n_kv_heads*head_dim][d_model] */
+    const uint16_t *const *wo;                /* [d_model][n_q_heads*head_dim] */
+    const uint16_t *const *w_gate, *const *w_up; /* [d_ff][d_model] */
+    const uint16_t *const *w_down;            /* [d_model][d_ff] */
+    const uint16_t *const *g_attn, *const *g_ffn; /* RMSNorm gains [d_model] */
+    const uint16_t *g_final;                  /* [d_model] */
+    const uint16_t *lm_head;                  /* [vocab][d_model] */
+} duo_weights;
+
+/* KV cache, bf16, caller-owned.  Keys are stored after the rotary embedding as
+ * k[layer][kv_head][slot][head_dim]; values are stored TRANSPOSED as
+ * v[layer][kv_head][head_dim][slot] so that the P*V product reads eight consecutive slots of
+ * one channel with a single 16-byte load.  Slots [0, *prefix_len) hold the shared prefix. */
+typedef struct duo_kv_cache {
+    uint16_t *k;
+    uint16_t *v;
+    int32_t  *prefix_len;   /* device scalar P; advanced by the commit */
+    float    *root_logits;  /* fp32 [vocab]: target logits after the last prefix token (from
+                               prefill); read when root_token < 0, may be NULL otherwise */
+} duo_kv_cache;
+
+typedef struct duo_call {
+    int32_t n, k;            /* n sequences of k draft tokens, n*k + (root?1:0) <= DUO_MAX_ROWS */
+    float   temperature;     /* p = softmax(logits / temperature), > 0 */
+    int32_t select_mode;     /* DUO_SELECT_* */
+    int32_t root_token;      /* >= 0: the token emitted by the previous step, scored as one shared
+                                row in front of every sequence (its logits judge the first draft
+                                tokens); < 0: cache.root_logits judges them */
+    int32_t host_prefix_len; /* P as the host knows it; sizes the launch and is checked on device */
+} duo_call;
+
+/* Outputs (device).  Alg. 2 returns the new prefix length, the new prefix and the unverified
+ * suffix; here: per-sequence accepted lengths, the correction / bonus token, and the commit. */
+typedef struct duo_result {
+    int32_t *accept_len; /* [n]  leading accepted draft tokens of each sequence; in paper mode 0 for
+                                 sequences rejected before the selected one, -1 for those after it */
+    int32_t *next_token; /* [n]  correction token (residual sample at the first rejection) or bonus
+                                 token (all k accepted); paper mode: only the selected entry, else -1 */
+    int32_t *commit;     /* [4]  {selected sequence or -1, commit_len, commit_token, new prefix length} */
+    int32_t *status;     /* [1]  DUO_STATUS_* bits, 0 when clean */
+    float   *logits_out; /* optional fp32 [rows][vocab] (rows = (root?1:0) + n*k), may be NULL */
+} duo_result;
+
+/* Bytes of device scratch duo_verify / duo_prefill_chunk need for calls of up to `max_rows` rows. */
+int duo_workspace_bytes(const duo_model_config *cfg, int max_rows, size_t *bytes);
+
+/*
+ * The whole step.  Rows: the root token (if any) at position P and cache slot P, draft token
+ * (i, j) at position P + R + j and slot P + R + i*k + j (R = 1 with a root token).  Row (i, j)
+ * attends to the prefix, the root and (i, j' <= j).  logits of row (i, j) score the token after
+ * draft (i, j): draft (i, 0) is judged by the root distribution, draft (i, j >= 1) by row
+ * (i, j-1), the bonus token is drawn from row (i, k-1).
+ *
+ * Speculative sampling (Alg. 2; accept iff u * q(t) < p(t), i.e. with probability
+ * min(1, p/q); on rejection sample norm(max(0, p - q)) by inverse CDF over ascending ids):
+ *   INDEPENDENT_LONGEST  every sequence is verified on its own (Sec. 3.3, "same procedure as
+ *                        speculative sampling"); the longest (lowest index on ties) is committed.
+ *   PAPER_SEQUENTIAL     first tokens are tested in order against the root distribution, which
+ *                        is replaced by its normalised residual after each rejection (Alg. 2,
+ *                        multi-sequence block); the first accepted sequence is verified to its
+ *                        end; if none is accepted a token is drawn from the final residual.
+ * uniforms[i][j] (j < k) tests draft (i, j); uniforms[i][k] drives the correction / bonus sample
+ * (paper mode, none accepted: uniforms[n-1][k]).
+ *
+ * Commit: keys/values of the selected sequence's first commit_len tokens are moved to slots
+ * P + R + 0.., *prefix_len becomes P + R + commit_len.  The emitted token is not in the cache;
+ * pass it as root_token to the next call.
+ *
+ * draft_tokens int32 [n][k]; draft_probs fp32 [n][k][vocab] (full draft distributions, needed
+ * for residuals); uniforms fp32 [n][k+1] in [0, 1).
+ */
+int duo_verify(const duo_model_config *cfg, const duo_weights *w, duo_kv_cache *cache,
+               const int32_t *draft_tokens, const float *draft_probs, const float *uniforms,
+               const duo_call *call, duo_result *out,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Scores m <= DUO_MAX_ROWS tokens (device int32) as a continuation of the cached prefix with a
+ * plain causal mask, appends their keys/values, advances *prefix_len by m and stores the last
+ * row's logits in cache->root_logits: the target pass of Alg. 1 applied to prompt tokens.
+ */
+int duo_prefill_chunk(const duo_model_config *cfg, const duo_weights *w, duo_kv_cache *cache,
+                      const int32_t *tokens, int m, int host_prefix_len, int32_t *status,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Speculative sampling alone (the second half of duo_verify) on logits the caller supplies:
+ * logits fp32 [R + n*k][vocab] with row stride `vocab`.  Does not touch any KV cache; writes
+ * accept_len, next_token and commit as duo_verify does (new prefix length = host_prefix_len +
+ * R + commit_len).  `workspace` needs duo_sample_workspace_bytes(vocab, n, k) bytes.
+ */
+int duo_sample_workspace_bytes(int vocab, int n, int k, size_t *bytes);
+int duo_spec_sample(const float *logits, const float *root_logits, int vocab,
+                    const int32_t *draft_tokens, const float *draft_probs, const float *uniforms,
+                    const duo_call *call, duo_result *out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One skinny weight-streaming product, the building block of the target pass:
+ * y[m][n] = sum_k x[m][k] * w[n][k], x bf16 [rows_padded][K] (rows_padded = rows rounded up to
+ * 16, all rows readable), w bf16 [N][K], y fp32 [rows][N]; rows <= DUO_MAX_ROWS, K % 32 == 0.
+ */
+int duo_skinny_gemm(const uint16_t *x, const uint16_t *w, float *y, int rows, int N, int K,
+                    void *hip_stream);
+
+const char *duo_status_string(int code);
+const char *duo_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DUO_VERIFY_H */

@@ -20,11 +20,11 @@ What it computes
     then first tokens of the new sequences), used to show the fused form is built from
     the same pieces.
 
-Rounding.  The paper runs the target in FP16 (Sec. 4.1); this build's contract is bf16
-storage with wide accumulation.  `rounding="contract"` rounds to bf16 exactly at the six
-places where the GPU path stores bf16 (normalised activations, rotated Q, cached K, cached
-V, attention output, SwiGLU output); everything else stays float64.  `rounding="ideal"`
-rounds nowhere.  Logits are handed to sampling as float32, sampling is float64.
+Rounding.  The paper runs the target in FP16 (Sec. 4.1); this build's contract is bf16 weights
+and a bf16 KV cache with everything else carried wide.  `rounding="contract"` rounds exactly
+where bf16 is a storage format: the rotated keys and the values written to the cache (the
+weights arrive as bf16 already); every activation stays float64.  `rounding="ideal"` rounds
+nowhere.  Logits are handed to sampling as float32, sampling is float64.
 
 Pins (tests/test_oracle_*.py): HF `transformers` LlamaForCausalLM in float64 (the library
 the paper's implementation builds on), brute-force uncached causal attention, k sequential
@@ -197,7 +197,7 @@ def verify_forward(shape: OracleShape, weights: Dict[str, object], cache: Oracle
     x = embed_rows(weights, tokens)
 
     for l in range(shape.n_layers):
-        h = rnd(rmsnorm(x, _w(weights, "g_attn", l), shape.rms_eps))
+        h = rmsnorm(x, _w(weights, "g_attn", l), shape.rms_eps)
         q = h @ _w(weights, "wq", l).T
         kk = h @ _w(weights, "wk", l).T
         vv = h @ _w(weights, "wv", l).T
@@ -207,9 +207,8 @@ def verify_forward(shape: OracleShape, weights: Dict[str, object], cache: Oracle
         for r, (pos, slot, _) in enumerate(plan):
             q[r] = rope(q[r], pos, shape.rope_theta)
             kk[r] = rope(kk[r], pos, shape.rope_theta)
-        q = rnd(q)
         for r, (_, slot, _) in enumerate(plan):
-            cache.k[l, :, slot, :] = rnd(kk[r])
+            cache.k[l, :, slot, :] = rnd(kk[r])   # the cache stores bf16
             cache.v[l, :, slot, :] = rnd(vv[r])
         attn = np.zeros((M, Hq, D))
         for r, (_, _, vis_rows) in enumerate(plan):
@@ -221,13 +220,10 @@ def verify_forward(shape: OracleShape, weights: Dict[str, object], cache: Oracle
                 s = np.concatenate([k_pre @ q[r, a], k_own @ q[r, a]]) / np.sqrt(D)
                 w = softmax(s)
                 attn[r, a] = w[:P] @ v_pre + w[P:] @ v_own
-        o = rnd(attn.reshape(M, Hq * D))
-        x = x + o @ _w(weights, "wo", l).T
-        h2 = rnd(rmsnorm(x, _w(weights, "g_ffn", l), shape.rms_eps))
-        act = rnd(silu(h2 @ _w(weights, "w_gate", l).T) * (h2 @ _w(weights, "w_up", l).T))
-        x = x + act @ _w(weights, "w_down", l).T
-    hf = rnd(rmsnorm(x, _w(weights, "g_final"), shape.rms_eps))
-    return hf @ _w(weights, "lm_head").T
+        x = x + attn.reshape(M, Hq * D) @ _w(weights, "wo", l).T
+        h2 = rmsnorm(x, _w(weights, "g_ffn", l), shape.rms_eps)
+        x = x + (silu(h2 @ _w(weights, "w_gate", l).T) * (h2 @ _w(weights, "w_up", l).T)) @ _w(weights, "w_down", l).T
+    return rmsnorm(x, _w(weights, "g_final"), shape.rms_eps) @ _w(weights, "lm_head").T
 
 
 def prefill(shape: OracleShape, weights: Dict[str, object], tokens: Sequence[int], max_seq: int,
@@ -254,11 +250,11 @@ def full_forward_uncached(shape: OracleShape, weights: Dict[str, object], tokens
     x = embed_rows(weights, tokens)
     mask = np.tril(np.ones((T, T), dtype=bool))
     for l in range(shape.n_layers):
-        h = rnd(rmsnorm(x, _w(weights, "g_attn", l), shape.rms_eps))
+        h = rmsnorm(x, _w(weights, "g_attn", l), shape.rms_eps)
         q = (h @ _w(weights, "wq", l).T).reshape(T, Hq, D)
         k = (h @ _w(weights, "wk", l).T).reshape(T, Hkv, D)
         v = rnd((h @ _w(weights, "wv", l).T).reshape(T, Hkv, D))
-        q = rnd(np.stack([rope(q[t], t, shape.rope_theta) for t in range(T)]))
+        q = np.stack([rope(q[t], t, shape.rope_theta) for t in range(T)])
         k = rnd(np.stack([rope(k[t], t, shape.rope_theta) for t in range(T)]))
         out = np.zeros((T, Hq, D))
         for a in range(Hq):
@@ -268,10 +264,10 @@ def full_forward_uncached(shape: OracleShape, weights: Dict[str, object], tokens
             s = s - s.max(axis=1, keepdims=True)
             e = np.exp(s)
             out[:, a, :] = (e / e.sum(axis=1, keepdims=True)) @ v[:, kvh, :]
-        x = x + rnd(out.reshape(T, Hq * D)) @ _w(weights, "wo", l).T
-        h2 = rnd(rmsnorm(x, _w(weights, "g_ffn", l), shape.rms_eps))
-        x = x + rnd(silu(h2 @ _w(weights, "w_gate", l).T) * (h2 @ _w(weights, "w_up", l).T)) @ _w(weights, "w_down", l).T
-    return rnd(rmsnorm(x, _w(weights, "g_final"), shape.rms_eps)) @ _w(weights, "lm_head").T
+        x = x + out.reshape(T, Hq * D) @ _w(weights, "wo", l).T
+        h2 = rmsnorm(x, _w(weights, "g_ffn", l), shape.rms_eps)
+        x = x + (silu(h2 @ _w(weights, "w_gate", l).T) * (h2 @ _w(weights, "w_up", l).T)) @ _w(weights, "w_down", l).T
+    return rmsnorm(x, _w(weights, "g_final"), shape.rms_eps) @ _w(weights, "lm_head").T
 
 
 # ----------------------------------------------------------------------------- sampling
@@ -319,9 +315,11 @@ class VerifyResult:
     commit_len: int
     commit_token: int
     new_prefix_len: int
-    # smallest relative margin of any decision that shaped a sequence's outcome
-    margins: np.ndarray = None       # float64 [n]
-    commit_margin: float = np.inf
+    # smallest relative margins of the decisions that shaped each sequence's outcome:
+    # accept tests |u q - p| / p, and the inverse-CDF draw (distance to the nearer CDF edge / total)
+    accept_margins: np.ndarray = None  # float64 [n]
+    draw_margins: np.ndarray = None    # float64 [n]
+    commit_margin: float = np.inf      # min over everything that decided the commit
 
 
 def _chain(i: int, start: int, judge, q, tokens, u, k_draft: int) -> Tuple[int, float]:
@@ -378,15 +376,17 @@ def speculative_verify(logits_f32: np.ndarray, root_logits_f32: np.ndarray, draf
     accept_len = np.zeros(n, dtype=np.int32)
     next_token = np.full(n, -1, dtype=np.int32)
     margins = np.full(n, np.inf)
+    draws = np.full(n, np.inf)
 
     if select_mode == MODE_INDEPENDENT_LONGEST:
         for i in range(n):
             a, m = _chain(i, 0, judge, q, tokens, u, k)
             tok, m2 = finish(i, a)
-            accept_len[i], next_token[i], margins[i] = a, tok, min(m, m2)
+            accept_len[i], next_token[i], margins[i], draws[i] = a, tok, m, m2
         sel = int(np.argmax(accept_len))  # lowest index among the longest
         return VerifyResult(accept_len, next_token, sel, int(accept_len[sel]), int(next_token[sel]),
-                            prefix_len + R + int(accept_len[sel]), margins, float(margins[sel]))
+                            prefix_len + R + int(accept_len[sel]), margins, draws,
+                            float(min(margins.min(), draws[sel])))
 
     if select_mode != MODE_PAPER_SEQUENTIAL:
         raise ValueError("unknown select_mode")
@@ -407,15 +407,17 @@ def speculative_verify(logits_f32: np.ndarray, root_logits_f32: np.ndarray, draf
         p_run = residual_distribution(p_run, q0)
     if sel < 0:
         tok, m2 = inverse_cdf(p_run, u[n - 1, k])
-        return VerifyResult(accept_len, next_token, -1, 0, tok, prefix_len + R, margins,
+        draws[:] = m2
+        return VerifyResult(accept_len, next_token, -1, 0, tok, prefix_len + R, margins, draws,
                             float(min(commit_margin, m2)))
     a, m = _chain(sel, 1, judge, q, tokens, u, k)
     tok, m2 = finish(sel, a)
     accept_len[sel] = a
     next_token[sel] = tok
     accept_len[sel + 1:] = -1
-    margins[sel] = min(margins[sel], m, m2)
-    return VerifyResult(accept_len, next_token, sel, a, tok, prefix_len + R + a, margins,
+    margins[sel] = min(margins[sel], m)
+    draws[sel] = m2
+    return VerifyResult(accept_len, next_token, sel, a, tok, prefix_len + R + a, margins, draws,
                         float(min(commit_margin, m, m2)))
 
 

@@ -1,0 +1,275 @@
+"""ctypes binding of libduo_verify.so: argument marshalling only.
+
+Every step of the verify path runs in the HIP kernels behind the C ABI declared in
+include/duo_verify.h; this module turns torch device tensors into raw pointers and back.
+There is no CPU fallback: if the shared library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libduo_verify.so")
+
+DUO_MAX_ROWS = 80
+SELECT_INDEPENDENT_LONGEST = 0
+SELECT_PAPER_SEQUENTIAL = 1
+STATUS_TOKEN_CLAMPED = 1
+STATUS_PREFIX_MISMATCH = 2
+
+EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
+           "duo_spec_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error"]
+
+_u16p = C.POINTER(C.c_uint16)
+_u16pp = C.POINTER(_u16p)
+
+
+class ModelConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ff",
+                                         "vocab", "max_seq")] + [("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in
+                                          ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")] + \
+               [("g_final", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+class KVCache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("prefix_len", C.c_void_p), ("root_logits", C.c_void_p)]
+
+
+class Call(C.Structure):
+    _fields_ = [("n", C.c_int32), ("k", C.c_int32), ("temperature", C.c_float), ("select_mode", C.c_int32),
+                ("root_token", C.c_int32), ("host_prefix_len", C.c_int32)]
+
+
+class Result(C.Structure):
+    _fields_ = [("accept_len", C.c_void_p), ("next_token", C.c_void_p), ("commit", C.c_void_p),
+                ("status", C.c_void_p), ("logits_out", C.c_void_p)]
+
+
+class DuoError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{where}: {detail} (code {code})")
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_00784_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    lib.duo_workspace_bytes.argtypes = [C.POINTER(ModelConfig), C.c_int, C.POINTER(C.c_size_t)]
+    lib.duo_verify.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(KVCache), C.c_void_p, C.c_void_p,
+                               C.c_void_p, C.POINTER(Call), C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_prefill_chunk.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(KVCache), C.c_void_p, C.c_int,
+                                      C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_sample_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    lib.duo_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Call),
+                                    C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+    for name in ("duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
+                 "duo_spec_sample", "duo_skinny_gemm"):
+        getattr(lib, name).restype = C.c_int
+    lib.duo_status_string.argtypes = [C.c_int]
+    lib.duo_status_string.restype = C.c_char_p
+    lib.duo_last_hip_error.argtypes = []
+    lib.duo_last_hip_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load().duo_status_string(code).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        lib = load()
+        detail = lib.duo_status_string(code).decode()
+        if code == -7:
+            detail += ": " + lib.duo_last_hip_error().decode()
+        raise DuoError(code, where, detail)
+
+
+def make_config(shape, max_seq: int) -> ModelConfig:
+    return ModelConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff,
+                       shape.vocab, max_seq, shape.rope_theta, shape.rms_eps)
+
+
+def workspace_bytes(cfg: ModelConfig, max_rows: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().duo_workspace_bytes(C.byref(cfg), max_rows, C.byref(out)), "duo_workspace_bytes")
+    return out.value
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+_LAYER_KEYS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")
+
+
+class DeviceWeights:
+    """bf16 parameters on the GPU (torch int16 tensors holding the bit patterns) + the C tables."""
+
+    def __init__(self, host_weights: Dict[str, object], device: str = "cuda:0"):
+        import torch
+        self.tensors: Dict[str, object] = {}
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
+        for key in ("embed", "lm_head", "g_final"):
+            self.tensors[key] = up(host_weights[key])
+        for key in _LAYER_KEYS:
+            self.tensors[key] = [up(a) for a in host_weights[key]]
+        self.n_layers = len(self.tensors["wq"])
+        self._tables = {}
+        self.c = Weights()
+        self.c.embed = self.tensors["embed"].data_ptr()
+        self.c.lm_head = self.tensors["lm_head"].data_ptr()
+        self.c.g_final = self.tensors["g_final"].data_ptr()
+        for key in _LAYER_KEYS:
+            tab = (C.c_void_p * self.n_layers)(*[t.data_ptr() for t in self.tensors[key]])
+            self._tables[key] = tab
+            setattr(self.c, key, C.cast(tab, C.POINTER(C.c_void_p)))
+
+
+class VerifyEngine:
+    """Owns the device buffers of one model instance (cache, workspace, results) and calls the C ABI."""
+
+    def __init__(self, shape, host_weights: Dict[str, object], max_seq: int, device: str = "cuda:0",
+                 max_rows: int = DUO_MAX_ROWS, weights: Optional[DeviceWeights] = None):
+        import torch
+        self.torch = torch
+        self.lib = load()
+        self.shape = shape
+        self.device = device
+        self.cfg = make_config(shape, max_seq)
+        self.max_seq = max_seq
+        self.weights = weights if weights is not None else DeviceWeights(host_weights, device)
+        L, H, D = shape.n_layers, shape.n_kv_heads, shape.head_dim
+        self.k = torch.zeros((L, H, max_seq, D), dtype=torch.int16, device=device)
+        self.vT = torch.zeros((L, H, D, max_seq), dtype=torch.int16, device=device)
+        self.prefix_len = torch.zeros(1, dtype=torch.int32, device=device)
+        self.root_logits = torch.zeros(shape.vocab, dtype=torch.float32, device=device)
+        self.ws_bytes = workspace_bytes(self.cfg, max_rows)
+        self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
+        self.accept_len = torch.zeros(DUO_MAX_ROWS, dtype=torch.int32, device=device)
+        self.next_token = torch.zeros(DUO_MAX_ROWS, dtype=torch.int32, device=device)
+        self.commit = torch.zeros(4, dtype=torch.int32, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self.cache_c = KVCache(self.k.data_ptr(), self.vT.data_ptr(), self.prefix_len.data_ptr(),
+                               self.root_logits.data_ptr())
+        self.host_prefix_len = 0
+
+    # ---- cache management (plain copies, no arithmetic)
+    def load_cache(self, k_bits: np.ndarray, v_bits: np.ndarray, prefix_len: int,
+                   root_logits: Optional[np.ndarray]) -> None:
+        """k_bits, v_bits: uint16 [L][Hkv][max_seq][D] (row layout); V is transposed on upload."""
+        torch = self.torch
+        self.k.copy_(torch.from_numpy(np.ascontiguousarray(k_bits).view(np.int16)))
+        v = torch.from_numpy(np.ascontiguousarray(v_bits).view(np.int16)).to(self.device)
+        self.vT.copy_(v.permute(0, 1, 3, 2))
+        del v
+        self.set_prefix_len(prefix_len)
+        if root_logits is not None:
+            self.root_logits.copy_(torch.from_numpy(np.asarray(root_logits, dtype=np.float32)))
+
+    def set_prefix_len(self, p: int) -> None:
+        self.host_prefix_len = int(p)
+        self.prefix_len.fill_(int(p))
+
+    def cache_to_host(self):
+        """(k, v) as uint16 [L][Hkv][max_seq][D] in the row layout."""
+        k = self.k.cpu().numpy().view(np.uint16)
+        v = self.vT.permute(0, 1, 3, 2).contiguous().cpu().numpy().view(np.uint16)
+        return k, v
+
+    # ---- entry points
+    def prefill(self, tokens: Sequence[int], chunk: int = 64) -> None:
+        torch = self.torch
+        toks = torch.tensor(list(tokens), dtype=torch.int32, device=self.device)
+        for s in range(0, len(tokens), chunk):
+            m = min(chunk, len(tokens) - s)
+            rc = self.lib.duo_prefill_chunk(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),
+                                            toks[s:s + m].data_ptr(), m, self.host_prefix_len, self.status.data_ptr(),
+                                            self.workspace.data_ptr(), self.ws_bytes, _stream_ptr())
+            _check(rc, "duo_prefill_chunk")
+            self.host_prefix_len += m
+
+    def verify(self, draft_tokens, draft_probs, uniforms, temperature: float = 1.0,
+               select_mode: int = SELECT_INDEPENDENT_LONGEST, root_token: int = -1, logits_out=None) -> None:
+        """Enqueue one verify step on torch's current stream.  Inputs are device tensors:
+        draft_tokens int32 [n][k], draft_probs fp32 [n][k][V], uniforms fp32 [n][k+1]."""
+        n, k = draft_tokens.shape
+        call = Call(n, k, float(temperature), int(select_mode), int(root_token), self.host_prefix_len)
+        res = Result(self.accept_len.data_ptr(), self.next_token.data_ptr(), self.commit.data_ptr(),
+                     self.status.data_ptr(), _ptr(logits_out))
+        rc = self.lib.duo_verify(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),
+                                 draft_tokens.data_ptr(), draft_probs.data_ptr(), uniforms.data_ptr(), C.byref(call),
+                                 C.byref(res), self.workspace.data_ptr(), self.ws_bytes, _stream_ptr())
+        _check(rc, "duo_verify")
+
+    def results(self, n: int) -> Dict[str, object]:
+        """Synchronise and fetch the outputs of the last verify call."""
+        self.torch.cuda.synchronize()
+        commit = self.commit.cpu().numpy()
+        self.host_prefix_len = int(commit[3])  # the commit advanced the device-side prefix length
+        return {"accept_len": self.accept_len[:n].cpu().numpy(), "next_token": self.next_token[:n].cpu().numpy(),
+                "selected": int(commit[0]), "commit_len": int(commit[1]), "commit_token": int(commit[2]),
+                "new_prefix_len": int(commit[3]), "status": int(self.status.cpu().numpy()[0]),
+                "device_prefix_len": int(self.prefix_len.cpu().numpy()[0])}
+
+
+def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temperature: float = 1.0,
+                select_mode: int = SELECT_INDEPENDENT_LONGEST, has_root: bool = False, prefix_len: int = 0
+                ) -> Dict[str, object]:
+    """duo_spec_sample on device tensors; returns host results."""
+    import torch
+    lib = load()
+    n, k = draft_tokens.shape
+    vocab = logits.shape[-1]
+    nbytes = C.c_size_t(0)
+    _check(lib.duo_sample_workspace_bytes(vocab, n, k, C.byref(nbytes)), "duo_sample_workspace_bytes")
+    dev = logits.device
+    ws = torch.empty(nbytes.value, dtype=torch.uint8, device=dev)
+    accept_len = torch.zeros(n, dtype=torch.int32, device=dev)
+    next_token = torch.zeros(n, dtype=torch.int32, device=dev)
+    commit = torch.zeros(4, dtype=torch.int32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    call = Call(n, k, float(temperature), int(select_mode), 0 if has_root else -1, int(prefix_len))
+    res = Result(accept_len.data_ptr(), next_token.data_ptr(), commit.data_ptr(), status.data_ptr(), None)
+    rc = lib.duo_spec_sample(logits.data_ptr(), _ptr(root_logits), vocab, draft_tokens.data_ptr(), draft_probs.data_ptr(),
+                             uniforms.data_ptr(), C.byref(call), C.byref(res), ws.data_ptr(), nbytes.value, _stream_ptr())
+    _check(rc, "duo_spec_sample")
+    torch.cuda.synchronize()
+    c = commit.cpu().numpy()
+    return {"accept_len": accept_len.cpu().numpy(), "next_token": next_token.cpu().numpy(), "selected": int(c[0]),
+            "commit_len": int(c[1]), "commit_token": int(c[2]), "new_prefix_len": int(c[3]),
+            "status": int(status.cpu().numpy()[0])}
+
+
+def skinny_gemm(x_bits, w_bits, rows: int):
+    """y = x W^T through duo_skinny_gemm.  x_bits int16 [rows_padded][K], w_bits int16 [N][K] (device)."""
+    import torch
+    N, K = w_bits.shape
+    y = torch.empty((rows, N), dtype=torch.float32, device=x_bits.device)
+    _check(load().duo_skinny_gemm(x_bits.data_ptr(), w_bits.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()),
+           "duo_skinny_gemm")
+    return y

@@ -1,0 +1,347 @@
+// C ABI of the verify step: host-side validation, workspace carving and the launch sequence.
+// Everything that computes lives in the kernels of duo_gemm.h / duo_attn.h / duo_rowops.h /
+// duo_sample.h; this file only enqueues them on the caller's stream.
+#include "../../include/duo_verify.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "duo_attn.h"
+#include "duo_common.h"
+#include "duo_gemm.h"
+#include "duo_rowops.h"
+#include "duo_sample.h"
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int MAX_CHUNKS = 64;
+
+// GEMM operand buffers (h, attn, act) hold activations as bf16 pairs: row m = hi, row pair_rows + m = lo,
+// padded to whole 16-row MFMA tiles; rows that carry no activation are never stored from.
+struct Workspace {
+    float* x;        // fp32 residual stream [M][d]
+    u16* h;          // normalised activations, operand layout [A_rows][d]
+    u16* q;          // rotated queries: hi plane [Mp][Hq*D], lo plane [Mp][Hq*D]
+    u16* attn;       // attention output, operand layout [A_rows][Hq*D]
+    u16* act;        // SwiGLU output, operand layout [A_rows][F]
+    float* part;     // attention chunk partials
+    float* rope_c;   // [Mp][D/2]
+    float* rope_s;
+    float* logits;   // fp32 [Mp][V]
+    double* stats;   // sampler
+    double* p_run;
+    int32_t* acc;
+    size_t q_plane;  // elements between the two query planes
+    size_t total;
+};
+
+size_t sample_ws_bytes(int vocab) {
+    return align_up((size_t)2 * DUO_MAX_ROWS * 2 * sizeof(double), 256) + align_up((size_t)vocab * sizeof(double), 256) +
+           align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256);
+}
+
+void carve_sampler(char* base, size_t& off, int vocab, Workspace& ws) {
+    ws.stats = reinterpret_cast<double*>(base + off);
+    off += align_up((size_t)2 * DUO_MAX_ROWS * 2 * sizeof(double), 256);
+    ws.p_run = reinterpret_cast<double*>(base + off);
+    off += align_up((size_t)vocab * sizeof(double), 256);
+    ws.acc = reinterpret_cast<int32_t*>(base + off);
+    off += align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256);
+}
+
+Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
+    Workspace ws{};
+    char* base = static_cast<char*>(base_v);
+    const size_t Mp = align_up((size_t)max_rows, 16);
+    const size_t Ar = (size_t)a_tiles_for(max_rows, true) * 16;
+    const size_t d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim, F = c.d_ff, V = c.vocab;
+    const size_t group = c.n_q_heads / c.n_kv_heads;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = base + off;
+        off += align_up(bytes, 256);
+        return p;
+    };
+    ws.x = reinterpret_cast<float*>(take(Mp * d * 4));
+    ws.h = reinterpret_cast<u16*>(take(Ar * d * 2));
+    ws.q_plane = Mp * qd;
+    ws.q = reinterpret_cast<u16*>(take(2 * Mp * qd * 2));
+    ws.attn = reinterpret_cast<u16*>(take(Ar * qd * 2));
+    ws.act = reinterpret_cast<u16*>(take(Ar * F * 2));
+    ws.part = reinterpret_cast<float*>(take((size_t)c.n_kv_heads * (Mp * group) * MAX_CHUNKS * (c.head_dim + 4) * 4));
+    ws.rope_c = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
+    ws.rope_s = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
+    ws.logits = reinterpret_cast<float*>(take(Mp * V * 4));
+    carve_sampler(base, off, c.vocab, ws);
+    ws.total = off;
+    return ws;
+}
+
+int check_config(const duo_model_config* c) {
+    if (!c) return DUO_ERR_NULL;
+    if (c->n_layers < 1 || c->d_model < 32 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ff < 32 || c->vocab < 2 ||
+        c->max_seq < 32)
+        return DUO_ERR_SHAPE;
+    if (c->head_dim != 64 && c->head_dim != 128) return DUO_ERR_SHAPE;
+    if (c->d_model % 32 || c->d_ff % 32 || c->max_seq % 32) return DUO_ERR_SHAPE;
+    if (c->n_q_heads % c->n_kv_heads) return DUO_ERR_SHAPE;
+    if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return DUO_ERR_SHAPE;
+    return DUO_OK;
+}
+
+int check_weights(const duo_model_config* c, const duo_weights* w) {
+    if (!w || !w->embed || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down || !w->g_attn ||
+        !w->g_ffn || !w->g_final || !w->lm_head)
+        return DUO_ERR_NULL;
+    if (!aligned16(w->embed) || !aligned16(w->lm_head) || !aligned16(w->g_final)) return DUO_ERR_ALIGN;
+    const uint16_t* const* tabs[9] = {w->wq, w->wk, w->wv, w->wo, w->w_gate, w->w_up, w->w_down, w->g_attn, w->g_ffn};
+    for (auto tab : tabs)
+        for (int l = 0; l < c->n_layers; ++l) {
+            if (!tab[l]) return DUO_ERR_NULL;
+            if (!aligned16(tab[l])) return DUO_ERR_ALIGN;
+        }
+    return DUO_OK;
+}
+
+int hip_ok(hipError_t e, const char* what) {
+    if (e == hipSuccess) return DUO_OK;
+    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
+    return DUO_ERR_HIP;
+}
+
+template <int D>
+void launch_attention(int mtw, dim3 grid, const AttnArgs& a, hipStream_t s) {
+    switch (mtw) {
+        case 1: hipLaunchKernelGGL((attn_partial_kernel<D, 1>), grid, dim3(256), 0, s, a); break;
+        default: hipLaunchKernelGGL((attn_partial_kernel<D, 2>), grid, dim3(256), 0, s, a); break;
+    }
+}
+
+// The target pass over the rows of `plan`: fills the cache slots P .. P+M-1 and writes fp32
+// logits [M][V] (row stride V) to `logits`.
+void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_kv_cache& cache,
+                     const int32_t* tokens, int root_token, const RowPlan& plan, const Workspace& ws,
+                     float* logits, int32_t* status, hipStream_t s) {
+    const int M = plan.M, Mp = (M + 15) / 16 * 16, PR = pair_rows_for(M);
+    const int d = c.d_model, D = c.head_dim, half = D / 2, Hq = c.n_q_heads, Hkv = c.n_kv_heads;
+    const int qd = Hq * D, F = c.d_ff, V = c.vocab, group = Hq / Hkv;
+
+    hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(64), 0, s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
+    hipLaunchKernelGGL(embed_norm_kernel, dim3(M), dim3(256), 0, s, w.embed, tokens, root_token, plan, V,
+                       cache.prefix_len, status, ws.x, w.g_attn[0], ws.h, d, PR, c.rms_eps);
+
+    // attention launch shape
+    const int Ktot = plan.P + M;
+    const int NB = (Ktot + 31) / 32;
+    const int MQ = M * group, MqT = (MQ + 15) / 16;
+    const int mtw = MqT >= 2 ? 2 : 1;
+    const int MG = (MqT + mtw - 1) / mtw;
+    int target = (1024 + Hkv * MG - 1) / (Hkv * MG);
+    target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
+    const int bpw = (NB + 4 * target - 1) / (4 * target);
+    const int nchunks = (NB + 4 * bpw - 1) / (4 * bpw);
+    const int mq_pad = Mp * group;
+
+    for (int l = 0; l < c.n_layers; ++l) {
+        u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
+        u16* vc = cache.v + (size_t)l * Hkv * D * c.max_seq;
+        EpiQKV eq{w.wq[l], w.wk[l], w.wv[l], d, Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq,
+                  ws.rope_c, ws.rope_s, plan};
+        launch_gemm_rows<2>(M, true, ws.h, d, d, (Hq + 2 * Hkv) * (half / 16), eq, s);
+
+        AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
+                    1.4426950408889634f / sqrtf((float)D), ws.part};
+        const dim3 grid(nchunks, Hkv, MG);
+        if (D == 128) launch_attention<128>(mtw, grid, aa, s);
+        else launch_attention<64>(mtw, grid, aa, s);
+        if (D == 128)
+            hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), 0, s, ws.part, nchunks, mq_pad, group, M,
+                               ws.attn, qd, PR);
+        else
+            hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), 0, s, ws.part, nchunks, mq_pad, group, M,
+                               ws.attn, qd, PR);
+
+        EpiResidual eo{w.wo[l], qd, d, M, 1, ws.x, d};
+        launch_gemm_rows<1>(M, true, ws.attn, qd, qd, d / 16, eo, s);
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, w.g_ffn[l], ws.h, d, PR, c.rms_eps);
+
+        EpiSwiGLU eg{w.w_gate[l], w.w_up[l], d, F, M, ws.act, F, PR};
+        launch_gemm_rows<2>(M, true, ws.h, d, d, F / 16, eg, s);
+
+        EpiResidual ed{w.w_down[l], F, d, M, 1, ws.x, d};
+        launch_gemm_rows<1>(M, true, ws.act, F, F, d / 16, ed, s);
+        const u16* gnext = l + 1 < c.n_layers ? w.g_attn[l + 1] : w.g_final;
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, gnext, ws.h, d, PR, c.rms_eps);
+    }
+    EpiStoreF32 el{w.lm_head, d, V, M, 2, logits, V};
+    launch_gemm_rows<2>(M, true, ws.h, d, d, (V + 31) / 32, el, s);
+}
+
+void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
+                      hipStream_t s) {
+    hipLaunchKernelGGL(sample_stats_kernel, dim3(sa.k + 1, sa.n), dim3(256), 0, s, sa);
+    if (mode == DUO_SELECT_INDEPENDENT_LONGEST)
+        hipLaunchKernelGGL(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), 0, s, sa);
+    else
+        hipLaunchKernelGGL(sample_paper_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, s, sa);
+    CommitArgs ca{kc, vc, c ? c->n_kv_heads : 1, c ? c->head_dim : 0, c ? c->max_seq : 0, sa.P, sa.R, sa.n, sa.k, mode,
+                  sa.accept_len, sa.next_token, sa.commit, prefix_len};
+    const dim3 grid = kc ? dim3(c->n_kv_heads, c->n_layers) : dim3(1, 1);
+    hipLaunchKernelGGL(commit_kernel, grid, dim3(256), 0, s, ca);
+}
+
+int check_call(const duo_call* call, int vocab) {
+    if (!call) return DUO_ERR_NULL;
+    if (call->n < 1 || call->k < 1) return DUO_ERR_SHAPE;
+    const int R = call->root_token >= 0 ? 1 : 0;
+    if ((long long)call->n * call->k + R > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
+    if (!(call->temperature > 0.f)) return DUO_ERR_ARG;
+    if (call->select_mode != DUO_SELECT_INDEPENDENT_LONGEST && call->select_mode != DUO_SELECT_PAPER_SEQUENTIAL)
+        return DUO_ERR_ARG;
+    if (call->root_token >= vocab) return DUO_ERR_TOKEN_RANGE;
+    if (call->host_prefix_len < 0) return DUO_ERR_ARG;
+    return DUO_OK;
+}
+
+int check_result(const duo_result* out) {
+    if (!out || !out->accept_len || !out->next_token || !out->commit || !out->status) return DUO_ERR_NULL;
+    return DUO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int duo_workspace_bytes(const duo_model_config* cfg, int max_rows, size_t* bytes) {
+    if (!bytes) return DUO_ERR_NULL;
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (max_rows < 1 || max_rows > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
+    *bytes = carve(*cfg, max_rows, nullptr).total;
+    return DUO_OK;
+}
+
+int duo_verify(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* cache, const int32_t* draft_tokens,
+               const float* draft_probs, const float* uniforms, const duo_call* call, duo_result* out, void* workspace,
+               size_t workspace_bytes, void* hip_stream) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if ((rc = check_weights(cfg, w))) return rc;
+    if (!cache || !cache->k || !cache->v || !cache->prefix_len || !draft_tokens || !draft_probs || !uniforms || !workspace)
+        return DUO_ERR_NULL;
+    if ((rc = check_call(call, cfg->vocab))) return rc;
+    if ((rc = check_result(out))) return rc;
+    const int R = call->root_token >= 0 ? 1 : 0;
+    if (!R && !cache->root_logits) return DUO_ERR_NULL;
+    const int M = R + call->n * call->k;
+    if ((long long)call->host_prefix_len + M > cfg->max_seq) return DUO_ERR_CAPACITY;
+    if (!aligned16(cache->k) || !aligned16(cache->v) || !aligned16(workspace) || !aligned16(draft_probs) ||
+        (out->logits_out && !aligned16(out->logits_out)))
+        return DUO_ERR_ALIGN;
+    const Workspace ws = carve(*cfg, M, workspace);
+    if (workspace_bytes < ws.total) return DUO_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, out->status, 1, 0);
+    const RowPlan plan{call->host_prefix_len, R, call->n, call->k, M};
+    float* logits = out->logits_out ? out->logits_out : ws.logits;
+    enqueue_forward(*cfg, *w, *cache, draft_tokens, call->root_token, plan, ws, logits, out->status, s);
+    SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, call->n, call->k, R, call->host_prefix_len,
+                  (double)call->temperature, draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run,
+                  out->accept_len, out->next_token, out->commit, out->status};
+    enqueue_sampling(sa, call->select_mode, cache->k, cache->v, cfg, cache->prefix_len, s);
+    return hip_ok(hipGetLastError(), "duo_verify launch");
+}
+
+int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* cache, const int32_t* tokens, int m,
+                      int host_prefix_len, int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if ((rc = check_weights(cfg, w))) return rc;
+    if (!cache || !cache->k || !cache->v || !cache->prefix_len || !cache->root_logits || !tokens || !status || !workspace)
+        return DUO_ERR_NULL;
+    if (m < 1 || m > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
+    if (host_prefix_len < 0) return DUO_ERR_ARG;
+    if ((long long)host_prefix_len + m > cfg->max_seq) return DUO_ERR_CAPACITY;
+    if (!aligned16(cache->k) || !aligned16(cache->v) || !aligned16(workspace)) return DUO_ERR_ALIGN;
+    const Workspace ws = carve(*cfg, m, workspace);
+    if (workspace_bytes < ws.total) return DUO_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, status, 1, 0);
+    const RowPlan plan{host_prefix_len, 0, 1, m, m};
+    enqueue_forward(*cfg, *w, *cache, tokens, -1, plan, ws, ws.logits, status, s);
+    hipLaunchKernelGGL(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), 0, s,
+                       ws.logits + (size_t)(m - 1) * cfg->vocab, cache->root_logits, cfg->vocab, cache->prefix_len,
+                       host_prefix_len + m);
+    return hip_ok(hipGetLastError(), "duo_prefill_chunk launch");
+}
+
+int duo_sample_workspace_bytes(int vocab, int n, int k, size_t* bytes) {
+    if (!bytes) return DUO_ERR_NULL;
+    if (vocab < 2 || n < 1 || k < 1 || (long long)n * k + 1 > DUO_MAX_ROWS + 1) return DUO_ERR_SHAPE;
+    *bytes = sample_ws_bytes(vocab);
+    return DUO_OK;
+}
+
+int duo_spec_sample(const float* logits, const float* root_logits, int vocab, const int32_t* draft_tokens,
+                    const float* draft_probs, const float* uniforms, const duo_call* call, duo_result* out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    if (vocab < 2) return DUO_ERR_SHAPE;
+    int rc = check_call(call, vocab);
+    if (rc) return rc;
+    if ((rc = check_result(out))) return rc;
+    const int R = call->root_token >= 0 ? 1 : 0;
+    if (!logits || !draft_tokens || !draft_probs || !uniforms || !workspace || (!R && !root_logits)) return DUO_ERR_NULL;
+    if (!aligned16(workspace)) return DUO_ERR_ALIGN;
+    if (workspace_bytes < sample_ws_bytes(vocab)) return DUO_ERR_WORKSPACE;
+    Workspace ws{};
+    size_t off = 0;
+    carve_sampler(static_cast<char*>(workspace), off, vocab, ws);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, out->status, 1, 0);
+    SampleArgs sa{logits, vocab, root_logits, vocab, call->n, call->k, R, call->host_prefix_len, (double)call->temperature,
+                  draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
+                  out->commit, out->status};
+    enqueue_sampling(sa, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
+    return hip_ok(hipGetLastError(), "duo_spec_sample launch");
+}
+
+int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, int N, int K, void* hip_stream) {
+    if (!x || !w || !y) return DUO_ERR_NULL;
+    if (rows < 1 || rows > DUO_MAX_ROWS || N < 1 || K < 32 || K % 32) return DUO_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    EpiStoreF32 e{w, K, N, rows, 2, y, N};
+    launch_gemm_rows<2>(rows, false, x, K, K, (N + 31) / 32, e, s);
+    return hip_ok(hipGetLastError(), "duo_skinny_gemm launch");
+}
+
+const char* duo_status_string(int code) {
+    switch (code) {
+        case DUO_OK: return "ok";
+        case DUO_ERR_NULL: return "required pointer is NULL";
+        case DUO_ERR_SHAPE: return "unsupported shape";
+        case DUO_ERR_CAPACITY: return "KV cache capacity exceeded";
+        case DUO_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case DUO_ERR_WORKSPACE: return "workspace too small";
+        case DUO_ERR_TOKEN_RANGE: return "token id out of range";
+        case DUO_ERR_HIP: return "HIP error";
+        case DUO_ERR_ARG: return "invalid argument";
+        default: return "unknown status";
+    }
+}
+
+const char* duo_last_hip_error(void) { return g_hip_err; }
+
+}  // extern "C"

@@ -1,0 +1,70 @@
+// Shared device-side types and helpers (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define DUO_WAVE 64
+
+// bf16 <-> fp32 (round to nearest even); inputs here are finite.
+__device__ __forceinline__ float bf16_to_f32(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ u16 f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (u16)(u >> 16);
+}
+
+union Frag8 {  // eight bf16 values = one 16-byte load = one MFMA operand
+    bf16x8 v;
+    u32x4 q;
+    u16 h[8];
+};
+
+__device__ __forceinline__ bf16x8 load_frag(const u16* p) {
+    Frag8 f;
+    f.q = *reinterpret_cast<const u32x4*>(p);
+    return f.v;
+}
+// weights and prefix KV are read once per step: mark the loads non-temporal so they do not
+// displace the activations that every workgroup re-reads from L2
+__device__ __forceinline__ bf16x8 load_frag_stream(const u16* p) {
+    Frag8 f;
+    f.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return f.v;
+}
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    // D[16x16] += A[16x32] * B[32x16]; lane l supplies A[l%16][8*(l/16) .. +8] and
+    // B[8*(l/16) .. +8][l%16]; it receives D[4*(l/16) .. +4][l%16].
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Row bookkeeping of one pass: row m -> (sequence, index in sequence, position, slot).
+struct RowPlan {
+    int P;       // prefix length
+    int R;       // 1 if row 0 is the shared root token
+    int n, k;    // n sequences of k tokens
+    int M;       // R + n*k
+    __device__ __forceinline__ int pos(int m) const { return m < R ? P : P + R + (m - R) % k; }
+    __device__ __forceinline__ int slot(int m) const { return P + m; }
+};

@@ -1,0 +1,292 @@
+// Speculative sampling over the target logits (Alg. 2, Sec. 3.3) and the KV commit.
+//
+// All probabilities are evaluated in double from the fp32 logits, so that the accept decision
+// u * q(t) < p(t) and the inverse-CDF draws are taken in the precision a plain reference uses;
+// the volumes are tiny next to the weight stream (two passes over a few vocabulary rows).
+//   sample_stats_kernel   one workgroup per judging distribution (i, j): max and normaliser of
+//                         softmax(logits / T), and the accept flag of draft token (i, j)
+//   sample_finish_kernel  one workgroup per sequence: leading accepts, then the correction
+//                         token from norm(max(0, p - q)) or the bonus token from p
+//   sample_paper_kernel   the sequential first-token rule over the n sequences, with the
+//                         running distribution replaced by its residual after each rejection
+//   commit_kernel         picks the sequence to keep, moves its accepted K/V next to the prefix
+#pragma once
+#include "duo_common.h"
+
+struct SampleArgs {
+    const float* logits;  // fp32 [R + n*k][ld]
+    int ld;
+    const float* root_logits;  // fp32 [V], judges first tokens when R == 0
+    int V, n, k, R, P;
+    double T;
+    const int32_t* tokens;  // [n][k]
+    const float* q;         // [n][k][V]
+    const float* u;         // [n][k+1]
+    double* stats;          // [n][k+1][2]: max of z = logit / T, sum exp(z - max)
+    int32_t* acc;           // [n][k] accept flags
+    double* p_run;          // [V] running distribution of the sequential rule
+    int32_t* accept_len;    // [n]
+    int32_t* next_token;    // [n]
+    int32_t* commit;        // [4]
+    int32_t* status;
+    __device__ __forceinline__ const float* judge_row(int i, int j) const {
+        if (j == 0) return R ? logits : root_logits;
+        return logits + (size_t)(R + i * k + j - 1) * ld;
+    }
+    __device__ __forceinline__ int token(int i, int j) const {
+        int t = tokens[i * k + j];
+        return t < 0 ? 0 : (t >= V ? V - 1 : t);
+    }
+};
+
+constexpr int SAMPLE_THREADS = 1024;
+
+__device__ __forceinline__ double block_sum_d(double v, double* sm) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    __syncthreads();
+    if (lane == 0) sm[wave] = v;
+    __syncthreads();
+    double t = 0.0;
+    for (int w = 0; w < nw; ++w) t += sm[w];
+    return t;
+}
+__device__ __forceinline__ double block_max_d(double v, double* sm) {
+    v = wave_max(v);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    __syncthreads();
+    if (lane == 0) sm[wave] = v;
+    __syncthreads();
+    double t = sm[0];
+    for (int w = 1; w < nw; ++w) t = fmax(t, sm[w]);
+    return t;
+}
+
+__global__ __launch_bounds__(256) void sample_stats_kernel(SampleArgs a) {
+    __shared__ double sm[16];
+    const int j = blockIdx.x, i = blockIdx.y;
+    const float* row = a.judge_row(i, j);
+    float lm = -INFINITY;
+    for (int v = threadIdx.x; v < a.V; v += 256) lm = fmaxf(lm, row[v]);
+    const double zmax = block_max_d((double)lm, sm) / a.T;
+    double s = 0.0;
+    for (int v = threadIdx.x; v < a.V; v += 256) s += exp((double)row[v] / a.T - zmax);
+    const double Z = block_sum_d(s, sm);
+    if (threadIdx.x == 0) {
+        double* st = a.stats + ((size_t)i * (a.k + 1) + j) * 2;
+        st[0] = zmax;
+        st[1] = Z;
+        if (j < a.k) {
+            const int raw = a.tokens[i * a.k + j];
+            if ((raw < 0 || raw >= a.V) && a.status) atomicOr(a.status, 1);
+            const int t = a.token(i, j);
+            const double p_t = exp((double)row[t] / a.T - zmax) / Z;
+            const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
+            a.acc[i * a.k + j] = lhs < p_t ? 1 : 0;
+        }
+    }
+}
+
+// Inverse CDF over non-negative weights w(v), v ascending: smallest v whose running sum exceeds
+// u * total.  Each thread owns a contiguous segment; segment sums are scanned in thread order.
+// Returns (to every thread) the token, or -1 if the total is zero.
+template <class F>
+__device__ int block_inverse_cdf(F w, int V, double u, double* sm_d, int* sm_i) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int seg = (V + nt - 1) / nt;
+    const int v0 = tid * seg, v1 = min(V, v0 + seg);
+    double local = 0.0;
+    int lastpos = -1;
+    for (int v = v0; v < v1; ++v) {
+        const double x = w(v);
+        local += x;
+        if (x > 0.0) lastpos = v;
+    }
+    // exclusive scan of the segment sums: within a wave by shuffles, across waves serially
+    const int wave = tid >> 6, lane = tid & 63, nw = nt >> 6;
+    double incl = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double y = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += y;
+    }
+    __syncthreads();
+    if (lane == 63) sm_d[wave] = incl;
+    __syncthreads();
+    double base = 0.0, total = 0.0;
+    for (int ww = 0; ww < nw; ++ww) {
+        if (ww == wave) base = total;
+        total += sm_d[ww];
+    }
+    if (!(total > 0.0)) return -1;
+    const double excl = base + (incl - local);
+    const double target = u * total;
+    const bool mine = excl + local > target;
+    // first thread whose inclusive sum exceeds the target / last positive weight overall
+    __syncthreads();
+    if (tid == 0) {
+        sm_i[0] = 0x7FFFFFFF;
+        sm_i[1] = -1;
+    }
+    __syncthreads();
+    if (mine) atomicMin(&sm_i[0], tid);
+    atomicMax(&sm_i[1], lastpos);
+    __syncthreads();
+    const int first = sm_i[0];
+    if (first == 0x7FFFFFFF) return sm_i[1];  // rounding left no crossing: largest positive id
+    if (tid == first) {
+        double s = 0.0;
+        int tok = lastpos;
+        for (int v = v0; v < v1; ++v) {
+            s += w(v);
+            if (excl + s > target) {
+                tok = v;
+                break;
+            }
+        }
+        sm_i[2] = tok;
+    }
+    __syncthreads();
+    return sm_i[2];
+}
+
+// Correction / bonus token of sequence i after `a` accepted drafts.
+__device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_d, int* sm_i) {
+    const float* row = a.judge_row(i, acc_len);
+    const double* st = a.stats + ((size_t)i * (a.k + 1) + acc_len) * 2;
+    const double zmax = st[0], Z = st[1], T = a.T;
+    const double u = (double)a.u[i * (a.k + 1) + a.k];
+    auto pw = [=](int v) { return exp((double)row[v] / T - zmax) / Z; };
+    if (acc_len < a.k) {
+        const float* qrow = a.q + ((size_t)i * a.k + acc_len) * a.V;
+        auto rw = [=](int v) { return fmax(exp((double)row[v] / T - zmax) / Z - (double)qrow[v], 0.0); };
+        const int tok = block_inverse_cdf(rw, a.V, u, sm_d, sm_i);
+        if (tok >= 0) return tok;  // else: the residual vanished (p == q), fall back to p
+    }
+    return block_inverse_cdf(pw, a.V, u, sm_d, sm_i);
+}
+
+__device__ __forceinline__ int leading_accepts(const SampleArgs& a, int i, int from) {
+    int n = from;
+    while (n < a.k && a.acc[i * a.k + n]) ++n;
+    return n;
+}
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArgs a) {
+    __shared__ double sm_d[16];
+    __shared__ int sm_i[4];
+    const int i = blockIdx.x;
+    const int acc_len = leading_accepts(a, i, 0);
+    const int tok = finish_token(a, i, acc_len, sm_d, sm_i);
+    if (threadIdx.x == 0) {
+        a.accept_len[i] = acc_len;
+        a.next_token[i] = tok;
+    }
+}
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs a) {
+    __shared__ double sm_d[16];
+    __shared__ int sm_i[4];
+    const int tid = threadIdx.x;
+    {
+        const float* row = a.judge_row(0, 0);
+        const double zmax = a.stats[0], Z = a.stats[1];
+        for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
+    }
+    __syncthreads();
+    int sel = -1;
+    for (int i = 0; i < a.n; ++i) {
+        const int t = a.token(i, 0);
+        const float* qrow = a.q + (size_t)i * a.k * a.V;
+        const double lhs = (double)a.u[i * (a.k + 1)] * (double)qrow[t];
+        if (lhs < a.p_run[t]) {  // same value in every thread
+            sel = i;
+            break;
+        }
+        double s = 0.0;
+        for (int v = tid; v < a.V; v += SAMPLE_THREADS) s += fmax(a.p_run[v] - (double)qrow[v], 0.0);
+        const double Rm = block_sum_d(s, sm_d);
+        if (Rm > 0.0)
+            for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = fmax(a.p_run[v] - (double)qrow[v], 0.0) / Rm;
+        __syncthreads();
+    }
+    int acc_len = 0, tok;
+    if (sel < 0) {
+        const double* pr = a.p_run;
+        auto pw = [=](int v) { return pr[v]; };
+        tok = block_inverse_cdf(pw, a.V, (double)a.u[(a.n - 1) * (a.k + 1) + a.k], sm_d, sm_i);
+    } else {
+        acc_len = leading_accepts(a, sel, 1);
+        tok = finish_token(a, sel, acc_len, sm_d, sm_i);
+    }
+    for (int i = tid; i < a.n; i += SAMPLE_THREADS) {
+        a.accept_len[i] = sel < 0 ? 0 : (i < sel ? 0 : (i == sel ? acc_len : -1));
+        a.next_token[i] = i == sel ? tok : -1;
+    }
+    if (tid == 0) {
+        a.commit[0] = sel;
+        a.commit[1] = acc_len;
+        a.commit[2] = tok;
+        a.commit[3] = a.P + a.R + acc_len;
+    }
+}
+
+struct CommitArgs {
+    u16* kc;  // [L][Hkv][max_seq][D]
+    u16* vc;  // [L][Hkv][D][max_seq]
+    int Hkv, D, max_seq;
+    int P, R, n, k, mode;
+    const int32_t* accept_len;
+    const int32_t* next_token;
+    int32_t* commit;
+    int32_t* prefix_len;  // may be NULL (sampling only)
+};
+
+// grid (Hkv, L) for the copy; (1, 1) when there is no cache.  In longest mode every workgroup
+// recomputes the (cheap) selection; workgroup (0, 0) publishes it.
+__global__ __launch_bounds__(256) void commit_kernel(CommitArgs a) {
+    int sel, len, tok;
+    if (a.mode == 0) {
+        sel = 0;
+        len = a.accept_len[0];
+        for (int i = 1; i < a.n; ++i)
+            if (a.accept_len[i] > len) {
+                len = a.accept_len[i];
+                sel = i;
+            }
+        tok = a.next_token[sel];
+    } else {
+        sel = a.commit[0];
+        len = a.commit[1];
+        tok = a.commit[2];
+    }
+    const int newP = a.P + a.R + len;
+    if (a.kc && sel > 0 && len > 0) {
+        const int hk = blockIdx.x, l = blockIdx.y;
+        const int src = a.P + a.R + sel * a.k, dst = a.P + a.R;
+        u16* kp = a.kc + ((size_t)l * a.Hkv + hk) * a.max_seq * a.D;
+        for (int e = threadIdx.x; e < len * a.D; e += 256) kp[(size_t)dst * a.D + e] = kp[(size_t)src * a.D + e];
+        u16* vp = a.vc + ((size_t)l * a.Hkv + hk) * a.D * a.max_seq;
+        for (int e = threadIdx.x; e < len * a.D; e += 256) {
+            const int d = e / len, j = e - d * len;
+            vp[(size_t)d * a.max_seq + dst + j] = vp[(size_t)d * a.max_seq + src + j];
+        }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        if (a.mode == 0) {
+            a.commit[0] = sel;
+            a.commit[1] = len;
+            a.commit[2] = tok;
+            a.commit[3] = newP;
+        }
+        if (a.prefix_len) *a.prefix_len = newP;
+    }
+}
+
+// Prefill bookkeeping: all m rows join the prefix, the last row's logits become the root logits.
+__global__ void prefill_finish_kernel(const float* __restrict__ last_logits, float* __restrict__ root_logits, int V,
+                                      int32_t* prefix_len, int newP) {
+    const int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < V) root_logits[v] = last_logits[v];
+    if (v == 0) *prefix_len = newP;
+}

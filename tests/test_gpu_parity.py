@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from oracle import duo_oracle as O
+from paper_2503_00784_amd import inputs
+from tests.gpu_util import (ACCEPT_TIE, compare_end_to_end, logits_close, say, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2503_00784_amd import binding
+    binding.load()
+    return binding
+
+
+# ------------------------------------------------------------------ skinny GEMM
+@pytest.mark.parametrize("rows,N,K", [(1, 64, 64), (8, 4096, 4096), (16, 1000, 512), (33, 4099, 1408), (64, 11008, 4096),
+                                      (65, 4096, 11008), (80, 515, 96), (7, 17, 32)])
+def test_skinny_gemm_matches_oracle_matmul(B, rows, N, K):
+    import torch
+    say(f"gemm rows={rows} N={N} K={K}")
+    g = np.random.default_rng(rows * 1000 + N)
+    x = inputs.f32_to_bf16_bits(g.normal(0, 1, (rows, K)).astype(np.float32))
+    w = inputs.f32_to_bf16_bits(g.normal(0, 0.02, (N, K)).astype(np.float32))
+    rp = (rows + 15) // 16 * 16
+    xp = np.zeros((rp, K), dtype=np.uint16)
+    xp[:rows] = x
+    y = B.skinny_gemm(to_dev(xp.view(np.int16)), to_dev(w.view(np.int16)), rows)
+    torch.cuda.synchronize()
+    ref = O.bf16_bits_to_f64(x) @ O.bf16_bits_to_f64(w).T
+    err = np.abs(y.cpu().numpy() - ref).max()
+    say(f"  max abs err {err:.3e}")
+    # fp32 accumulation of K products of magnitude ~0.02: error far below 1e-4 * sqrt(K)
+    assert err <= 2e-6 * np.sqrt(K) * max(1.0, np.abs(ref).max())
+
+
+# ------------------------------------------------------------------ sampler on identical logits
+def _sampling_case(V, n, k, seed, has_root, peaked):
+    g = np.random.default_rng(seed)
+    R = 1 if has_root else 0
+    scale = 4.0 if peaked else 1.28
+    logits = (g.normal(0, scale, (R + n * k, V))).astype(np.float32)
+    root = (g.normal(0, scale, V)).astype(np.float32)
+    q, toks, u = inputs.make_draft(V, n, k, seed=seed, easy_rows=inputs.easy_rows_for(n, k))
+    if peaked:  # make drafts agree with the target often: draft tokens = argmax of the judging row
+        for i in range(n):
+            for j in range(k):
+                if g.random() < 0.7:
+                    jr = (logits[0] if has_root else root) if j == 0 else logits[R + i * k + j - 1]
+                    toks[i, j] = int(np.argmax(jr))
+    return logits, root, q, toks, u
+
+
+@pytest.mark.parametrize("V,n,k,has_root,peaked", [(32000, 1, 8, False, False), (32000, 4, 8, False, True),
+                                                    (32000, 8, 8, True, True), (4099, 3, 5, True, False),
+                                                    (128256, 4, 16, False, True), (50, 2, 3, False, False),
+                                                    (1031, 1, 1, False, True), (32000, 1, 16, True, True)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_sampler_bit_exact_on_identical_logits(B, V, n, k, has_root, peaked, mode):
+    total = ties = 0
+    for seed in range(3):
+        say(f"sampler V={V} n={n} k={k} root={has_root} peaked={peaked} mode={mode} seed={seed}")
+        logits, root, q, toks, u = _sampling_case(V, n, k, seed, has_root, peaked)
+        ref = O.speculative_verify(logits, root, toks, q, u, prefix_len=100, temperature=0.9 if seed == 2 else 1.0,
+                                   select_mode=mode, has_root=has_root)
+        got = B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u),
+                            temperature=0.9 if seed == 2 else 1.0, select_mode=mode, has_root=has_root, prefix_len=100)
+        assert got["status"] == 0
+        total += 1
+        if ref.commit_margin <= 1e-9 or (mode == 0 and min(ref.accept_margins.min(), ref.draw_margins.min()) <= 1e-9):
+            ties += 1
+            continue
+        np.testing.assert_array_equal(got["accept_len"], ref.accept_len)
+        np.testing.assert_array_equal(got["next_token"], ref.next_token)
+        assert (got["selected"], got["commit_len"], got["commit_token"], got["new_prefix_len"]) == \
+               (ref.selected, ref.commit_len, ref.commit_token, ref.new_prefix_len)
+    assert ties < total
+
+
+def test_sampler_flags_out_of_range_token(B):
+    logits, root, q, toks, u = _sampling_case(50, 1, 2, 0, False, False)
+    toks[0, 1] = 50
+    got = B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u))
+    assert got["status"] & B.STATUS_TOKEN_CLAMPED
+
+
+# ------------------------------------------------------------------ the whole step
+def _engine_and_oracle(B, shape, P, max_seq, seed, synthetic_cache):
+    w = inputs.make_weights(shape, seed=seed, threads=16)
+    oshape = O.shape_from(shape)
+    eng = B.VerifyEngine(shape, w, max_seq)
+    if synthetic_cache:
+        kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=seed)
+        eng.load_cache(kb, vb, P, root)
+        cache = O.OracleCache.from_bits(oshape, kb, vb, P, root)
+        del kb, vb
+    else:
+        prefix = inputs.make_prefix_ids(shape, P, seed=seed)
+        eng.prefill(prefix.tolist())
+        cache = O.prefill(oshape, w, prefix.tolist(), max_seq)
+    return w, oshape, eng, cache
+
+
+def _check_step(B, shape, w, oshape, eng, cache, n, k, seed, mode, root_token, temperature=1.0):
+    import torch
+    V = shape.vocab
+    q, toks, u = inputs.make_draft(V, n, k, seed=seed, easy_rows=inputs.easy_rows_for(n, k))
+    R = 1 if root_token >= 0 else 0
+    P = cache.prefix_len
+    logits_dev = torch.empty((R + n * k, V), dtype=torch.float32, device="cuda")
+    eng.verify(to_dev(toks), to_dev(q), to_dev(u), temperature=temperature, select_mode=mode, root_token=root_token,
+               logits_out=logits_dev)
+    got = eng.results(n)
+    assert got["status"] == 0
+    gl = logits_dev.cpu().numpy()
+    res, ol = O.oracle_verify(oshape, w, cache, toks, q, u, temperature=temperature, select_mode=mode,
+                              root_token=root_token)
+    ok, max_abs, worst = logits_close(gl, ol)
+    say(f"  logits max abs err {max_abs:.3e} (worst err/bound {worst:.3f}); gpu accept {got['accept_len']} "
+        f"oracle {res.accept_len} accept margins {np.round(res.accept_margins, 4)}")
+    assert ok, (max_abs, worst)
+    compared = compare_end_to_end(got, res, n) if mode == 0 else 0
+    # the fused call's sampler sees the same logits it returned: same decisions as the stand-alone sampler entry point
+    again = B.spec_sample(logits_dev, eng.root_logits, to_dev(toks), to_dev(q), to_dev(u), temperature=temperature,
+                          select_mode=mode, has_root=bool(R), prefix_len=P)
+    for key in ("selected", "commit_len", "commit_token", "new_prefix_len"):
+        assert again[key] == got[key], key
+    np.testing.assert_array_equal(again["accept_len"], got["accept_len"])
+    assert got["new_prefix_len"] == P + R + got["commit_len"] == got["device_prefix_len"]
+    return got, res, compared
+
+
+def _check_cache(eng, cache, upto, atol=0.07):
+    """GPU cache slots [0, upto) against the oracle's (bf16 values, a rounding flip is one ulp)."""
+    kg, vg = eng.cache_to_host()
+    kd = np.abs(O.bf16_bits_to_f64(kg[:, :, :upto]) - cache.k[:, :, :upto])
+    vd = np.abs(O.bf16_bits_to_f64(vg[:, :, :upto]) - cache.v[:, :, :upto])
+    say(f"  cache max abs diff k {kd.max():.3e} v {vd.max():.3e}")
+    assert kd.max() <= atol and vd.max() <= atol
+
+
+def test_tiny_config_prefill_and_verify_chain(B):
+    """68M-class shape: GPU prefill vs oracle prefill, then three chained verify steps with commits."""
+    wl = inputs.WORKLOADS["C0"]
+    shape, P = wl.shape, wl.prefix_len
+    say("C0 prefill")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, 256, seed=0, synthetic_cache=False)
+    ok, max_abs, worst = logits_close(eng.root_logits.cpu().numpy(), cache.root_logits)
+    say(f"  root logits max abs err {max_abs:.3e}")
+    assert ok
+    _check_cache(eng, cache, P)
+    root = -1
+    for step, (n, k, mode) in enumerate([(1, 8, 0), (3, 5, 1), (4, 8, 0)]):
+        say(f"C0 step {step}: n={n} k={k} mode={mode} root={root} P={cache.prefix_len}")
+        got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=10 + step, mode=mode, root_token=root)
+        same = (got["selected"], got["commit_len"]) == (res.selected, res.commit_len)
+        if not same:  # a declared tie moved the commit: put both sides on the oracle's state
+            say("  commit differs (declared tie); stopping the chain")
+            break
+        _check_cache(eng, cache, cache.prefix_len)
+        root = res.commit_token
+
+
+@pytest.mark.parametrize("n,k,mode,root", [(3, 5, 1, 17), (1, 16, 0, -1), (4, 16, 0, 3), (8, 8, 1, -1), (2, 1, 0, 5)])
+def test_mid_config_gqa_ragged(B, n, k, mode, root):
+    """3 layers, 8 query / 2 KV heads of 64, vocab 4099 (not a multiple of 16), prefix 77."""
+    shape = inputs.MID
+    say(f"MID n={n} k={k} mode={mode} root={root}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False)
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 31 + k, mode=mode, root_token=root)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len)
+
+
+def test_verify_is_repeatable_and_flags_prefix_mismatch(B):
+    import torch
+    shape = inputs.MID
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 40, 128, seed=5, synthetic_cache=True)
+    q, toks, u = inputs.make_draft(shape.vocab, 2, 4, seed=1)
+    outs = []
+    for rep in range(2):
+        eng.set_prefix_len(40)
+        lg = torch.empty((8, shape.vocab), dtype=torch.float32, device="cuda")
+        eng.verify(to_dev(toks), to_dev(q), to_dev(u), logits_out=lg)
+        r = eng.results(2)
+        outs.append((lg.cpu().numpy(), r))
+    np.testing.assert_array_equal(outs[0][0], outs[1][0])  # bit-identical: no atomics in any reduction
+    assert outs[0][1]["commit_token"] == outs[1][1]["commit_token"]
+    eng.host_prefix_len = 41  # host and device now disagree
+    eng.verify(to_dev(toks), to_dev(q), to_dev(u))
+    assert eng.results(2)["status"] & B.STATUS_PREFIX_MISMATCH
+
+
+@pytest.mark.parametrize("name", ["C1", "C3"])
+def test_full_size_7b_shape(B, name):
+    """Llama-2-7B geometry at the benchmark's launch configuration, synthetic prefix cache."""
+    wl = inputs.WORKLOADS[name]
+    shape, P, n, k = wl.shape, wl.prefix_len, wl.n_seq, wl.k_draft
+    say(f"{name}: generating weights")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, P + 128, seed=0, synthetic_cache=True)
+    say(f"{name}: verify n={n} k={k} P={P}")
+    got, res, compared = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=1, mode=0, root_token=-1)
+    say(f"  accept lengths compared away from ties: {compared}/{n}")
