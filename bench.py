@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify step on one MI355X.
+
+A step = one duo_verify call (target pass over n*k draft tokens + speculative sampling + KV
+commit) on seeded synthetic inputs already resident in HBM.  The default workload is the
+Llama-2-7B-shaped configuration the metric is quoted on (prefix 512, 1 sequence x 8 tokens).
+Prints ONE JSON line: verified tokens/s, ms per step, the roofline entry of the dominant kernel
+(measured live with HIP events on the launch stream) and the CPU oracle timed beside it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C1", help="C0..C4 (default C1, the configuration the metric is quoted on)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a captured HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the verify step of one model replica); "
+              f"--gpus {args.gpus} is not supported. See DESIGN.md for how the path would shard.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2503_00784_amd import binding as B
+    from paper_2503_00784_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2503_00784_amd import build
+        build.build(verbose=False)
+    B.load()
+
+    wl = inputs.WORKLOADS[args.workload]
+    shape, P, n, k = wl.shape, wl.prefix_len, wl.n_seq, wl.k_draft
+    max_seq = (P + n * k + 1 + 31) // 32 * 32 + 32
+    t0 = time.time()
+    log(f"[bench] workload {wl.name}: generating weights ({shape.weight_bytes() / 1e9:.2f} GB) ...")
+    w = inputs.make_weights(shape, seed=args.seed, threads=16)
+    kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=args.seed)
+    q, toks, u = inputs.make_draft(shape.vocab, n, k, seed=args.seed + 1, easy_rows=inputs.easy_rows_for(n, k))
+    eng = B.VerifyEngine(shape, w, max_seq)
+    eng.load_cache(kb, vb, P, root)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    d_toks, d_q, d_u = dev(toks), dev(q), dev(u)
+    logits = torch.empty((n * k, shape.vocab), dtype=torch.float32, device="cuda")
+    log(f"[bench] inputs resident after {time.time() - t0:.1f}s")
+
+    def step():
+        # restore the cache state (the previous step's commit advanced the prefix length), then verify
+        eng.set_prefix_len(P)
+        eng.verify(d_toks, d_q, d_u, logits_out=logits)
+
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = None
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            step()
+        stream.synchronize()
+        if not args.no_graph:
+            try:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=stream):
+                    step()
+            except Exception as e:  # capture is an optimisation; fall back to eager launches
+                log(f"[bench] graph capture failed ({e}); launching eagerly")
+                graph = None
+        run = (lambda: graph.replay()) if graph is not None else step
+        for _ in range(args.warmup):
+            run()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        ms_per_step = (t2 - t1) * 1e3 / args.steps
+        res = eng.results(n)
+        assert res["status"] == 0, res
+
+        # per-kernel timing pass (eager launches with HIP events between kernels on the same stream)
+        B.profile_enable(True)
+        prof_steps = min(args.steps, 20)
+        for _ in range(prof_steps):
+            step()
+        prof = B.profile_read()
+        B.profile_enable(False)
+        stream.synchronize()
+
+    algo_bytes = wl.algorithmic_bytes()
+    tok_s = n * k / (ms_per_step * 1e-3)
+    achieved = algo_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # roofline of the dominant kernel: the gate/up projection (2*F*d bf16 weights per launch)
+    kernels = {}
+    for name, v in prof.items():
+        if v["launches"]:
+            kernels[name] = {"avg_us": round(v["ms"] * 1e3 / v["launches"], 2), "launches_per_step": v["launches"] // prof_steps,
+                             "ms_per_step": round(v["ms"] / prof_steps, 4)}
+    per_launch = {"qkv_rope": 2 * (shape.q_dim + 2 * shape.kv_dim) * shape.d_model, "o_proj": 2 * shape.d_model * shape.q_dim,
+                  "gate_up_swiglu": 2 * 2 * shape.d_ff * shape.d_model, "down_proj": 2 * shape.d_model * shape.d_ff,
+                  "lm_head": 2 * shape.vocab * shape.d_model,
+                  "attn": 2 * 2 * shape.kv_dim * P}
+    for name, b in per_launch.items():
+        if name in kernels:
+            kernels[name]["algo_GBps"] = round(b / (kernels[name]["avg_us"] * 1e-6) / 1e9, 1)
+    dom = max((nm for nm in per_launch if nm in kernels), key=lambda nm: kernels[nm]["ms_per_step"])
+    dom_bytes = per_launch[dom]
+    dom_gbps = dom_bytes / (kernels[dom]["avg_us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algo_bytes_per_launch": dom_bytes, "avg_launch_us": kernels[dom]["avg_us"]}
+
+    out = {"metric": "verified_tokens_per_s", "value": round(tok_s, 1), "unit": "tok/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": wl.name, "prefix_len": P, "n_seq": n, "k_draft": k, "rows": n * k,
+                      "launch": "hip_graph_replay" if graph is not None else "eager"},
+           "verify_latency_ms": round(ms_per_step, 4), "algorithmic_bytes": algo_bytes,
+           "achieved_hbm_GBps": round(achieved, 1), "frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
+           "roofline": roofline, "kernels": kernels}
+
+    if not args.no_cpu_baseline:
+        from oracle import duo_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        log("[bench] timing the CPU oracle on the same workload ...")
+        oshape = O.shape_from(shape)
+        cache = O.OracleCache.from_bits(oshape, kb, vb, P, root)
+        t3 = time.perf_counter()
+        ores, ol = O.oracle_verify(oshape, w, cache, toks, q, u)
+        t4 = time.perf_counter()
+        gl = logits.cpu().numpy()
+        err = float(np.abs(gl - ol).max())
+        out["cpu_baseline"] = {"value": round(n * k / (t4 - t3), 3), "unit": "tok/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"one full step of {wl.name} (numpy float64, BLAS threads = cores)",
+                               "seconds": round(t4 - t3, 2)}
+        out["parity"] = {"logits_max_abs_err": err,
+                         "accept_len_equal": bool((res["accept_len"] == ores.accept_len).all()),
+                         "accept_len": [int(a) for a in res["accept_len"]]}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -16,8 +16,8 @@
  *   - All work is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = default
  *     stream) without host synchronisation.  Arguments are validated on the host before
  *     anything is enqueued; a negative return code means nothing was enqueued.
- *   - bf16 values are passed as uint16_t bit patterns.  Matrices are row-major [out][in]
- *     (y = x W^T), 16-byte aligned, with `in` a multiple of 32.
+ *   - bf16 values are passed as uint16_t bit patterns.  Matrices compute y = x W^T, are 16-byte
+ *     aligned, and have an input dimension that is a multiple of 32.
  *   - A call with the same inputs and the same `host_prefix_len` is repeatable: cache slots
  *     below the prefix length are only read, slots at and above it are scratch.
  */
@@ -54,25 +54,50 @@ extern "C" {
 
 /* Geometry of the Llama-shaped target (the architecture of the paper's targets, Sec. 4.1
  * "Models").  head_dim is 64 or 128; d_model, n_q_heads*head_dim and d_ff are multiples of
- * 32; n_q_heads is a multiple of n_kv_heads; max_seq is a multiple of 8. */
+ * 32; n_q_heads is a multiple of n_kv_heads; max_seq is a multiple of 32. */
 typedef struct duo_model_config {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, max_seq;
     float   rope_theta; /* rotary base; pair (d, d + head_dim/2) turns by pos * theta^(-2d/head_dim) */
     float   rms_eps;
 } duo_model_config;
 
-/* Parameters, bf16.  The nine per-layer tables are HOST arrays of n_layers DEVICE pointers. */
+/*
+ * Parameters, bf16.  Every matrix the step streams is held in the library's STREAMING LAYOUT, made
+ * once at load time by the duo_pack_* calls below from ordinary row-major [out][in] matrices: bands
+ * of 16 output rows, cut into 16 x 32 tiles of 1 KiB that are contiguous and ordered the way one MFMA
+ * operand sits in a wavefront's registers, so that a wave reads its band as one linear stream.  The
+ * embedding table is gathered, not streamed, and stays row-major.  The seven per-layer tables are
+ * HOST arrays of n_layers DEVICE pointers.
+ */
 typedef struct duo_weights {
-    const uint16_t *embed;                    /* [vocab][d_model] */
-    const uint16_t *const *wq;                /* [n_q_heads*head_dim][d_model] */
-    const uint16_t *const *wk, *const *wv;    /* [n_kv_heads*head_dim][d_model] */
-    const uint16_t *const *wo;                /* [d_model][n_q_heads*head_dim] */
-    const uint16_t *const *w_gate, *const *w_up; /* [d_ff][d_model] */
-    const uint16_t *const *w_down;            /* [d_model][d_ff] */
+    const uint16_t *embed;                    /* row-major [vocab][d_model] */
+    const uint16_t *const *wqkv;              /* duo_pack_qkv of wq [n_q_heads*head_dim][d_model] and
+                                                 wk, wv [n_kv_heads*head_dim][d_model] */
+    const uint16_t *const *wo;                /* duo_pack_matrix of [d_model][n_q_heads*head_dim] */
+    const uint16_t *const *w_gate_up;         /* duo_pack_gate_up of w_gate, w_up [d_ff][d_model] */
+    const uint16_t *const *w_down;            /* duo_pack_matrix of [d_model][d_ff] */
     const uint16_t *const *g_attn, *const *g_ffn; /* RMSNorm gains [d_model] */
     const uint16_t *g_final;                  /* [d_model] */
-    const uint16_t *lm_head;                  /* [vocab][d_model] */
+    const uint16_t *lm_head;                  /* duo_pack_matrix of [vocab][d_model] */
 } duo_weights;
+
+/*
+ * Repacking into the streaming layout (device to device, enqueued on the stream, done once per
+ * model).  src matrices are row-major bf16, 16-byte aligned, K a multiple of 32.  dst needs
+ * duo_packed_elems(N, K) uint16 elements: N is rounded up to a multiple of 32 rows, missing rows are
+ * zero.  duo_pack_qkv needs duo_packed_elems((n_q_heads + 2*n_kv_heads)*head_dim, d_model) and orders
+ * the bands so that the two halves of every rotary pair land in the same workgroup;
+ * duo_pack_gate_up needs duo_packed_elems(2*d_ff, d_model) and interleaves gate and up bands.
+ */
+size_t duo_packed_elems(int N, int K);
+int duo_pack_matrix(const uint16_t *src, int N, int K, uint16_t *dst, void *hip_stream);
+int duo_pack_qkv(const duo_model_config *cfg, const uint16_t *wq, const uint16_t *wk, const uint16_t *wv,
+                 uint16_t *dst, void *hip_stream);
+int duo_pack_gate_up(const duo_model_config *cfg, const uint16_t *w_gate, const uint16_t *w_up, uint16_t *dst,
+                     void *hip_stream);
+/* Activation rows [rows][K] (row-major) -> operand layout for duo_skinny_gemm; dst needs
+ * ((rows + 15) / 16) * 16 * K elements. */
+int duo_pack_activations(const uint16_t *src, int rows, int K, uint16_t *dst, void *hip_stream);
 
 /* KV cache, bf16, caller-owned.  Keys are stored after the rotary embedding as
  * k[layer][kv_head][slot][head_dim]; values are stored TRANSPOSED as
@@ -164,11 +189,36 @@ int duo_spec_sample(const float *logits, const float *root_logits, int vocab,
 
 /*
  * One skinny weight-streaming product, the building block of the target pass:
- * y[m][n] = sum_k x[m][k] * w[n][k], x bf16 [rows_padded][K] (rows_padded = rows rounded up to
- * 16, all rows readable), w bf16 [N][K], y fp32 [rows][N]; rows <= DUO_MAX_ROWS, K % 32 == 0.
+ * y[m][n] = sum_k x[m][k] * w[n][k]; x from duo_pack_activations (rows <= DUO_MAX_ROWS), w from
+ * duo_pack_matrix (N x K, K % 32 == 0), y fp32 [rows][N] row-major.
  */
-int duo_skinny_gemm(const uint16_t *x, const uint16_t *w, float *y, int rows, int N, int K,
+int duo_skinny_gemm(const uint16_t *x_packed, const uint16_t *w_packed, float *y, int rows, int N, int K,
                     void *hip_stream);
+
+/*
+ * Per-kernel timing for the roofline report (the per-iteration time breakdown of Sec. 4.4
+ * "Profiling", at kernel granularity).  While enabled, duo_verify / duo_prefill_chunk record a HIP
+ * event on the call's stream before every kernel launch and after the last one;
+ * duo_profile_read waits for the recorded events, adds the elapsed time between consecutive
+ * events to the class of the kernel launched in between, returns the sums (milliseconds) and
+ * launch counts accumulated since the last read, and resets them.  Enabling allocates a pool of
+ * events; a verify call made while profiling is therefore not allocation-free or capturable.
+ * Not thread-safe.  ms and launches are HOST arrays of DUO_PROF_CLASSES entries.
+ */
+#define DUO_PROF_SETUP     0  /* rotary table, embedding gather + first RMSNorm */
+#define DUO_PROF_QKV       1  /* fused QKV projection + rotary + KV scatter */
+#define DUO_PROF_ATTN      2  /* masked attention over prefix + drafts (chunk partials) */
+#define DUO_PROF_ATTN_COMB 3  /* merge of the chunk partials */
+#define DUO_PROF_OPROJ     4  /* O projection + residual */
+#define DUO_PROF_NORM      5  /* RMSNorm */
+#define DUO_PROF_GATEUP    6  /* gate/up projection + SwiGLU */
+#define DUO_PROF_DOWN      7  /* down projection + residual */
+#define DUO_PROF_LMHEAD    8  /* LM head */
+#define DUO_PROF_SAMPLE    9  /* softmax statistics, accept tests, correction/bonus sampling */
+#define DUO_PROF_COMMIT    10 /* sequence selection + KV commit */
+#define DUO_PROF_CLASSES   11
+int duo_profile_enable(int enable);
+int duo_profile_read(double *ms, int32_t *launches);
 
 const char *duo_status_string(int code);
 const char *duo_last_hip_error(void);

@@ -22,7 +22,11 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error"]
+           "duo_spec_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
+           "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
+           "duo_pack_activations"]
+PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "rmsnorm", "gate_up_swiglu", "down_proj", "lm_head",
+                "sample", "commit"]
 
 _u16p = C.POINTER(C.c_uint16)
 _u16pp = C.POINTER(_u16p)
@@ -35,7 +39,7 @@ class ModelConfig(C.Structure):
 
 class Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in
-                                          ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")] + \
+                                          ("wqkv", "wo", "w_gate_up", "w_down", "g_attn", "g_ffn")] + \
                [("g_final", C.c_void_p), ("lm_head", C.c_void_p)]
 
 
@@ -80,9 +84,20 @@ def load() -> C.CDLL:
     lib.duo_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Call),
                                     C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+    lib.duo_packed_elems.argtypes = [C.c_int, C.c_int]
+    lib.duo_packed_elems.restype = C.c_size_t
+    lib.duo_pack_matrix.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.duo_pack_qkv.argtypes = [C.POINTER(ModelConfig), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.duo_pack_gate_up.argtypes = [C.POINTER(ModelConfig), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.duo_pack_activations.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     for name in ("duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-                 "duo_spec_sample", "duo_skinny_gemm"):
+                 "duo_spec_sample", "duo_skinny_gemm", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
+                 "duo_pack_activations"):
         getattr(lib, name).restype = C.c_int
+    lib.duo_profile_enable.argtypes = [C.c_int]
+    lib.duo_profile_enable.restype = C.c_int
+    lib.duo_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.duo_profile_read.restype = C.c_int
     lib.duo_status_string.argtypes = [C.c_int]
     lib.duo_status_string.restype = C.c_char_p
     lib.duo_last_hip_error.argtypes = []
@@ -102,6 +117,19 @@ def _check(code: int, where: str) -> None:
         if code == -7:
             detail += ": " + lib.duo_last_hip_error().decode()
         raise DuoError(code, where, detail)
+
+
+def profile_enable(on: bool) -> None:
+    _check(load().duo_profile_enable(1 if on else 0), "duo_profile_enable")
+
+
+def profile_read() -> Dict[str, Dict[str, float]]:
+    """{class: {"ms": total milliseconds, "launches": count}} since the last read."""
+    n = len(PROF_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int32 * n)()
+    _check(load().duo_profile_read(ms, cnt), "duo_profile_read")
+    return {PROF_CLASSES[i]: {"ms": ms[i], "launches": cnt[i]} for i in range(n)}
 
 
 def make_config(shape, max_seq: int) -> ModelConfig:
@@ -124,28 +152,69 @@ def _stream_ptr():
     return torch.cuda.current_stream().cuda_stream
 
 
-_LAYER_KEYS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")
+_LAYER_KEYS = ("wqkv", "wo", "w_gate_up", "w_down", "g_attn", "g_ffn")
+
+
+def pack_matrix(w_bits):
+    """Row-major int16 [N][K] device tensor -> streaming layout (device tensor of duo_packed_elems)."""
+    import torch
+    lib = load()
+    N, K = w_bits.shape
+    out = torch.empty(lib.duo_packed_elems(N, K), dtype=torch.int16, device=w_bits.device)
+    _check(lib.duo_pack_matrix(w_bits.data_ptr(), N, K, out.data_ptr(), _stream_ptr()), "duo_pack_matrix")
+    return out
+
+
+def pack_activations(x_bits):
+    import torch
+    rows, K = x_bits.shape
+    out = torch.empty((rows + 15) // 16 * 16 * K, dtype=torch.int16, device=x_bits.device)
+    _check(load().duo_pack_activations(x_bits.data_ptr(), rows, K, out.data_ptr(), _stream_ptr()), "duo_pack_activations")
+    return out
 
 
 class DeviceWeights:
-    """bf16 parameters on the GPU (torch int16 tensors holding the bit patterns) + the C tables."""
+    """bf16 parameters on the GPU in the library's streaming layout (torch int16 tensors) + the C tables.
 
-    def __init__(self, host_weights: Dict[str, object], device: str = "cuda:0"):
+    Row-major host matrices are uploaded one layer at a time, repacked on the device by the
+    duo_pack_* entry points and dropped; only the packed copies stay resident.
+    """
+
+    def __init__(self, shape, host_weights: Dict[str, object], device: str = "cuda:0"):
         import torch
-        self.tensors: Dict[str, object] = {}
+        lib = load()
+        cfg = make_config(shape, 32)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
-        for key in ("embed", "lm_head", "g_final"):
-            self.tensors[key] = up(host_weights[key])
+        empty = lambda n: torch.empty(n, dtype=torch.int16, device=device)
+        sp = _stream_ptr()
+        self.tensors: Dict[str, object] = {"embed": up(host_weights["embed"]), "g_final": up(host_weights["g_final"]),
+                                           "lm_head": pack_matrix(up(host_weights["lm_head"]))}
         for key in _LAYER_KEYS:
-            self.tensors[key] = [up(a) for a in host_weights[key]]
-        self.n_layers = len(self.tensors["wq"])
+            self.tensors[key] = []
+        L = shape.n_layers
+        for l in range(L):
+            wq, wk, wv = (up(host_weights[k][l]) for k in ("wq", "wk", "wv"))
+            qkv = empty(lib.duo_packed_elems(shape.q_dim + 2 * shape.kv_dim, shape.d_model))
+            _check(lib.duo_pack_qkv(C.byref(cfg), wq.data_ptr(), wk.data_ptr(), wv.data_ptr(), qkv.data_ptr(), sp), "duo_pack_qkv")
+            wg, wu = up(host_weights["w_gate"][l]), up(host_weights["w_up"][l])
+            gu = empty(lib.duo_packed_elems(2 * shape.d_ff, shape.d_model))
+            _check(lib.duo_pack_gate_up(C.byref(cfg), wg.data_ptr(), wu.data_ptr(), gu.data_ptr(), sp), "duo_pack_gate_up")
+            self.tensors["wqkv"].append(qkv)
+            self.tensors["w_gate_up"].append(gu)
+            self.tensors["wo"].append(pack_matrix(up(host_weights["wo"][l])))
+            self.tensors["w_down"].append(pack_matrix(up(host_weights["w_down"][l])))
+            self.tensors["g_attn"].append(up(host_weights["g_attn"][l]))
+            self.tensors["g_ffn"].append(up(host_weights["g_ffn"][l]))
+            torch.cuda.synchronize()  # the row-major temporaries are released when this iteration ends
+            del wq, wk, wv, wg, wu
+        self.n_layers = L
         self._tables = {}
         self.c = Weights()
         self.c.embed = self.tensors["embed"].data_ptr()
         self.c.lm_head = self.tensors["lm_head"].data_ptr()
         self.c.g_final = self.tensors["g_final"].data_ptr()
         for key in _LAYER_KEYS:
-            tab = (C.c_void_p * self.n_layers)(*[t.data_ptr() for t in self.tensors[key]])
+            tab = (C.c_void_p * L)(*[t.data_ptr() for t in self.tensors[key]])
             self._tables[key] = tab
             setattr(self.c, key, C.cast(tab, C.POINTER(C.c_void_p)))
 
@@ -162,7 +231,7 @@ class VerifyEngine:
         self.device = device
         self.cfg = make_config(shape, max_seq)
         self.max_seq = max_seq
-        self.weights = weights if weights is not None else DeviceWeights(host_weights, device)
+        self.weights = weights if weights is not None else DeviceWeights(shape, host_weights, device)
         L, H, D = shape.n_layers, shape.n_kv_heads, shape.head_dim
         self.k = torch.zeros((L, H, max_seq, D), dtype=torch.int16, device=device)
         self.vT = torch.zeros((L, H, D, max_seq), dtype=torch.int16, device=device)
@@ -265,11 +334,13 @@ def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temper
             "status": int(status.cpu().numpy()[0])}
 
 
-def skinny_gemm(x_bits, w_bits, rows: int):
-    """y = x W^T through duo_skinny_gemm.  x_bits int16 [rows_padded][K], w_bits int16 [N][K] (device)."""
+def skinny_gemm(x_bits, w_bits):
+    """y = x W^T through duo_pack_activations / duo_pack_matrix / duo_skinny_gemm.
+    x_bits int16 [rows][K], w_bits int16 [N][K] (row-major bf16 bit patterns on the device)."""
     import torch
-    N, K = w_bits.shape
+    rows, K = x_bits.shape
+    N = w_bits.shape[0]
+    xp, wp = pack_activations(x_bits), pack_matrix(w_bits)
     y = torch.empty((rows, N), dtype=torch.float32, device=x_bits.device)
-    _check(load().duo_skinny_gemm(x_bits.data_ptr(), w_bits.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()),
-           "duo_skinny_gemm")
+    _check(load().duo_skinny_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_skinny_gemm")
     return y

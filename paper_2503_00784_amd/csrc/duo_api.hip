@@ -7,9 +7,12 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "duo_attn.h"
 #include "duo_common.h"
 #include "duo_gemm.h"
+#include "duo_pack.h"
 #include "duo_rowops.h"
 #include "duo_sample.h"
 
@@ -96,17 +99,35 @@ int check_config(const duo_model_config* c) {
 }
 
 int check_weights(const duo_model_config* c, const duo_weights* w) {
-    if (!w || !w->embed || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down || !w->g_attn ||
-        !w->g_ffn || !w->g_final || !w->lm_head)
+    if (!w || !w->embed || !w->wqkv || !w->wo || !w->w_gate_up || !w->w_down || !w->g_attn || !w->g_ffn || !w->g_final ||
+        !w->lm_head)
         return DUO_ERR_NULL;
     if (!aligned16(w->embed) || !aligned16(w->lm_head) || !aligned16(w->g_final)) return DUO_ERR_ALIGN;
-    const uint16_t* const* tabs[9] = {w->wq, w->wk, w->wv, w->wo, w->w_gate, w->w_up, w->w_down, w->g_attn, w->g_ffn};
+    const uint16_t* const* tabs[6] = {w->wqkv, w->wo, w->w_gate_up, w->w_down, w->g_attn, w->g_ffn};
     for (auto tab : tabs)
         for (int l = 0; l < c->n_layers; ++l) {
             if (!tab[l]) return DUO_ERR_NULL;
             if (!aligned16(tab[l])) return DUO_ERR_ALIGN;
         }
     return DUO_OK;
+}
+
+// ---- optional per-kernel timing (see duo_profile_enable in the header)
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;
+    std::vector<int> cls;  // class of the kernel launched after event i (-1: end of a call)
+    size_t used = 0;
+};
+Profiler g_prof;
+constexpr size_t PROF_POOL = 8192;
+
+// Called before a launch of class `cls`, and with cls = -1 after the last launch of a call.
+inline void prof(int cls, hipStream_t s) {
+    if (!g_prof.on || g_prof.used >= g_prof.ev.size()) return;
+    (void)hipEventRecord(g_prof.ev[g_prof.used], s);
+    g_prof.cls[g_prof.used] = cls;
+    ++g_prof.used;
 }
 
 int hip_ok(hipError_t e, const char* what) {
@@ -128,13 +149,14 @@ void launch_attention(int mtw, dim3 grid, const AttnArgs& a, hipStream_t s) {
 void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_kv_cache& cache,
                      const int32_t* tokens, int root_token, const RowPlan& plan, const Workspace& ws,
                      float* logits, int32_t* status, hipStream_t s) {
-    const int M = plan.M, Mp = (M + 15) / 16 * 16, PR = pair_rows_for(M);
+    const int M = plan.M, Mp = (M + 15) / 16 * 16, PR = pair_rows_for(M), AT = a_tiles_for(M, true);
     const int d = c.d_model, D = c.head_dim, half = D / 2, Hq = c.n_q_heads, Hkv = c.n_kv_heads;
     const int qd = Hq * D, F = c.d_ff, V = c.vocab, group = Hq / Hkv;
 
+    prof(DUO_PROF_SETUP, s);
     hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(64), 0, s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
     hipLaunchKernelGGL(embed_norm_kernel, dim3(M), dim3(256), 0, s, w.embed, tokens, root_token, plan, V,
-                       cache.prefix_len, status, ws.x, w.g_attn[0], ws.h, d, PR, c.rms_eps);
+                       cache.prefix_len, status, ws.x, w.g_attn[0], ws.h, d, PR, AT, c.rms_eps);
 
     // attention launch shape
     const int Ktot = plan.P + M;
@@ -151,40 +173,49 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * D * c.max_seq;
-        EpiQKV eq{w.wq[l], w.wk[l], w.wv[l], d, Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq,
-                  ws.rope_c, ws.rope_s, plan};
-        launch_gemm_rows<2>(M, true, ws.h, d, d, (Hq + 2 * Hkv) * (half / 16), eq, s);
+        EpiQKV eq{Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
+        prof(DUO_PROF_QKV, s);
+        launch_gemm_rows<2>(M, true, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), eq, s);
 
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
                     1.4426950408889634f / sqrtf((float)D), ws.part};
         const dim3 grid(nchunks, Hkv, MG);
+        prof(DUO_PROF_ATTN, s);
         if (D == 128) launch_attention<128>(mtw, grid, aa, s);
         else launch_attention<64>(mtw, grid, aa, s);
+        prof(DUO_PROF_ATTN_COMB, s);
         if (D == 128)
             hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), 0, s, ws.part, nchunks, mq_pad, group, M,
-                               ws.attn, qd, PR);
+                               ws.attn, AT, PR);
         else
             hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), 0, s, ws.part, nchunks, mq_pad, group, M,
-                               ws.attn, qd, PR);
+                               ws.attn, AT, PR);
 
-        EpiResidual eo{w.wo[l], qd, d, M, 1, ws.x, d};
-        launch_gemm_rows<1>(M, true, ws.attn, qd, qd, d / 16, eo, s);
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, w.g_ffn[l], ws.h, d, PR, c.rms_eps);
+        EpiResidual eo{d, M, 1, ws.x, d};
+        prof(DUO_PROF_OPROJ, s);
+        launch_gemm_rows<1>(M, true, ws.attn, w.wo[l], qd, d / 16, eo, s);
+        prof(DUO_PROF_NORM, s);
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, w.g_ffn[l], ws.h, d, PR, AT, c.rms_eps);
 
-        EpiSwiGLU eg{w.w_gate[l], w.w_up[l], d, F, M, ws.act, F, PR};
-        launch_gemm_rows<2>(M, true, ws.h, d, d, F / 16, eg, s);
+        EpiSwiGLU eg{F, M, ws.act, AT, PR};
+        prof(DUO_PROF_GATEUP, s);
+        launch_gemm_rows<2>(M, true, ws.h, w.w_gate_up[l], d, F / 16, eg, s);
 
-        EpiResidual ed{w.w_down[l], F, d, M, 1, ws.x, d};
-        launch_gemm_rows<1>(M, true, ws.act, F, F, d / 16, ed, s);
+        EpiResidual ed{d, M, 1, ws.x, d};
+        prof(DUO_PROF_DOWN, s);
+        launch_gemm_rows<1>(M, true, ws.act, w.w_down[l], F, d / 16, ed, s);
         const u16* gnext = l + 1 < c.n_layers ? w.g_attn[l + 1] : w.g_final;
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, gnext, ws.h, d, PR, c.rms_eps);
+        prof(DUO_PROF_NORM, s);
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, gnext, ws.h, d, PR, AT, c.rms_eps);
     }
-    EpiStoreF32 el{w.lm_head, d, V, M, 2, logits, V};
-    launch_gemm_rows<2>(M, true, ws.h, d, d, (V + 31) / 32, el, s);
+    EpiStoreF32 el{V, M, 2, logits, V};
+    prof(DUO_PROF_LMHEAD, s);
+    launch_gemm_rows<2>(M, true, ws.h, w.lm_head, d, (V + 31) / 32, el, s);
 }
 
 void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
                       hipStream_t s) {
+    prof(DUO_PROF_SAMPLE, s);
     hipLaunchKernelGGL(sample_stats_kernel, dim3(sa.k + 1, sa.n), dim3(256), 0, s, sa);
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST)
         hipLaunchKernelGGL(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), 0, s, sa);
@@ -193,7 +224,9 @@ void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const du
     CommitArgs ca{kc, vc, c ? c->n_kv_heads : 1, c ? c->head_dim : 0, c ? c->max_seq : 0, sa.P, sa.R, sa.n, sa.k, mode,
                   sa.accept_len, sa.next_token, sa.commit, prefix_len};
     const dim3 grid = kc ? dim3(c->n_kv_heads, c->n_layers) : dim3(1, 1);
+    prof(DUO_PROF_COMMIT, s);
     hipLaunchKernelGGL(commit_kernel, grid, dim3(256), 0, s, ca);
+    prof(-1, s);
 }
 
 int check_call(const duo_call* call, int vocab) {
@@ -282,6 +315,7 @@ int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_
     hipLaunchKernelGGL(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), 0, s,
                        ws.logits + (size_t)(m - 1) * cfg->vocab, cache->root_logits, cfg->vocab, cache->prefix_len,
                        host_prefix_len + m);
+    prof(-1, s);
     return hip_ok(hipGetLastError(), "duo_prefill_chunk launch");
 }
 
@@ -322,9 +356,98 @@ int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, in
     if (!aligned16(x) || !aligned16(w)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    EpiStoreF32 e{w, K, N, rows, 2, y, N};
-    launch_gemm_rows<2>(rows, false, x, K, K, (N + 31) / 32, e, s);
+    EpiStoreF32 e{N, rows, 2, y, N};
+    launch_gemm_rows<2>(rows, false, x, w, K, (N + 31) / 32, e, s);
     return hip_ok(hipGetLastError(), "duo_skinny_gemm launch");
+}
+
+size_t duo_packed_elems(int N, int K) {
+    if (N < 1 || K < 1) return 0;
+    return (size_t)((N + 31) / 32) * 32 * (size_t)K;
+}
+
+int duo_pack_matrix(const uint16_t* src, int N, int K, uint16_t* dst, void* hip_stream) {
+    if (!src || !dst) return DUO_ERR_NULL;
+    if (N < 1 || K < 32 || K % 32) return DUO_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL((pack_bands_kernel<PlainRows>), dim3((N + 31) / 32 * 2), dim3(256), 0, s, PlainRows{src, N, K}, K / 32,
+                       dst);
+    return hip_ok(hipGetLastError(), "duo_pack_matrix launch");
+}
+
+int duo_pack_qkv(const duo_model_config* cfg, const uint16_t* wq, const uint16_t* wk, const uint16_t* wv, uint16_t* dst,
+                 void* hip_stream) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!wq || !wk || !wv || !dst) return DUO_ERR_NULL;
+    if (!aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(dst)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    const int D = cfg->head_dim, half = D / 2, bph = half / 16;
+    const int bands = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * bph * 2;
+    hipLaunchKernelGGL((pack_bands_kernel<QKVRows>), dim3(bands), dim3(256), 0, s,
+                       QKVRows{wq, wk, wv, cfg->n_q_heads, cfg->n_kv_heads, D, half, bph, cfg->d_model}, cfg->d_model / 32, dst);
+    return hip_ok(hipGetLastError(), "duo_pack_qkv launch");
+}
+
+int duo_pack_gate_up(const duo_model_config* cfg, const uint16_t* w_gate, const uint16_t* w_up, uint16_t* dst,
+                     void* hip_stream) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!w_gate || !w_up || !dst) return DUO_ERR_NULL;
+    if (!aligned16(w_gate) || !aligned16(w_up) || !aligned16(dst)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL((pack_bands_kernel<GateUpRows>), dim3(cfg->d_ff / 16 * 2), dim3(256), 0, s,
+                       GateUpRows{w_gate, w_up, cfg->d_ff, cfg->d_model}, cfg->d_model / 32, dst);
+    return hip_ok(hipGetLastError(), "duo_pack_gate_up launch");
+}
+
+int duo_pack_activations(const uint16_t* src, int rows, int K, uint16_t* dst, void* hip_stream) {
+    if (!src || !dst) return DUO_ERR_NULL;
+    if (rows < 1 || rows > DUO_MAX_ROWS || K < 32 || K % 32) return DUO_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(pack_operand_kernel, dim3(K / 32), dim3(256), 0, s, src, rows, K, (rows + 15) / 16, dst);
+    return hip_ok(hipGetLastError(), "duo_pack_activations launch");
+}
+
+int duo_profile_enable(int enable) {
+    if (enable && g_prof.ev.empty()) {
+        g_prof.ev.resize(PROF_POOL);
+        g_prof.cls.assign(PROF_POOL, -1);
+        for (auto& e : g_prof.ev) {
+            int rc = hip_ok(hipEventCreate(&e), "hipEventCreate");
+            if (rc) return rc;
+        }
+    }
+    g_prof.on = enable != 0;
+    g_prof.used = 0;
+    return DUO_OK;
+}
+
+int duo_profile_read(double* ms, int32_t* launches) {
+    if (!ms || !launches) return DUO_ERR_NULL;
+    for (int i = 0; i < DUO_PROF_CLASSES; ++i) {
+        ms[i] = 0.0;
+        launches[i] = 0;
+    }
+    if (g_prof.used == 0) return DUO_OK;
+    int rc = hip_ok(hipEventSynchronize(g_prof.ev[g_prof.used - 1]), "hipEventSynchronize");
+    if (rc) return rc;
+    for (size_t i = 0; i + 1 < g_prof.used; ++i) {
+        const int cls = g_prof.cls[i];
+        if (cls < 0) continue;
+        float t = 0.f;
+        if ((rc = hip_ok(hipEventElapsedTime(&t, g_prof.ev[i], g_prof.ev[i + 1]), "hipEventElapsedTime"))) return rc;
+        ms[cls] += t;
+        launches[cls] += 1;
+    }
+    g_prof.used = 0;
+    return DUO_OK;
 }
 
 const char* duo_status_string(int code) {

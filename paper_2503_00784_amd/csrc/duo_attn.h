@@ -17,6 +17,7 @@
 // unnormalised O) go to scratch and a small kernel merges the chunks in chunk order.
 #pragma once
 #include "duo_common.h"
+#include "duo_gemm.h"
 
 struct AttnArgs {
     const u16* q;  // queries as bf16 pairs: hi plane [rows][Hq*D], lo plane q_plane elements further on
@@ -223,10 +224,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 }
 
 // Merge the chunk partials of one (row, query head) in chunk order, normalise, store as a bf16 pair
-// (hi in row m, lo in row m + pair_rows of the O-projection's operand buffer).
+// into the O projection's operand buffer (tile order; hi = operand row m, lo = row m + pair_rows).
 template <int D>
 __global__ __launch_bounds__(64) void attn_combine_kernel(const float* __restrict__ part, int nchunks, int mq_pad, int group,
-                                                           int M, u16* __restrict__ out, int ldo, int pair_rows) {
+                                                           int M, u16* __restrict__ out, int tiles, int pair_rows) {
     const int r = blockIdx.x, hk = blockIdx.y;
     const int m = r / group, gq = r % group;
     if (m >= M) return;
@@ -246,13 +247,13 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(const float* __restric
 #pragma unroll
         for (int e = 0; e < D / 64; ++e) acc[e] += p[threadIdx.x + e * 64] * w;
     }
-    u16* hi_row = out + (size_t)m * ldo + (hk * group + gq) * D;
-    u16* lo_row = out + (size_t)(pair_rows + m) * ldo + (hk * group + gq) * D;
+    const int col0 = (hk * group + gq) * D;
 #pragma unroll
     for (int e = 0; e < D / 64; ++e) {
         const float o = acc[e] / L;
         const u16 hi = f32_to_bf16(o);
-        hi_row[threadIdx.x + e * 64] = hi;
-        lo_row[threadIdx.x + e * 64] = f32_to_bf16(o - bf16_to_f32(hi));
+        const int col = col0 + threadIdx.x + e * 64;
+        out[operand_offset(m, col, tiles)] = hi;
+        out[operand_offset(pair_rows + m, col, tiles)] = f32_to_bf16(o - bf16_to_f32(hi));
     }
 }

@@ -2,12 +2,21 @@
 // pass, Alg. 1 right column).  The weights are read exactly once from HBM, straight into MFMA
 // operand registers; the few activation rows are re-read from L2 by every workgroup.
 //
-// Work split: a workgroup owns NT tiles of 16 weight rows and the whole K range; its NW waves
-// take the 32-wide K steps round-robin (so at any moment the workgroup reads NW*64 contiguous
-// bytes of each row), keep PF steps of loads in flight, and their partial sums are added in
-// wave order through LDS (deterministic, no float atomics).  The epilogue functor decides which
-// weight rows form a tile and what happens to the sums (plain store, residual add, SwiGLU,
-// rotary embedding + KV-cache scatter).
+// Streaming layout.  Both operands are stored in MFMA-tile order: a tile of 16 rows x 32 columns
+// (one MFMA operand, 1 KiB) is contiguous, lane l's eight bf16 values at byte 16*l, i.e.
+//     tile[(l % 16)][8 * (l / 16) + j]   at element   l * 8 + j        (l = 0..63, j = 0..7)
+// and the K/32 tiles of a 16-row band follow each other.  A wave therefore reads its band of the
+// weights as one linear stream, 1 KiB per load instruction, eight full cache lines at a time; with
+// row-major weights the same load touches sixteen half lines and costs a third of the bandwidth.
+// Weights are repacked once at load time (duo_pack.h); activations are written in this layout by
+// the kernels that produce them ([k step][row tile][lane][8]).
+//
+// Work split: a workgroup owns NT bands of 16 weight rows and the whole K range; its NW waves
+// take the K steps round-robin in groups of GRP, keep PF steps of loads in flight, and their partial
+// sums are added in wave order through LDS (deterministic, no float atomics).  NW = 1 (one wave per
+// workgroup, no partial sums) is used whenever the matrix has enough bands to fill the chip.  The
+// epilogue functor decides what happens to the sums (plain store, residual add, SwiGLU, rotary
+// embedding + KV-cache scatter).
 //
 // Activation precision: an activation a is carried as a bf16 pair (hi, lo) with hi = bf16(a),
 // lo = bf16(a - hi), i.e. 16 mantissa bits.  The pair occupies two ROWS of the MFMA A operand:
@@ -18,22 +27,25 @@
 #pragma once
 #include "duo_common.h"
 
-template <int MT, int NT, int NW, int PF, class Epi>
-__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restrict__ X, int ldx, int K, int quads,
-                                                               int pair_quads, Epi epi) {
+// element offset of (row r, column k) in an operand buffer of MT row tiles
+__device__ __forceinline__ size_t operand_offset(int r, int k, int MT) {
+    return ((size_t)((k >> 5) * MT + (r >> 4)) * 64 + ((k & 31) >> 3) * 16 + (r & 15)) * 8 + (k & 7);
+}
+
+template <int MT, int NT, int NW, int PF, int GRP, class Epi>
+__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restrict__ X, const u16* __restrict__ W, int K,
+                                                               int quads, int pair_quads, Epi epi) {
     __shared__ f32x4 red[NW * MT * NT * 64];
     const int tile = blockIdx.x;
     // the wave index must live in a scalar register: MFMA ignores the EXEC mask, so every branch
     // around an MFMA has to be a scalar (wave-uniform) branch, never lane predication
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int c = lane & 15, g = lane >> 4;
+    const int steps = K >> 5;
 
     const u16* wp[NT];
-    const u16* xp[MT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) wp[t] = epi.row_ptr(tile, t, c) + g * 8;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) xp[mt] = X + (size_t)(mt * 16 + c) * ldx + g * 8;
+    for (int t = 0; t < NT; ++t) wp[t] = W + ((size_t)(tile * NT + t) * steps) * 512 + lane * 8;
+    const u16* xp = X + lane * 8;
 
     f32x4 acc[MT][NT];
 #pragma unroll
@@ -41,42 +53,50 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int steps = K >> 5;
-    const int ni = (steps - wave + NW - 1) / NW;  // this wave's steps: wave, wave + NW, ...
+    // K steps are dealt to the waves in groups of GRP consecutive steps
+    const int groups = (steps + GRP - 1) / GRP;
+    const int my_groups = (groups - wave + NW - 1) / NW;
+    int ni = my_groups * GRP;  // this wave's steps (the last group of the matrix may be short)
+    auto step_of = [&](int i) { return ((i / GRP) * NW + wave) * GRP + (i % GRP); };
+    if (ni > 0 && step_of(ni - 1) >= steps) ni -= step_of(ni - 1) - steps + 1;
+
+    // Software pipeline with PF register slots per operand.  Slot p always holds step i0 + p; a slot is
+    // refilled right after the MFMAs that consumed it, so every slot keeps its registers for the whole
+    // loop and the number of loads in flight behind any MFMA is the same in every iteration.  All loads
+    // are unconditional (indices clamped to the wave's last step) and scheduling barriers keep the
+    // compiler from regrouping them, so the wait before each MFMA group is for exactly one slot.
+    bf16x8 bb[PF][NT], aa[PF][MT];
+    auto load_slot = [&](int p, int i) {
+        const int st = step_of(i);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) bb[p][t] = load_frag(wp[t] + (size_t)st * 512);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) aa[p][mt] = load_frag(xp + ((size_t)st * MT + mt) * 512);
+    };
+    auto mfma_slot = [&](int p) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[mt][t] = mfma16(aa[p][mt], bb[p][t], acc[mt][t]);
+    };
     if (ni > 0) {
-        bf16x8 bb[PF][NT], aa[PF][MT];
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int i = p < ni ? p : ni - 1;
-            const int off = (wave + NW * i) << 5;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) bb[p][t] = load_frag_stream(wp[t] + off);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) aa[p][mt] = load_frag(xp[mt] + off);
-        }
-        for (int i0 = 0; i0 < ni; i0 += PF) {
+        for (int p = 0; p < PF; ++p) load_slot(p, p < ni ? p : ni - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        int i0 = 0;
+        for (; i0 + PF < ni; i0 += PF) {
 #pragma unroll
             for (int p = 0; p < PF; ++p) {
-                const int i = i0 + p;
-                bf16x8 b[NT], a[MT];
-#pragma unroll
-                for (int t = 0; t < NT; ++t) b[t] = bb[p][t];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) a[mt] = aa[p][mt];
-                int in = i + PF;
-                in = in < ni ? in : ni - 1;  // tail: re-read the last step (in bounds, L1 hit)
-                const int off = (wave + NW * in) << 5;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) bb[p][t] = load_frag_stream(wp[t] + off);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) aa[p][mt] = load_frag(xp[mt] + off);
-                if (i < ni) {
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int t = 0; t < NT; ++t) acc[mt][t] = mfma16(a[mt], b[t], acc[mt][t]);
-                }
+                mfma_slot(p);
+                const int in = i0 + p + PF;
+                load_slot(p, in < ni ? in : ni - 1);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {  // drain: the last (up to PF) steps are already in the slots
+            if (i0 + p < ni) mfma_slot(p);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 #pragma unroll
@@ -112,16 +132,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 // ---- epilogues -------------------------------------------------------------------------------
 // store(tile, qi, c, v): v[t][i] is the sum for row m = 4*qi + i, column c of tile slot t.
 
-struct EpiStoreF32 {  // y[m][n] = sum ; tile slot t covers rows (tile*NT + t)*16 .. +16 of W
-    const u16* W;
-    int ldw, N, M, NT;
+struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile*NT + t)*16 .. +16 of W
+    int N, M, NT;
     float* Y;
     int ldy;
-    __device__ __forceinline__ const u16* row_ptr(int tile, int t, int c) const {
-        int n = (tile * NT + t) * 16 + c;
-        n = n < N ? n : N - 1;
-        return W + (size_t)n * ldw;
-    }
     template <int NTT>
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT]) const {
 #pragma unroll
@@ -138,15 +152,9 @@ struct EpiStoreF32 {  // y[m][n] = sum ; tile slot t covers rows (tile*NT + t)*1
 };
 
 struct EpiResidual {  // x[m][n] += sum  (fp32 residual stream, each element owned by one workgroup)
-    const u16* W;
-    int ldw, N, M, NT;
+    int N, M, NT;
     float* X;
     int ldx;
-    __device__ __forceinline__ const u16* row_ptr(int tile, int t, int c) const {
-        int n = (tile * NT + t) * 16 + c;
-        n = n < N ? n : N - 1;
-        return W + (size_t)n * ldw;
-    }
     template <int NTT>
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT]) const {
 #pragma unroll
@@ -162,17 +170,12 @@ struct EpiResidual {  // x[m][n] += sum  (fp32 residual stream, each element own
     }
 };
 
-struct EpiSwiGLU {  // slot 0 = gate row n, slot 1 = up row n; act[m][n] = silu(gate) * up as a bf16 pair
-    const u16* Wg;
-    const u16* Wu;
-    int ldw, F, M;
-    u16* act;  // [2 * pair_rows ..][ld]: row m hi, row pair_rows + m lo
-    int ld, pair_rows;
-    __device__ __forceinline__ const u16* row_ptr(int tile, int t, int c) const {
-        int n = tile * 16 + c;
-        n = n < F ? n : F - 1;
-        return (t == 0 ? Wg : Wu) + (size_t)n * ldw;
-    }
+// band 0 = gate rows tile*16.., band 1 = up rows tile*16..; act[m][n] = silu(gate) * up, written as a
+// bf16 pair straight into the down projection's operand buffer (row m hi, row pair_rows + m lo)
+struct EpiSwiGLU {
+    int F, M;
+    u16* act;
+    int act_tiles, pair_rows;
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2]) const {
         const int n = tile * 16 + c;
         if (n >= F) return;
@@ -183,22 +186,19 @@ struct EpiSwiGLU {  // slot 0 = gate row n, slot 1 = up row n; act[m][n] = silu(
                 const float gate = v[0][i], up = v[1][i];
                 const float a = gate / (1.f + expf(-gate)) * up;
                 const u16 hi = f32_to_bf16(a);
-                act[(size_t)m * ld + n] = hi;
-                act[(size_t)(pair_rows + m) * ld + n] = f32_to_bf16(a - bf16_to_f32(hi));
+                act[operand_offset(m, n, act_tiles)] = hi;
+                act[operand_offset(pair_rows + m, n, act_tiles)] = f32_to_bf16(a - bf16_to_f32(hi));
             }
         }
     }
 };
 
-// Fused Q/K/V projection: a tile pairs rows d and d + D/2 of one head (slot 0 / slot 1), the two
+// Fused Q/K/V projection: a workgroup's two bands are rows d.. and d + D/2.. of one head, the two
 // halves of a rotary pair, so the rotation is thread-local.  Q goes to the query buffer as a bf16 pair
 // (hi plane, lo plane), K
 // (rotated) and V into their cache slots; V is stored transposed [head][d][slot].
 struct EpiQKV {
-    const u16* Wq;
-    const u16* Wk;
-    const u16* Wv;
-    int ldw, Hq, Hkv, D, half, bph;  // bph = (D/2)/16 tiles per head
+    int Hq, Hkv, D, half, bph;  // bph = (D/2)/16 workgroup tiles per head
     u16* q_out;  // hi plane; the lo plane starts q_plane elements further on
     int ldq;
     size_t q_plane;
@@ -208,16 +208,6 @@ struct EpiQKV {
     const float* rope_cos;  // [rows][D/2]
     const float* rope_sin;
     RowPlan plan;
-    __device__ __forceinline__ const u16* row_ptr(int tile, int t, int c) const {
-        int head = tile / bph;
-        const int blk = tile - head * bph;
-        const int r = t * half + blk * 16 + c;
-        if (head < Hq) return Wq + (size_t)(head * D + r) * ldw;
-        head -= Hq;
-        if (head < Hkv) return Wk + (size_t)(head * D + r) * ldw;
-        head -= Hkv;
-        return Wv + (size_t)(head * D + r) * ldw;
-    }
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2]) const {
         int head = tile / bph;
         const int d = (tile - head * bph) * 16 + c;
@@ -250,36 +240,46 @@ struct EpiQKV {
     }
 };
 
-// rows: output rows M; paired: activations are bf16 pairs (rows m and pair_rows + m of X).
-template <int MT, int NT, class Epi>
-static inline void launch_gemm(const u16* X, int ldx, int K, int tiles, int quads, int pair_quads, const Epi& epi,
-                               hipStream_t s) {
-    constexpr int NW = MT <= 2 ? 8 : (MT <= 6 ? 4 : 2);  // keeps the reduction buffer within 64 KB of LDS
-    constexpr int PF = MT <= 2 ? 8 : (MT <= 4 ? 4 : 2);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, NW, PF, Epi>), dim3(tiles), dim3(NW * 64), 0, s, X, ldx, K, quads,
-                       pair_quads, epi);
-}
-
 // Rows of the A operand for M paired activations: hi rows [0, pair_rows), lo rows [pair_rows, 2*pair_rows).
 static inline int pair_rows_for(int M) { return (M + 7) / 8 * 8; }
 static inline int a_tiles_for(int M, bool paired) { return paired ? (2 * pair_rows_for(M) + 15) / 16 : (M + 15) / 16; }
 
+template <int MT, int NT, int NW, class Epi>
+static inline void launch_gemm_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int pq, const Epi& epi,
+                                   hipStream_t s) {
+    constexpr int PF = (NT + MT) <= 4 ? 8 : ((NT + MT) <= 8 ? 4 : 2);
+    constexpr int GRP = 2;
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, NW, PF, GRP, Epi>), dim3(tiles), dim3(NW * 64), 0, s, X, W, K, quads, pq,
+                       epi);
+}
+
+// One wave per workgroup when there are enough bands to fill the chip on their own (no partial sums to
+// add); otherwise several waves split K.
+template <int MT, int NT, class Epi>
+static inline void launch_gemm(const u16* X, const u16* W, int K, int tiles, int quads, int pq, const Epi& epi,
+                               hipStream_t s) {
+    constexpr int NWK = MT <= 6 ? 4 : 2;  // keeps the partial-sum buffer within 64 KiB of LDS
+    if (tiles >= 320) launch_gemm_cfg<MT, NT, 1>(X, W, K, tiles, quads, pq, epi, s);
+    else launch_gemm_cfg<MT, NT, NWK>(X, W, K, tiles, quads, pq, epi, s);
+}
+
+// M output rows; paired: the activations are bf16 pairs (rows m and pair_rows + m of the operand).
 template <int NT, class Epi>
-static inline void launch_gemm_rows(int M, bool paired, const u16* X, int ldx, int K, int tiles, const Epi& epi,
+static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16* W, int K, int tiles, const Epi& epi,
                                     hipStream_t s) {
     const int mt = a_tiles_for(M, paired);
     const int quads = paired ? pair_rows_for(M) / 4 : (M + 3) / 4;
     const int pq = paired ? pair_rows_for(M) / 4 : 0;
     switch (mt) {
-        case 1: launch_gemm<1, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 2: launch_gemm<2, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 3: launch_gemm<3, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 4: launch_gemm<4, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 5: launch_gemm<5, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 6: launch_gemm<6, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 7: launch_gemm<7, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 8: launch_gemm<8, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        case 9: launch_gemm<9, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
-        default: launch_gemm<10, NT>(X, ldx, K, tiles, quads, pq, epi, s); break;
+        case 1: launch_gemm<1, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 2: launch_gemm<2, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 3: launch_gemm<3, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 4: launch_gemm<4, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 5: launch_gemm<5, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 6: launch_gemm<6, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 7: launch_gemm<7, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 8: launch_gemm<8, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 9: launch_gemm<9, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        default: launch_gemm<10, NT>(X, W, K, tiles, quads, pq, epi, s); break;
     }
 }

@@ -1,6 +1,7 @@
 // Row-wise pieces of the target pass: embedding gather, RMSNorm, rotary tables.
 #pragma once
 #include "duo_common.h"
+#include "duo_gemm.h"
 
 __device__ __forceinline__ float block_sum_256(float v, float* sm) {
     v = wave_sum(v);
@@ -12,10 +13,11 @@ __device__ __forceinline__ float block_sum_256(float v, float* sm) {
     return t;
 }
 
-// h[m] = x[m] * rsqrt(mean(x[m]^2) + eps) * gain as a bf16 pair: hi in row m, lo in row m + pair_rows
-// of the GEMM operand buffer.  One workgroup (256 threads) per row.
+// h[m] = x[m] * rsqrt(mean(x[m]^2) + eps) * gain as a bf16 pair, written into a GEMM operand buffer
+// (tile order, see duo_gemm.h): hi as operand row m, lo as operand row m + pair_rows.  One workgroup
+// (256 threads) per row; a thread handles runs of eight consecutive channels = one 16-byte store.
 __device__ __forceinline__ void rmsnorm_row(const float* __restrict__ xr, const u16* __restrict__ gain,
-                                            u16* __restrict__ hi_row, u16* __restrict__ lo_row, int d, float eps,
+                                            u16* __restrict__ h, int m, int pair_rows, int tiles, int d, float eps,
                                             float* sm) {
     float ss = 0.f;
     for (int j = threadIdx.x; j < d; j += 256) {
@@ -24,19 +26,24 @@ __device__ __forceinline__ void rmsnorm_row(const float* __restrict__ xr, const 
     }
     const float tot = block_sum_256(ss, sm);
     const float rs = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int j = threadIdx.x; j < d; j += 256) {
-        const float h = xr[j] * rs * bf16_to_f32(gain[j]);
-        const u16 hi = f32_to_bf16(h);
-        hi_row[j] = hi;
-        lo_row[j] = f32_to_bf16(h - bf16_to_f32(hi));
+    for (int j8 = threadIdx.x * 8; j8 < d; j8 += 256 * 8) {
+        Frag8 hi, lo;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float v = xr[j8 + j] * rs * bf16_to_f32(gain[j8 + j]);
+            hi.h[j] = f32_to_bf16(v);
+            lo.h[j] = f32_to_bf16(v - bf16_to_f32(hi.h[j]));
+        }
+        *reinterpret_cast<u32x4*>(h + operand_offset(m, j8, tiles)) = hi.q;
+        *reinterpret_cast<u32x4*>(h + operand_offset(pair_rows + m, j8, tiles)) = lo.q;
     }
 }
 
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const u16* __restrict__ gain,
-                                                       u16* __restrict__ h, int d, int pair_rows, float eps) {
+                                                       u16* __restrict__ h, int d, int pair_rows, int tiles, float eps) {
     __shared__ float sm[4];
     const int m = blockIdx.x;
-    rmsnorm_row(x + (size_t)m * d, gain, h + (size_t)m * d, h + (size_t)(pair_rows + m) * d, d, eps, sm);
+    rmsnorm_row(x + (size_t)m * d, gain, h, m, pair_rows, tiles, d, eps, sm);
 }
 
 // x[m] = E[token_m]; h[m] = RMSNorm(x[m]) with the first layer's gain.  Also the device-side
@@ -44,7 +51,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 __global__ __launch_bounds__(256) void embed_norm_kernel(const u16* __restrict__ embed, const int32_t* __restrict__ tokens,
                                                           int root_token, RowPlan plan, int vocab, const int32_t* prefix_len,
                                                           int32_t* status, float* __restrict__ x, const u16* __restrict__ gain,
-                                                          u16* __restrict__ h, int d, int pair_rows, float eps) {
+                                                          u16* __restrict__ h, int d, int pair_rows, int tiles, float eps) {
     __shared__ float sm[4];
     const int m = blockIdx.x;
     if (m == 0 && threadIdx.x == 0 && prefix_len && status && *prefix_len != plan.P)
@@ -58,7 +65,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const u16* __restrict__
     float* xr = x + (size_t)m * d;
     for (int j = threadIdx.x; j < d; j += 256) xr[j] = bf16_to_f32(e[j]);
     __syncthreads();
-    rmsnorm_row(xr, gain, h + (size_t)m * d, h + (size_t)(pair_rows + m) * d, d, eps, sm);
+    rmsnorm_row(xr, gain, h, m, pair_rows, tiles, d, eps, sm);
 }
 
 // cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.

@@ -119,6 +119,14 @@ def test_other_entry_points_validate(lib):
     assert ss(lg=None) == -1 and ss(root=None) == -1 and ss(V=1) == -2 and ss(nb=16) == -5
     g = lambda **kw: lib.duo_skinny_gemm(kw.get("x", 0x1000), 0x1000, 0x1000, kw.get("rows", 8), 64, kw.get("K", 64), None)
     assert g(x=None) == -1 and g(rows=0) == -2 and g(rows=81) == -2 and g(K=48) == -2 and g(x=0x1002) == -4
+    assert lib.duo_packed_elems(4099, 512) == 4128 * 512 and lib.duo_packed_elems(32, 64) == 32 * 64
+    assert lib.duo_packed_elems(0, 64) == 0
+    pm = lambda **kw: lib.duo_pack_matrix(kw.get("src", 0x1000), kw.get("N", 64), kw.get("K", 64), kw.get("dst", 0x1000), None)
+    assert pm(src=None) == -1 and pm(dst=None) == -1 and pm(N=0) == -2 and pm(K=40) == -2 and pm(src=0x1004) == -4
+    assert lib.duo_pack_qkv(C.byref(cfg), None, 0x1000, 0x1000, 0x1000, None) == -1
+    assert lib.duo_pack_qkv(C.byref(cfg), 0x1000, 0x1000, 0x1008, 0x1000, None) == -4
+    assert lib.duo_pack_gate_up(C.byref(cfg), 0x1000, None, 0x1000, None) == -1
+    assert lib.duo_pack_activations(0x1000, 81, 64, 0x1000, None) == -2 and lib.duo_pack_activations(None, 8, 64, 0x1000, None) == -1
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
