@@ -53,8 +53,8 @@ extern "C" {
 #define DUO_SELECT_PAPER_SEQUENTIAL    1
 
 /* Geometry of the Llama-shaped target (the architecture of the paper's targets, Sec. 4.1
- * "Models").  head_dim is 64 or 128; d_model, n_q_heads*head_dim and d_ff are multiples of
- * 32; n_q_heads is a multiple of n_kv_heads; max_seq is a multiple of 32. */
+ * "Models").  head_dim is 64 or 128; d_model is a multiple of 64 (at most 8192), n_q_heads*head_dim and d_ff
+ * are multiples of 32; n_q_heads is a multiple of n_kv_heads; max_seq is a multiple of 32. */
 typedef struct duo_model_config {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, max_seq;
     float   rope_theta; /* rotary base; pair (d, d + head_dim/2) turns by pos * theta^(-2d/head_dim) */

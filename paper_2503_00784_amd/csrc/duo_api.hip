@@ -40,6 +40,7 @@ struct Workspace {
     double* stats;   // sampler
     double* p_run;
     int32_t* acc;
+    float* ssq;      // [Mp][d/16] partial sums of squares of the residual stream (for the next RMSNorm)
     size_t q_plane;  // elements between the two query planes
     size_t total;
 };
@@ -81,6 +82,7 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.rope_c = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
     ws.rope_s = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
     ws.logits = reinterpret_cast<float*>(take(Mp * V * 4));
+    ws.ssq = reinterpret_cast<float*>(take(Mp * (d / 16) * 4));
     carve_sampler(base, off, c.vocab, ws);
     ws.total = off;
     return ws;
@@ -92,8 +94,8 @@ int check_config(const duo_model_config* c) {
         c->max_seq < 32)
         return DUO_ERR_SHAPE;
     if (c->head_dim != 64 && c->head_dim != 128) return DUO_ERR_SHAPE;
-    if (c->d_model % 32 || c->d_ff % 32 || c->max_seq % 32) return DUO_ERR_SHAPE;
-    if (c->n_q_heads % c->n_kv_heads) return DUO_ERR_SHAPE;
+    if (c->d_model % 64 || c->d_model > 8192 || c->d_ff % 32 || c->max_seq % 32) return DUO_ERR_SHAPE;
+    if (c->n_q_heads % c->n_kv_heads || c->n_q_heads > 512) return DUO_ERR_SHAPE;
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return DUO_ERR_SHAPE;
     return DUO_OK;
 }
@@ -137,10 +139,13 @@ int hip_ok(hipError_t e, const char* what) {
 }
 
 template <int D>
-void launch_attention(int mtw, dim3 grid, const AttnArgs& a, hipStream_t s) {
-    switch (mtw) {
-        case 1: hipLaunchKernelGGL((attn_partial_kernel<D, 1>), grid, dim3(256), 0, s, a); break;
-        default: hipLaunchKernelGGL((attn_partial_kernel<D, 2>), grid, dim3(256), 0, s, a); break;
+void launch_attention(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_t s) {
+    if (nwv == 8) {
+        if (mtw == 1) hipLaunchKernelGGL((attn_partial_kernel<D, 1, 8>), grid, dim3(512), 0, s, a);
+        else if (D == 64) hipLaunchKernelGGL((attn_partial_kernel<64, 2, 8>), grid, dim3(512), 0, s, a);
+    } else {
+        if (mtw == 1) hipLaunchKernelGGL((attn_partial_kernel<D, 1, 4>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((attn_partial_kernel<D, 2, 4>), grid, dim3(256), 0, s, a);
     }
 }
 
@@ -153,64 +158,70 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const int d = c.d_model, D = c.head_dim, half = D / 2, Hq = c.n_q_heads, Hkv = c.n_kv_heads;
     const int qd = Hq * D, F = c.d_ff, V = c.vocab, group = Hq / Hkv;
 
+    const int NP = d / 16;  // partial sums of squares per row (one per 16-column tile of the residual stream)
+    const RowScale norm{ws.ssq, NP, 1.0f / (float)d, c.rms_eps}, none{nullptr, 0, 0.f, 0.f};
     prof(DUO_PROF_SETUP, s);
     hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(64), 0, s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
-    hipLaunchKernelGGL(embed_norm_kernel, dim3(M), dim3(256), 0, s, w.embed, tokens, root_token, plan, V,
-                       cache.prefix_len, status, ws.x, w.g_attn[0], ws.h, d, PR, AT, c.rms_eps);
+    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(256), 0, s, w.embed, tokens, root_token, plan, V, cache.prefix_len,
+                       status, ws.x, w.g_attn[0], ws.h, d, PR, AT, ws.ssq);
 
-    // attention launch shape
+    // Attention launch shape.  Short contexts: one workgroup of 8 waves per (kv head, row group) does
+    // the whole head and writes the output itself.  Long contexts: the keys are cut into chunks for
+    // more workgroups, and a second small kernel merges the chunk partials.
     const int Ktot = plan.P + M;
     const int NB = (Ktot + 31) / 32;
     const int MQ = M * group, MqT = (MQ + 15) / 16;
     const int mtw = MqT >= 2 ? 2 : 1;
     const int MG = (MqT + mtw - 1) / mtw;
-    int target = (1024 + Hkv * MG - 1) / (Hkv * MG);
-    target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
-    const int bpw = (NB + 4 * target - 1) / (4 * target);
-    const int nchunks = (NB + 4 * bpw - 1) / (4 * bpw);
     const int mq_pad = Mp * group;
+    int nwv, bpw, nchunks;
+    if (NB <= 32) {
+        nwv = (mtw == 2 && D == 128) ? 4 : 8;  // register budget of the two-tile, 128-channel variant
+        bpw = (NB + nwv - 1) / nwv;
+        nchunks = 1;
+    } else {
+        nwv = 4;
+        int target = (1024 + Hkv * MG - 1) / (Hkv * MG);
+        target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
+        bpw = (NB + 4 * target - 1) / (4 * target);
+        nchunks = (NB + 4 * bpw - 1) / (4 * bpw);
+    }
 
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * D * c.max_seq;
         EpiQKV eq{Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
         prof(DUO_PROF_QKV, s);
-        launch_gemm_rows<2>(M, true, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), eq, s);
+        launch_gemm_rows<2>(M, true, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), norm, eq, s);
 
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
-                    1.4426950408889634f / sqrtf((float)D), ws.part};
-        const dim3 grid(nchunks, Hkv, MG);
+                    1.4426950408889634f / sqrtf((float)D), ws.part, ws.attn, AT, PR};
         prof(DUO_PROF_ATTN, s);
-        if (D == 128) launch_attention<128>(mtw, grid, aa, s);
-        else launch_attention<64>(mtw, grid, aa, s);
-        prof(DUO_PROF_ATTN_COMB, s);
-        if (D == 128)
-            hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), 0, s, ws.part, nchunks, mq_pad, group, M,
-                               ws.attn, AT, PR);
-        else
-            hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), 0, s, ws.part, nchunks, mq_pad, group, M,
-                               ws.attn, AT, PR);
+        if (D == 128) launch_attention<128>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
+        else launch_attention<64>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
+        if (nchunks > 1) {
+            prof(DUO_PROF_ATTN_COMB, s);
+            if (D == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), 0, s, aa);
+            else hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), 0, s, aa);
+        }
 
-        EpiResidual eo{d, M, 1, ws.x, d};
+        // the residual projections leave x, the next norm's operand u = x * gain and its partial sums
+        EpiResidual eo{d, M, ws.x, d, w.g_ffn[l], ws.h, PR, AT, ws.ssq};
         prof(DUO_PROF_OPROJ, s);
-        launch_gemm_rows<1>(M, true, ws.attn, w.wo[l], qd, d / 16, eo, s);
-        prof(DUO_PROF_NORM, s);
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, w.g_ffn[l], ws.h, d, PR, AT, c.rms_eps);
+        launch_gemm_rows<1>(M, true, ws.attn, w.wo[l], qd, d / 16, none, eo, s);
 
         EpiSwiGLU eg{F, M, ws.act, AT, PR};
         prof(DUO_PROF_GATEUP, s);
-        launch_gemm_rows<2>(M, true, ws.h, w.w_gate_up[l], d, F / 16, eg, s);
+        launch_gemm_rows<2>(M, true, ws.h, w.w_gate_up[l], d, F / 16, norm, eg, s);
 
-        EpiResidual ed{d, M, 1, ws.x, d};
-        prof(DUO_PROF_DOWN, s);
-        launch_gemm_rows<1>(M, true, ws.act, w.w_down[l], F, d / 16, ed, s);
         const u16* gnext = l + 1 < c.n_layers ? w.g_attn[l + 1] : w.g_final;
-        prof(DUO_PROF_NORM, s);
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, ws.x, gnext, ws.h, d, PR, AT, c.rms_eps);
+        EpiResidual ed{d, M, ws.x, d, gnext, ws.h, PR, AT, ws.ssq};
+        prof(DUO_PROF_DOWN, s);
+        launch_gemm_rows<1>(M, true, ws.act, w.w_down[l], F, d / 16, none, ed, s);
     }
     EpiStoreF32 el{V, M, 2, logits, V};
     prof(DUO_PROF_LMHEAD, s);
-    launch_gemm_rows<2>(M, true, ws.h, w.lm_head, d, (V + 31) / 32, el, s);
+    launch_gemm_rows<2>(M, true, ws.h, w.lm_head, d, (V + 31) / 32, norm, el, s);
 }
 
 void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
@@ -357,7 +368,7 @@ int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, in
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
     EpiStoreF32 e{N, rows, 2, y, N};
-    launch_gemm_rows<2>(rows, false, x, w, K, (N + 31) / 32, e, s);
+    launch_gemm_rows<2>(rows, false, x, w, K, (N + 31) / 32, RowScale{nullptr, 0, 0.f, 0.f}, e, s);
     return hip_ok(hipGetLastError(), "duo_skinny_gemm launch");
 }
 

@@ -2,7 +2,7 @@
 // token and the earlier tokens of its own draft sequence (independent sequences, Sec. 3.2).
 //
 // The prefix keys/values of one KV head are read ONCE for all rows and all query heads of the
-// group: a workgroup takes one (kv head, key chunk), each of its four waves a share of the
+// group: a workgroup takes one (kv head, key chunk), each of its waves a share of the
 // chunk's 32-key blocks.  Per block a wave computes S^T = K Q^T and O^T += V^T P^T with MFMA:
 //   - K rows and V^T rows (values are cached transposed) are loaded straight from HBM in MFMA
 //     operand layout, 16 bytes per lane, no LDS staging -- each byte is consumed by one wave;
@@ -13,8 +13,9 @@
 //     cache's bf16;
 //   - the softmax is online (running max / sum per row), reduced across the four lane groups
 //     with wavefront shuffles.
-// The four waves are merged through LDS in a fixed chain, chunk partials (max, sum,
-// unnormalised O) go to scratch and a small kernel merges the chunks in chunk order.
+// The waves are merged through LDS in a fixed chain, chunk partials (max, sum, unnormalised O)
+// go to scratch and are merged in chunk order: by the same workgroup when a head is one chunk (short
+// prefixes: one kernel per layer), by a small second kernel otherwise.
 #pragma once
 #include "duo_common.h"
 #include "duo_gemm.h"
@@ -28,19 +29,54 @@ struct AttnArgs {
     int max_seq, group;
     RowPlan plan;
     int Ktot;             // P + M keys in play
-    int blocks_per_wave;  // 32-key blocks per wave; a chunk is 4 * blocks_per_wave blocks
+    int blocks_per_wave;  // 32-key blocks per wave; a chunk is (waves per workgroup) * blocks_per_wave blocks
     int nchunks;
     int mq_pad;           // padded number of (row, query-head-in-group) pairs
     float scale_log2;     // log2(e) / sqrt(D)
     float* part;          // [Hkv][mq_pad][nchunks][D + 4]: O (unnormalised), max, sum
+    u16* out;             // attention output, operand layout of the O projection (bf16 pairs)
+    int out_tiles, pair_rows;
 };
 
-template <int D, int MTW>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+// Merge the chunk partials of one (row, query head) in chunk order, normalise, store as a bf16 pair
+// (hi = operand row m, lo = operand row m + pair_rows).  Called by one wave; lane handles D/64 channels.
+template <int D>
+__device__ __forceinline__ void attn_merge_row(const AttnArgs& a, int hk, int r, int lane) {
+    const int m = r / a.group, gq = r % a.group;
+    const float* pp = a.part + ((size_t)hk * a.mq_pad + r) * a.nchunks * (D + 4);
+    float mx = -INFINITY;
+    for (int cb = 0; cb < a.nchunks; ++cb) mx = fmaxf(mx, pp[(size_t)cb * (D + 4) + D]);
+    float L = 0.f;
+    float acc[D / 64];
+#pragma unroll
+    for (int e = 0; e < D / 64; ++e) acc[e] = 0.f;
+    for (int cb = 0; cb < a.nchunks; ++cb) {
+        const float* p = pp + (size_t)cb * (D + 4);
+        const float mc = p[D];
+        if (mc == -INFINITY) continue;
+        const float w = exp2f(mc - mx);
+        L += p[D + 1] * w;
+#pragma unroll
+        for (int e = 0; e < D / 64; ++e) acc[e] += p[lane + e * 64] * w;
+    }
+    const int col0 = (hk * a.group + gq) * D;
+#pragma unroll
+    for (int e = 0; e < D / 64; ++e) {
+        const float o = acc[e] / L;
+        const u16 hi = f32_to_bf16(o);
+        const int col = col0 + lane + e * 64;
+        a.out[operand_offset(m, col, a.out_tiles)] = hi;
+        a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(o - bf16_to_f32(hi));
+    }
+}
+
+template <int D, int MTW, int NWV>
+__global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
     constexpr int KS = D / 32;  // MFMA K steps of the QK^T product
     constexpr int DT = D / 16;  // 16-channel tiles of the PV product
-    __shared__ f32x4 lds_o[MTW * DT * 64];
-    __shared__ float lds_ml[MTW][2][16];
+    constexpr int NBUF = NWV / 2;
+    __shared__ f32x4 lds_o[NBUF][MTW * DT * 64];
+    __shared__ float lds_ml[NBUF][MTW][2][16];
 
     const int cb = blockIdx.x, hk = blockIdx.y, mg = blockIdx.z;
     // scalar wave index: MFMA ignores the EXEC mask, so all control flow around it must be wave-uniform
@@ -48,13 +84,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     const int c = lane & 15, g = lane >> 4;
     const int MQ = a.plan.M * a.group;
 
-    // query operand (B of S^T = K Q^T): column c of tile mt is pair r = (row m, head gq of the group)
     // Visibility of draft slots, branch-free: with mk = key - P, row m sees mk < R (prefix and root)
     // and vis_lo <= mk <= vis_hi (its own sequence up to itself).
     bf16x8 qf[MTW][KS], ql[MTW][KS];
     int vis_lo[MTW], vis_hi[MTW];
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
+        // query operand (B of S^T = K Q^T): column c of tile mt is pair r = (row m, head gq of the group)
         const int r = (mg * MTW + mt) * 16 + c;
         const bool ok = r < MQ;
         const int m = ok ? r / a.group : 0, gq = ok ? r % a.group : 0;
@@ -84,53 +120,63 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 
     const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
     const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
-    const int b0 = (cb * 4 + wave) * a.blocks_per_wave;
-    for (int ib = 0; ib < a.blocks_per_wave; ++ib) {
-        const int kb = (b0 + ib) * 32;
-        if (kb >= a.Ktot) break;  // wave-uniform
-        // ---- S^T tiles: tile t, MFMA row r' = 4*g' + i' is key kb + 8*g' + 4*t + i'
-        f32x4 s[2][MTW];
+    const int b0 = (cb * NWV + wave) * a.blocks_per_wave;
+    int nb = (a.Ktot + 31) / 32 - b0;  // this wave's blocks
+    nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
+
+    // K rows and V^T rows of one 32-key block, in MFMA operand layout.  S^T tile t, MFMA row 4g'+i' is
+    // key kb + 8g' + 4t + i'; V^T operand dt is (channel dt*16 + c, keys kb + 8g .. +8).
+    bf16x8 kf[2][2][KS], vf[2][DT];  // double buffered: the next block is loaded while this one is used
+    auto load_k = [&](int buf, int kb) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             int key = kb + (c >> 2) * 8 + t * 4 + (c & 3);
             key = key < a.Ktot ? key : a.Ktot - 1;
             const u16* kp = kbase + (size_t)key * D;
-            bf16x8 kf[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[ks] = load_frag_stream(kp + ks * 32);
-#pragma unroll
-            for (int mt = 0; mt < MTW; ++mt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc = mfma16(kf[ks], ql[mt][ks], acc);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc = mfma16(kf[ks], qf[mt][ks], acc);
-                s[t][mt] = acc;
-            }
+            for (int ks = 0; ks < KS; ++ks) kf[buf][t][ks] = load_frag(kp + ks * 32);
         }
-        // ---- V^T operands: lane (channel dt*16 + c, keys kb + 8g .. +8)
-        bf16x8 vf[DT];
-        const bool tail = kb + 32 > a.Ktot;
+    };
+    auto load_v = [&](int buf, int kb) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            Frag8 f;
-            f.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vbase + (size_t)dt * 16 * a.max_seq + kb));
-            if (tail) {  // slots at or beyond Ktot may hold anything: zero them (0 * NaN would poison O)
+        for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = load_frag(vbase + (size_t)dt * 16 * a.max_seq + kb);
+    };
+    // scores of block kb (buffer buf), then request the next block's values (kb_next < 0: none), then
+    // softmax and P V; the next block's keys were requested before the call
+    auto use_block = [&](int buf, int kb, int kb_next) {
+        const bool tail = kb + 32 > a.Ktot;      // slots at or beyond Ktot may hold anything: zero their V
+        const bool masked = kb + 32 > a.plan.P;  // block touches draft slots or the end
+        if (tail) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                Frag8 f;
+                f.v = vf[buf][dt];
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
                     if (kb + g * 8 + j >= a.Ktot) f.h[j] = 0;
+                vf[buf][dt] = f.v;
             }
-            vf[dt] = f.v;
         }
-        // ---- mask, online softmax, P^T operand
-        const bool masked = kb + 32 > a.plan.P;  // block touches draft slots or the end
+        float scs[MTW][8];
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) {
-            float sc[8];
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < 4; ++i) sc[t * 4 + i] = s[t][mt][i] * a.scale_log2;
+                for (int ks = 0; ks < KS; ++ks) acc = mfma16(kf[buf][t][ks], ql[mt][ks], acc);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = mfma16(kf[buf][t][ks], qf[mt][ks], acc);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) scs[mt][t * 4 + i] = acc[i] * a.scale_log2;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (kb_next >= 0) load_v(buf ^ 1, kb_next);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            float* sc = scs[mt];
             if (masked) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -164,9 +210,25 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 f32x4 acc = o[mt][dt] * alpha;
-                acc = mfma16(vf[dt], pl.v, acc);
-                o[mt][dt] = mfma16(vf[dt], pf.v, acc);
+                acc = mfma16(vf[buf][dt], pl.v, acc);
+                o[mt][dt] = mfma16(vf[buf][dt], pf.v, acc);
             }
+        }
+    };
+    if (nb > 0) {
+        load_k(0, b0 * 32);
+        load_v(0, b0 * 32);
+    }
+    for (int ib = 0; ib < nb; ib += 2) {  // two blocks per trip so that the buffer index is static
+        const int kb0 = (b0 + ib) * 32;
+        const bool more1 = ib + 1 < nb, more2 = ib + 2 < nb;
+        if (more1) load_k(1, kb0 + 32);
+        __builtin_amdgcn_sched_barrier(0);
+        use_block(0, kb0, more1 ? kb0 + 32 : -1);
+        if (more1) {
+            if (more2) load_k(0, kb0 + 64);
+            __builtin_amdgcn_sched_barrier(0);
+            use_block(1, kb0 + 32, more2 ? kb0 + 64 : -1);
         }
     }
     // lane-group partial sums -> row sums (max is already uniform across lane groups)
@@ -176,24 +238,26 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         l_run[mt] += __shfl_xor(l_run[mt], 32, 64);
     }
 
-    // ---- merge the four waves in a fixed chain: 2 <- 3, 1 <- 2, 0 <- 1 (one LDS buffer)
-    for (int sender = 3; sender >= 1; --sender) {
-        if (wave == sender) {
+    // ---- merge the waves through LDS in a fixed binary tree: wave w + s -> wave w for s = NWV/2 .. 1
+#pragma unroll
+    for (int s = NWV / 2; s >= 1; s >>= 1) {
+        if (wave >= s && wave < 2 * s) {
+            const int buf = wave - s;
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt) {
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) lds_o[(mt * DT + dt) * 64 + lane] = o[mt][dt];
+                for (int dt = 0; dt < DT; ++dt) lds_o[buf][(mt * DT + dt) * 64 + lane] = o[mt][dt];
                 if (g == 0) {
-                    lds_ml[mt][0][c] = m_run[mt];
-                    lds_ml[mt][1][c] = l_run[mt];
+                    lds_ml[buf][mt][0][c] = m_run[mt];
+                    lds_ml[buf][mt][1][c] = l_run[mt];
                 }
             }
         }
         __syncthreads();
-        if (wave == sender - 1) {
+        if (wave < s) {
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt) {
-                const float mo = lds_ml[mt][0][c], lo = lds_ml[mt][1][c];
+                const float mo = lds_ml[wave][mt][0][c], lo = lds_ml[wave][mt][1][c];
                 const float mn = fmaxf(m_run[mt], mo);
                 const float ms = mn == -INFINITY ? 0.f : mn;
                 const float sa = exp2f(m_run[mt] - ms), sb = exp2f(mo - ms);
@@ -201,20 +265,36 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
                 l_run[mt] = l_run[mt] * sa + lo * sb;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
-                    o[mt][dt] = o[mt][dt] * sa + lds_o[(mt * DT + dt) * 64 + lane] * sb;
+                    o[mt][dt] = o[mt][dt] * sa + lds_o[wave][(mt * DT + dt) * 64 + lane] * sb;
             }
         }
         __syncthreads();
     }
-    if (wave == 0) {
+    if (wave != 0) return;
+    // wave 0 holds the chunk's result: lane (c, g) has O[r = c][dt*16 + 4g .. +4].  A head that is one
+    // chunk is normalised and stored right away (bf16 pairs into the O projection's operand buffer);
+    // otherwise the chunk partial goes to scratch for attn_combine_kernel.
 #pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) {
-            const int r = (mg * MTW + mt) * 16 + c;
-            if (r >= MQ) continue;
-            float* pp = a.part + (((size_t)hk * a.mq_pad + r) * a.nchunks + cb) * (D + 4);
+    for (int mt = 0; mt < MTW; ++mt) {
+        const int r = (mg * MTW + mt) * 16 + c;
+        if (r >= MQ) continue;
+        if (a.nchunks == 1) {
+            const int m = r / a.group, col0 = (hk * a.group + r % a.group) * D;
+            const float inv = 1.0f / l_run[mt];
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
-                *reinterpret_cast<f32x4*>(pp + dt * 16 + g * 4) = o[mt][dt];  // O^T rows 4g..4g+3 of tile dt
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = o[mt][dt][i] * inv;
+                    const u16 hi = f32_to_bf16(v);
+                    const int col = col0 + dt * 16 + g * 4 + i;
+                    a.out[operand_offset(m, col, a.out_tiles)] = hi;
+                    a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+                }
+        } else {
+            float* pp = a.part + (((size_t)hk * a.mq_pad + r) * a.nchunks + cb) * (D + 4);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(pp + dt * 16 + g * 4) = o[mt][dt];
             if (g == 0) {
                 pp[D] = m_run[mt];
                 pp[D + 1] = l_run[mt];
@@ -223,37 +303,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     }
 }
 
-// Merge the chunk partials of one (row, query head) in chunk order, normalise, store as a bf16 pair
-// into the O projection's operand buffer (tile order; hi = operand row m, lo = row m + pair_rows).
+// Merge of the chunk partials when a head was split over several workgroups: one wave per (row, head).
 template <int D>
-__global__ __launch_bounds__(64) void attn_combine_kernel(const float* __restrict__ part, int nchunks, int mq_pad, int group,
-                                                           int M, u16* __restrict__ out, int tiles, int pair_rows) {
-    const int r = blockIdx.x, hk = blockIdx.y;
-    const int m = r / group, gq = r % group;
-    if (m >= M) return;
-    const float* pp = part + ((size_t)hk * mq_pad + r) * nchunks * (D + 4);
-    float mx = -INFINITY;
-    for (int cb = 0; cb < nchunks; ++cb) mx = fmaxf(mx, pp[(size_t)cb * (D + 4) + D]);
-    float L = 0.f;
-    float acc[D / 64];
-#pragma unroll
-    for (int e = 0; e < D / 64; ++e) acc[e] = 0.f;
-    for (int cb = 0; cb < nchunks; ++cb) {
-        const float* p = pp + (size_t)cb * (D + 4);
-        const float mc = p[D];
-        if (mc == -INFINITY) continue;
-        const float w = exp2f(mc - mx);
-        L += p[D + 1] * w;
-#pragma unroll
-        for (int e = 0; e < D / 64; ++e) acc[e] += p[threadIdx.x + e * 64] * w;
-    }
-    const int col0 = (hk * group + gq) * D;
-#pragma unroll
-    for (int e = 0; e < D / 64; ++e) {
-        const float o = acc[e] / L;
-        const u16 hi = f32_to_bf16(o);
-        const int col = col0 + threadIdx.x + e * 64;
-        out[operand_offset(m, col, tiles)] = hi;
-        out[operand_offset(pair_rows + m, col, tiles)] = f32_to_bf16(o - bf16_to_f32(hi));
-    }
+__global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
+    attn_merge_row<D>(a, blockIdx.y, blockIdx.x, threadIdx.x);
 }
+

@@ -32,10 +32,54 @@ __device__ __forceinline__ size_t operand_offset(int r, int k, int MT) {
     return ((size_t)((k >> 5) * MT + (r >> 4)) * 64 + ((k & 31) >> 3) * 16 + (r & 15)) * 8 + (k & 7);
 }
 
+// RMSNorm without a kernel of its own.  The producer of the residual stream (embedding gather or a
+// residual projection) stores, next to x, the operand u = x * gain as bf16 pairs and, per row and per
+// 16-column tile, the partial sum of x^2.  The consuming projection multiplies its output row m by
+//     rs[m] = 1 / sqrt(sum of the partials / d + eps),
+// which is the same product: (x * rs * gain) W^T = rs * ((x * gain) W^T).  The partials are added in
+// a fixed order, identically in every workgroup.
+struct RowScale {
+    const float* part;  // [rows][n_part] partial sums of squares, nullptr: operand is not normalised
+    int n_part;         // multiple of 4, at most 512
+    float inv_d, eps;
+    static constexpr int MAXQ = 16;  // float4 loads per lane: 8 lanes x 16 x 4 = 512 partials per row
+    // Eight rows at a time: lane = (row r0 + lane % 8, segment lane / 8); a lane adds its segment of the
+    // row's partials in index order, the eight segments are then added by a fixed butterfly.  The loads
+    // are issued together (load), the arithmetic comes later (reduce), so they overlap what lies between.
+    __device__ __forceinline__ void load(f32x4 (&v)[MAXQ], int r0, int rows, int lane) const {
+        const int m = r0 + (lane & 7), seg = lane >> 3;
+        const int nq = n_part >> 2, len = (nq + 7) >> 3;
+        const int b = seg * len, e = min(nq, b + len);
+        const f32x4* row = reinterpret_cast<const f32x4*>(part + (size_t)(m < rows ? m : rows - 1) * n_part);
+#pragma unroll
+        for (int q = 0; q < MAXQ; ++q) {  // unconditional, index clamped into the row
+            const int i = b + q;
+            v[q] = row[i < e ? i : (e > 0 ? e - 1 : 0)];
+        }
+    }
+    __device__ __forceinline__ void reduce(const f32x4 (&v)[MAXQ], float* out, int r0, int rows, int lane) const {
+        const int seg = lane >> 3;
+        const int nq = n_part >> 2, len = (nq + 7) >> 3;
+        const int cnt = min(nq, seg * len + len) - seg * len;  // valid float4s of this lane's segment
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < MAXQ; ++q) {
+            const float t = (v[q].x + v[q].y) + (v[q].z + v[q].w);
+            s += q < cnt ? t : 0.f;
+        }
+        s += __shfl_xor(s, 8, 64);
+        s += __shfl_xor(s, 16, 64);
+        s += __shfl_xor(s, 32, 64);
+        const int m = r0 + (lane & 7);
+        if (seg == 0 && m < rows) out[m] = 1.0f / sqrtf(s * inv_d + eps);
+    }
+};
+
 template <int MT, int NT, int NW, int PF, int GRP, class Epi>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restrict__ X, const u16* __restrict__ W, int K,
-                                                               int quads, int pair_quads, Epi epi) {
+                                                               int quads, int pair_quads, RowScale rsc, Epi epi) {
     __shared__ f32x4 red[NW * MT * NT * 64];
+    __shared__ float row_scale[MT * 16];
     const int tile = blockIdx.x;
     // the wave index must live in a scalar register: MFMA ignores the EXEC mask, so every branch
     // around an MFMA has to be a scalar (wave-uniform) branch, never lane predication
@@ -79,10 +123,26 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[mt][t] = mfma16(aa[p][mt], bb[p][t], acc[mt][t]);
     };
+    // Per-row RMSNorm factors of the operand (see RowScale): the partial sums of the wave's first eight
+    // rows are requested before the first weights and added up while those are in flight.
+    const int nrows = quads * 4;
+    f32x4 rsv[RowScale::MAXQ];
+    const bool rs_first = rsc.part && wave * 8 < nrows;
+    if (rs_first) rsc.load(rsv, wave * 8, nrows, lane);
+    __builtin_amdgcn_sched_barrier(0);
     if (ni > 0) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) load_slot(p, p < ni ? p : ni - 1);
-        __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (rs_first) rsc.reduce(rsv, row_scale, wave * 8, nrows, lane);
+    if (rsc.part)
+        for (int r0 = (wave + NW) * 8; r0 < nrows; r0 += NW * 8) {  // more than 8 * NW rows
+            rsc.load(rsv, r0, nrows, lane);
+            rsc.reduce(rsv, row_scale, r0, nrows, lane);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    if (ni > 0) {
         int i0 = 0;
         for (; i0 + PF < ni; i0 += PF) {
 #pragma unroll
@@ -123,6 +183,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
                 for (int w = 1; w < NW; ++w) l += red[w * MT * NT * 64 + slot_lo + t * 64];
                 s += l;
             }
+            if (rsc.part) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s[i] *= row_scale[qi * 4 + i];
+            }
             v[t] = s;
         }
         epi.store(tile, qi, c, v);
@@ -151,21 +215,41 @@ struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile
     }
 };
 
-struct EpiResidual {  // x[m][n] += sum  (fp32 residual stream, each element owned by one workgroup)
-    int N, M, NT;
+// x[m][n] += sum (fp32 residual stream, each element owned by one workgroup).  The same thread then
+// prepares the next RMSNorm (see RowScale): u = x * gain as a bf16 pair into the next projection's
+// operand buffer, and the tile's partial sum of x^2 per row.  One band per workgroup (NT = 1).
+struct EpiResidual {
+    int N, M;
     float* X;
     int ldx;
-    template <int NTT>
-    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT]) const {
+    const u16* gain;  // gain of the norm that follows
+    u16* h;           // operand buffer of the next projection
+    int pair_rows, h_tiles;
+    float* ssq_part;  // [M][N/16]
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[1]) const {
+        const int n = tile * 16 + c;
+        const float gn = bf16_to_f32(gain[n]);
+        float sq[4];
 #pragma unroll
-        for (int t = 0; t < NTT; ++t) {
-            const int n = (tile * NT + t) * 16 + c;
-            if (n >= N) continue;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = qi * 4 + i;
-                if (m < M) X[(size_t)m * ldx + n] += v[t][i];
+        for (int i = 0; i < 4; ++i) {
+            const int m = qi * 4 + i;
+            sq[i] = 0.f;
+            if (m < M) {
+                const float xn = X[(size_t)m * ldx + n] + v[0][i];
+                X[(size_t)m * ldx + n] = xn;
+                sq[i] = xn * xn;
+                const float u = xn * gn;
+                const u16 hi = f32_to_bf16(u);
+                h[operand_offset(m, n, h_tiles)] = hi;
+                h[operand_offset(pair_rows + m, n, h_tiles)] = f32_to_bf16(u - bf16_to_f32(hi));
             }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // sum over the 16 columns of the tile (16 consecutive lanes)
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) sq[i] += __shfl_xor(sq[i], o, 64);
+            const int m = qi * 4 + i;
+            if (c == 0 && m < M) ssq_part[(size_t)m * (N >> 4) + tile] = sq[i];
         }
     }
 };
@@ -245,41 +329,41 @@ static inline int pair_rows_for(int M) { return (M + 7) / 8 * 8; }
 static inline int a_tiles_for(int M, bool paired) { return paired ? (2 * pair_rows_for(M) + 15) / 16 : (M + 15) / 16; }
 
 template <int MT, int NT, int NW, class Epi>
-static inline void launch_gemm_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int pq, const Epi& epi,
-                                   hipStream_t s) {
+static inline void launch_gemm_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int pq, const RowScale& rsc,
+                                   const Epi& epi, hipStream_t s) {
     constexpr int PF = (NT + MT) <= 4 ? 8 : ((NT + MT) <= 8 ? 4 : 2);
     constexpr int GRP = 2;
     hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, NW, PF, GRP, Epi>), dim3(tiles), dim3(NW * 64), 0, s, X, W, K, quads, pq,
-                       epi);
+                       rsc, epi);
 }
 
 // One wave per workgroup when there are enough bands to fill the chip on their own (no partial sums to
 // add); otherwise several waves split K.
 template <int MT, int NT, class Epi>
-static inline void launch_gemm(const u16* X, const u16* W, int K, int tiles, int quads, int pq, const Epi& epi,
-                               hipStream_t s) {
+static inline void launch_gemm(const u16* X, const u16* W, int K, int tiles, int quads, int pq, const RowScale& rsc,
+                               const Epi& epi, hipStream_t s) {
     constexpr int NWK = MT <= 6 ? 4 : 2;  // keeps the partial-sum buffer within 64 KiB of LDS
-    if (tiles >= 320) launch_gemm_cfg<MT, NT, 1>(X, W, K, tiles, quads, pq, epi, s);
-    else launch_gemm_cfg<MT, NT, NWK>(X, W, K, tiles, quads, pq, epi, s);
+    if (tiles >= 320) launch_gemm_cfg<MT, NT, 1>(X, W, K, tiles, quads, pq, rsc, epi, s);
+    else launch_gemm_cfg<MT, NT, NWK>(X, W, K, tiles, quads, pq, rsc, epi, s);
 }
 
 // M output rows; paired: the activations are bf16 pairs (rows m and pair_rows + m of the operand).
 template <int NT, class Epi>
-static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16* W, int K, int tiles, const Epi& epi,
-                                    hipStream_t s) {
+static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc,
+                                    const Epi& epi, hipStream_t s) {
     const int mt = a_tiles_for(M, paired);
     const int quads = paired ? pair_rows_for(M) / 4 : (M + 3) / 4;
     const int pq = paired ? pair_rows_for(M) / 4 : 0;
     switch (mt) {
-        case 1: launch_gemm<1, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 2: launch_gemm<2, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 3: launch_gemm<3, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 4: launch_gemm<4, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 5: launch_gemm<5, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 6: launch_gemm<6, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 7: launch_gemm<7, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 8: launch_gemm<8, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        case 9: launch_gemm<9, NT>(X, W, K, tiles, quads, pq, epi, s); break;
-        default: launch_gemm<10, NT>(X, W, K, tiles, quads, pq, epi, s); break;
+        case 1: launch_gemm<1, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 2: launch_gemm<2, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 3: launch_gemm<3, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 4: launch_gemm<4, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 5: launch_gemm<5, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 6: launch_gemm<6, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 7: launch_gemm<7, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 8: launch_gemm<8, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        case 9: launch_gemm<9, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
+        default: launch_gemm<10, NT>(X, W, K, tiles, quads, pq, rsc, epi, s); break;
     }
 }
