@@ -197,20 +197,20 @@ int duo_skinny_gemm(const uint16_t *x_packed, const uint16_t *w_packed, float *y
 
 /*
  * Per-kernel timing for the roofline report (the per-iteration time breakdown of Sec. 4.4
- * "Profiling", at kernel granularity).  While enabled, duo_verify / duo_prefill_chunk record a HIP
- * event on the call's stream before every kernel launch and after the last one;
- * duo_profile_read waits for the recorded events, adds the elapsed time between consecutive
- * events to the class of the kernel launched in between, returns the sums (milliseconds) and
- * launch counts accumulated since the last read, and resets them.  Enabling allocates a pool of
- * events; a verify call made while profiling is therefore not allocation-free or capturable.
- * Not thread-safe.  ms and launches are HOST arrays of DUO_PROF_CLASSES entries.
+ * "Profiling", at kernel granularity).  While enabled, every kernel that duo_verify /
+ * duo_prefill_chunk launch carries a start and a stop HIP event that take the dispatch's own begin and
+ * end timestamps; duo_profile_read waits for them, adds each kernel's duration to its class, returns
+ * the sums (milliseconds) and launch counts accumulated since the last read, and resets them.
+ * Enabling allocates a pool of events, and at most 4096 launches are recorded between two reads; a
+ * call made while profiling is therefore not allocation-free or capturable.  Not thread-safe.
+ * ms and launches are HOST arrays of DUO_PROF_CLASSES entries.
  */
 #define DUO_PROF_SETUP     0  /* rotary table, embedding gather + first RMSNorm */
 #define DUO_PROF_QKV       1  /* fused QKV projection + rotary + KV scatter */
 #define DUO_PROF_ATTN      2  /* masked attention over prefix + drafts (chunk partials) */
-#define DUO_PROF_ATTN_COMB 3  /* merge of the chunk partials */
+#define DUO_PROF_ATTN_COMB 3  /* merge of the chunk partials (long contexts only) */
 #define DUO_PROF_OPROJ     4  /* O projection + residual */
-#define DUO_PROF_NORM      5  /* RMSNorm */
+#define DUO_PROF_NORM      5  /* unused: the RMSNorms are folded into the projections */
 #define DUO_PROF_GATEUP    6  /* gate/up projection + SwiGLU */
 #define DUO_PROF_DOWN      7  /* down projection + residual */
 #define DUO_PROF_LMHEAD    8  /* LM head */

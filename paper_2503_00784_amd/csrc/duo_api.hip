@@ -117,17 +117,18 @@ int check_weights(const duo_model_config* c, const duo_weights* w) {
 // ---- optional per-kernel timing (see duo_profile_enable in the header)
 struct Profiler {
     bool on = false;
-    std::vector<hipEvent_t> ev;
-    std::vector<int> cls;  // class of the kernel launched after event i (-1: end of a call)
-    size_t used = 0;
+    std::vector<hipEvent_t> ev;  // pairs: start, stop
+    std::vector<int> cls;        // class of pair i
+    size_t used = 0;             // pairs in use
 };
 Profiler g_prof;
-constexpr size_t PROF_POOL = 8192;
+constexpr size_t PROF_POOL = 4096;  // pairs
 
-// Called before a launch of class `cls`, and with cls = -1 after the last launch of a call.
-inline void prof(int cls, hipStream_t s) {
-    if (!g_prof.on || g_prof.used >= g_prof.ev.size()) return;
-    (void)hipEventRecord(g_prof.ev[g_prof.used], s);
+// Called right before a launch of class `cls`: arms DUO_LAUNCH with the next event pair.
+inline void prof(int cls, hipStream_t) {
+    if (!g_prof.on || cls < 0 || g_prof.used >= g_prof.cls.size()) return;
+    g_launch_events.start = g_prof.ev[2 * g_prof.used];
+    g_launch_events.stop = g_prof.ev[2 * g_prof.used + 1];
     g_prof.cls[g_prof.used] = cls;
     ++g_prof.used;
 }
@@ -141,11 +142,11 @@ int hip_ok(hipError_t e, const char* what) {
 template <int D>
 void launch_attention(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_t s) {
     if (nwv == 8) {
-        if (mtw == 1) hipLaunchKernelGGL((attn_partial_kernel<D, 1, 8>), grid, dim3(512), 0, s, a);
-        else if (D == 64) hipLaunchKernelGGL((attn_partial_kernel<64, 2, 8>), grid, dim3(512), 0, s, a);
+        if (mtw == 1) DUO_LAUNCH((attn_partial_kernel<D, 1, 8>), grid, dim3(512), s, a);
+        else if (D == 64) DUO_LAUNCH((attn_partial_kernel<64, 2, 8>), grid, dim3(512), s, a);
     } else {
-        if (mtw == 1) hipLaunchKernelGGL((attn_partial_kernel<D, 1, 4>), grid, dim3(256), 0, s, a);
-        else hipLaunchKernelGGL((attn_partial_kernel<D, 2, 4>), grid, dim3(256), 0, s, a);
+        if (mtw == 1) DUO_LAUNCH((attn_partial_kernel<D, 1, 4>), grid, dim3(256), s, a);
+        else DUO_LAUNCH((attn_partial_kernel<D, 2, 4>), grid, dim3(256), s, a);
     }
 }
 
@@ -161,8 +162,9 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const int NP = d / 16;  // partial sums of squares per row (one per 16-column tile of the residual stream)
     const RowScale norm{ws.ssq, NP, 1.0f / (float)d, c.rms_eps}, none{nullptr, 0, 0.f, 0.f};
     prof(DUO_PROF_SETUP, s);
-    hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(64), 0, s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
-    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(256), 0, s, w.embed, tokens, root_token, plan, V, cache.prefix_len,
+    DUO_LAUNCH(rope_table_kernel, dim3(M), dim3(64), s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
+    prof(DUO_PROF_SETUP, s);
+    DUO_LAUNCH(embed_kernel, dim3(M), dim3(256), s, w.embed, tokens, root_token, plan, V, cache.prefix_len,
                        status, ws.x, w.g_attn[0], ws.h, d, PR, AT, ws.ssq);
 
     // Attention launch shape.  Short contexts: one workgroup of 8 waves per (kv head, row group) does
@@ -201,8 +203,8 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         else launch_attention<64>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
         if (nchunks > 1) {
             prof(DUO_PROF_ATTN_COMB, s);
-            if (D == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), 0, s, aa);
-            else hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), 0, s, aa);
+            if (D == 128) DUO_LAUNCH((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), s, aa);
+            else DUO_LAUNCH((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), s, aa);
         }
 
         // the residual projections leave x, the next norm's operand u = x * gain and its partial sums
@@ -227,17 +229,17 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
 void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
                       hipStream_t s) {
     prof(DUO_PROF_SAMPLE, s);
-    hipLaunchKernelGGL(sample_stats_kernel, dim3(sa.k + 1, sa.n), dim3(256), 0, s, sa);
+    DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, sa.n), dim3(256), s, sa);
+    prof(DUO_PROF_SAMPLE, s);
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST)
-        hipLaunchKernelGGL(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), 0, s, sa);
+        DUO_LAUNCH(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa);
     else
-        hipLaunchKernelGGL(sample_paper_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, s, sa);
+        DUO_LAUNCH(sample_paper_kernel, dim3(1), dim3(SAMPLE_THREADS), s, sa);
     CommitArgs ca{kc, vc, c ? c->n_kv_heads : 1, c ? c->head_dim : 0, c ? c->max_seq : 0, sa.P, sa.R, sa.n, sa.k, mode,
                   sa.accept_len, sa.next_token, sa.commit, prefix_len};
     const dim3 grid = kc ? dim3(c->n_kv_heads, c->n_layers) : dim3(1, 1);
     prof(DUO_PROF_COMMIT, s);
-    hipLaunchKernelGGL(commit_kernel, grid, dim3(256), 0, s, ca);
-    prof(-1, s);
+    DUO_LAUNCH(commit_kernel, grid, dim3(256), s, ca);
 }
 
 int check_call(const duo_call* call, int vocab) {
@@ -293,7 +295,7 @@ int duo_verify(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* 
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, out->status, 1, 0);
+    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     const RowPlan plan{call->host_prefix_len, R, call->n, call->k, M};
     float* logits = out->logits_out ? out->logits_out : ws.logits;
     enqueue_forward(*cfg, *w, *cache, draft_tokens, call->root_token, plan, ws, logits, out->status, s);
@@ -320,13 +322,12 @@ int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, status, 1, 0);
+    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, status, 1, 0);
     const RowPlan plan{host_prefix_len, 0, 1, m, m};
     enqueue_forward(*cfg, *w, *cache, tokens, -1, plan, ws, ws.logits, status, s);
-    hipLaunchKernelGGL(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), 0, s,
+    DUO_LAUNCH(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), s,
                        ws.logits + (size_t)(m - 1) * cfg->vocab, cache->root_logits, cfg->vocab, cache->prefix_len,
                        host_prefix_len + m);
-    prof(-1, s);
     return hip_ok(hipGetLastError(), "duo_prefill_chunk launch");
 }
 
@@ -353,7 +354,7 @@ int duo_spec_sample(const float* logits, const float* root_logits, int vocab, co
     carve_sampler(static_cast<char*>(workspace), off, vocab, ws);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, out->status, 1, 0);
+    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     SampleArgs sa{logits, vocab, root_logits, vocab, call->n, call->k, R, call->host_prefix_len, (double)call->temperature,
                   draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
                   out->commit, out->status};
@@ -383,7 +384,7 @@ int duo_pack_matrix(const uint16_t* src, int N, int K, uint16_t* dst, void* hip_
     if (!aligned16(src) || !aligned16(dst)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL((pack_bands_kernel<PlainRows>), dim3((N + 31) / 32 * 2), dim3(256), 0, s, PlainRows{src, N, K}, K / 32,
+    DUO_LAUNCH((pack_bands_kernel<PlainRows>), dim3((N + 31) / 32 * 2), dim3(256), s, PlainRows{src, N, K}, K / 32,
                        dst);
     return hip_ok(hipGetLastError(), "duo_pack_matrix launch");
 }
@@ -398,7 +399,7 @@ int duo_pack_qkv(const duo_model_config* cfg, const uint16_t* wq, const uint16_t
     (void)hipGetLastError();
     const int D = cfg->head_dim, half = D / 2, bph = half / 16;
     const int bands = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * bph * 2;
-    hipLaunchKernelGGL((pack_bands_kernel<QKVRows>), dim3(bands), dim3(256), 0, s,
+    DUO_LAUNCH((pack_bands_kernel<QKVRows>), dim3(bands), dim3(256), s,
                        QKVRows{wq, wk, wv, cfg->n_q_heads, cfg->n_kv_heads, D, half, bph, cfg->d_model}, cfg->d_model / 32, dst);
     return hip_ok(hipGetLastError(), "duo_pack_qkv launch");
 }
@@ -411,7 +412,7 @@ int duo_pack_gate_up(const duo_model_config* cfg, const uint16_t* w_gate, const 
     if (!aligned16(w_gate) || !aligned16(w_up) || !aligned16(dst)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL((pack_bands_kernel<GateUpRows>), dim3(cfg->d_ff / 16 * 2), dim3(256), 0, s,
+    DUO_LAUNCH((pack_bands_kernel<GateUpRows>), dim3(cfg->d_ff / 16 * 2), dim3(256), s,
                        GateUpRows{w_gate, w_up, cfg->d_ff, cfg->d_model}, cfg->d_model / 32, dst);
     return hip_ok(hipGetLastError(), "duo_pack_gate_up launch");
 }
@@ -422,13 +423,13 @@ int duo_pack_activations(const uint16_t* src, int rows, int K, uint16_t* dst, vo
     if (!aligned16(src) || !aligned16(dst)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL(pack_operand_kernel, dim3(K / 32), dim3(256), 0, s, src, rows, K, (rows + 15) / 16, dst);
+    DUO_LAUNCH(pack_operand_kernel, dim3(K / 32), dim3(256), s, src, rows, K, (rows + 15) / 16, dst);
     return hip_ok(hipGetLastError(), "duo_pack_activations launch");
 }
 
 int duo_profile_enable(int enable) {
     if (enable && g_prof.ev.empty()) {
-        g_prof.ev.resize(PROF_POOL);
+        g_prof.ev.resize(2 * PROF_POOL);
         g_prof.cls.assign(PROF_POOL, -1);
         for (auto& e : g_prof.ev) {
             int rc = hip_ok(hipEventCreate(&e), "hipEventCreate");
@@ -437,6 +438,7 @@ int duo_profile_enable(int enable) {
     }
     g_prof.on = enable != 0;
     g_prof.used = 0;
+    g_launch_events = LaunchEvents{};
     return DUO_OK;
 }
 
@@ -446,16 +448,13 @@ int duo_profile_read(double* ms, int32_t* launches) {
         ms[i] = 0.0;
         launches[i] = 0;
     }
-    if (g_prof.used == 0) return DUO_OK;
-    int rc = hip_ok(hipEventSynchronize(g_prof.ev[g_prof.used - 1]), "hipEventSynchronize");
-    if (rc) return rc;
-    for (size_t i = 0; i + 1 < g_prof.used; ++i) {
-        const int cls = g_prof.cls[i];
-        if (cls < 0) continue;
+    for (size_t i = 0; i < g_prof.used; ++i) {
+        int rc = hip_ok(hipEventSynchronize(g_prof.ev[2 * i + 1]), "hipEventSynchronize");
+        if (rc) return rc;
         float t = 0.f;
-        if ((rc = hip_ok(hipEventElapsedTime(&t, g_prof.ev[i], g_prof.ev[i + 1]), "hipEventElapsedTime"))) return rc;
-        ms[cls] += t;
-        launches[cls] += 1;
+        if ((rc = hip_ok(hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]), "hipEventElapsedTime"))) return rc;
+        ms[g_prof.cls[i]] += t;
+        launches[g_prof.cls[i]] += 1;
     }
     g_prof.used = 0;
     return DUO_OK;

@@ -1,6 +1,7 @@
 // Shared device-side types and helpers (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -9,6 +10,24 @@ typedef uint16_t u16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 #define DUO_WAVE 64
+
+// Every kernel launch of the library goes through DUO_LAUNCH.  When the per-kernel profiler is armed
+// (see duo_profile_enable) the launch carries a start and a stop event that take the dispatch's own
+// begin and end timestamps, the same clock a kernel trace reads; otherwise it is a plain launch.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+static LaunchEvents g_launch_events;
+#define DUO_LAUNCH(kernel, grid, block, stream, ...)                                                            \
+    do {                                                                                                        \
+        if (g_launch_events.start) {                                                                            \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, g_launch_events.start, g_launch_events.stop, \
+                                  0, __VA_ARGS__);                                                              \
+            g_launch_events = LaunchEvents{};                                                                   \
+        } else {                                                                                                \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                                    \
+        }                                                                                                       \
+    } while (0)
 
 // bf16 <-> fp32 (round to nearest even); inputs here are finite.
 __device__ __forceinline__ float bf16_to_f32(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }

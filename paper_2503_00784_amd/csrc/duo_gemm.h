@@ -333,8 +333,7 @@ static inline void launch_gemm_cfg(const u16* X, const u16* W, int K, int tiles,
                                    const Epi& epi, hipStream_t s) {
     constexpr int PF = (NT + MT) <= 4 ? 8 : ((NT + MT) <= 8 ? 4 : 2);
     constexpr int GRP = 2;
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, NW, PF, GRP, Epi>), dim3(tiles), dim3(NW * 64), 0, s, X, W, K, quads, pq,
-                       rsc, epi);
+    DUO_LAUNCH((gemm_skinny_kernel<MT, NT, NW, PF, GRP, Epi>), dim3(tiles), dim3(NW * 64), s, X, W, K, quads, pq, rsc, epi);
 }
 
 // One wave per workgroup when there are enough bands to fill the chip on their own (no partial sums to
