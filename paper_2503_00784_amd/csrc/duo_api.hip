@@ -46,13 +46,13 @@ struct Workspace {
 };
 
 size_t sample_ws_bytes(int vocab) {
-    return align_up((size_t)2 * DUO_MAX_ROWS * 2 * sizeof(double), 256) + align_up((size_t)vocab * sizeof(double), 256) +
+    return align_up((size_t)2 * DUO_MAX_ROWS * STATS_SPLIT * 2 * sizeof(double), 256) + align_up((size_t)vocab * sizeof(double), 256) +
            align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256);
 }
 
 void carve_sampler(char* base, size_t& off, int vocab, Workspace& ws) {
     ws.stats = reinterpret_cast<double*>(base + off);
-    off += align_up((size_t)2 * DUO_MAX_ROWS * 2 * sizeof(double), 256);
+    off += align_up((size_t)2 * DUO_MAX_ROWS * STATS_SPLIT * 2 * sizeof(double), 256);
     ws.p_run = reinterpret_cast<double*>(base + off);
     off += align_up((size_t)vocab * sizeof(double), 256);
     ws.acc = reinterpret_cast<int32_t*>(base + off);
@@ -229,7 +229,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
 void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
                       hipStream_t s) {
     prof(DUO_PROF_SAMPLE, s);
-    DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, sa.n), dim3(256), s, sa);
+    DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, sa.n, STATS_SPLIT), dim3(256), s, sa);
     prof(DUO_PROF_SAMPLE, s);
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST)
         DUO_LAUNCH(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa);

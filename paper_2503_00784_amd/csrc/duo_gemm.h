@@ -123,6 +123,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[mt][t] = mfma16(aa[p][mt], bb[p][t], acc[mt][t]);
     };
+    // What the epilogue will read from memory (residual values, gains, rotary factors) is requested now,
+    // for the first output quad of each thread, so that its latency hides behind the weight stream.
+    typename Epi::Pre pre;
+    const bool has_pre = (int)threadIdx.x < quads * 16;
+    if (has_pre) epi.prefetch(tile, threadIdx.x >> 4, threadIdx.x & 15, pre);
     // Per-row RMSNorm factors of the operand (see RowScale): the partial sums of the wave's first eight
     // rows are requested before the first weights and added up while those are in flight.
     const int nrows = quads * 4;
@@ -189,7 +194,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
             }
             v[t] = s;
         }
-        epi.store(tile, qi, c, v);
+        epi.store(tile, qi, c, v, pre, idx == (int)threadIdx.x);
     }
 }
 
@@ -200,8 +205,10 @@ struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile
     int N, M, NT;
     float* Y;
     int ldy;
+    struct Pre {};
+    __device__ __forceinline__ void prefetch(int, int, int, Pre&) const {}
     template <int NTT>
-    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT]) const {
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT], const Pre&, bool) const {
 #pragma unroll
         for (int t = 0; t < NTT; ++t) {
             const int n = (tile * NT + t) * 16 + c;
@@ -226,16 +233,28 @@ struct EpiResidual {
     u16* h;           // operand buffer of the next projection
     int pair_rows, h_tiles;
     float* ssq_part;  // [M][N/16]
-    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[1]) const {
+    struct Pre {
+        float x[4], g;
+    };
+    __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
         const int n = tile * 16 + c;
-        const float gn = bf16_to_f32(gain[n]);
+        p.g = bf16_to_f32(gain[n]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = qi * 4 + i;
+            p.x[i] = m < M ? X[(size_t)m * ldx + n] : 0.f;
+        }
+    }
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[1], const Pre& p, bool use_pre) const {
+        const int n = tile * 16 + c;
+        const float gn = use_pre ? p.g : bf16_to_f32(gain[n]);
         float sq[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = qi * 4 + i;
             sq[i] = 0.f;
             if (m < M) {
-                const float xn = X[(size_t)m * ldx + n] + v[0][i];
+                const float xn = (use_pre ? p.x[i] : X[(size_t)m * ldx + n]) + v[0][i];
                 X[(size_t)m * ldx + n] = xn;
                 sq[i] = xn * xn;
                 const float u = xn * gn;
@@ -260,7 +279,9 @@ struct EpiSwiGLU {
     int F, M;
     u16* act;
     int act_tiles, pair_rows;
-    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2]) const {
+    struct Pre {};
+    __device__ __forceinline__ void prefetch(int, int, int, Pre&) const {}
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2], const Pre&, bool) const {
         const int n = tile * 16 + c;
         if (n >= F) return;
 #pragma unroll
@@ -292,7 +313,21 @@ struct EpiQKV {
     const float* rope_cos;  // [rows][D/2]
     const float* rope_sin;
     RowPlan plan;
-    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2]) const {
+    struct Pre {
+        float cs[4], sn[4];
+    };
+    __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
+        const int head = tile / bph;
+        const int d = (tile - head * bph) * 16 + c;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = qi * 4 + i;
+            const bool rot = m < plan.M && head < Hq + Hkv;
+            p.cs[i] = rot ? rope_cos[m * half + d] : 1.f;
+            p.sn[i] = rot ? rope_sin[m * half + d] : 0.f;
+        }
+    }
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2], const Pre& p, bool use_pre) const {
         int head = tile / bph;
         const int d = (tile - head * bph) * 16 + c;
 #pragma unroll
@@ -301,7 +336,8 @@ struct EpiQKV {
             if (m >= plan.M) continue;
             const float lo = v[0][i], hi = v[1][i];
             if (head < Hq + Hkv) {
-                const float cs = rope_cos[m * half + d], sn = rope_sin[m * half + d];
+                const float cs = use_pre ? p.cs[i] : rope_cos[m * half + d];
+                const float sn = use_pre ? p.sn[i] : rope_sin[m * half + d];
                 const float rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
                 if (head < Hq) {
                     u16* q = q_out + (size_t)m * ldq + head * D + d;

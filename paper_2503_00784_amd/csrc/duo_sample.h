@@ -3,10 +3,10 @@
 // All probabilities are evaluated in double from the fp32 logits, so that the accept decision
 // u * q(t) < p(t) and the inverse-CDF draws are taken in the precision a plain reference uses;
 // the volumes are tiny next to the weight stream (two passes over a few vocabulary rows).
-//   sample_stats_kernel   one workgroup per judging distribution (i, j): max and normaliser of
-//                         softmax(logits / T), and the accept flag of draft token (i, j)
-//   sample_finish_kernel  one workgroup per sequence: leading accepts, then the correction
-//                         token from norm(max(0, p - q)) or the bonus token from p
+//   sample_stats_kernel   max and normaliser of softmax(logits / T) for every judging distribution
+//                         (i, j), the vocabulary cut into slices for parallelism
+//   sample_finish_kernel  one workgroup per sequence: accept flags, leading accepts, then the
+//                         correction token from norm(max(0, p - q)) or the bonus token from p
 //   sample_paper_kernel   the sequential first-token rule over the n sequences, with the
 //                         running distribution replaced by its residual after each rejection
 //   commit_kernel         picks the sequence to keep, moves its accepted K/V next to the prefix
@@ -22,7 +22,7 @@ struct SampleArgs {
     const int32_t* tokens;  // [n][k]
     const float* q;         // [n][k][V]
     const float* u;         // [n][k+1]
-    double* stats;          // [n][k+1][2]: max of z = logit / T, sum exp(z - max)
+    double* stats;          // [n][k+1][STATS_SPLIT][2]: per vocabulary slice, max of z = logit / T and sum exp(z - max)
     int32_t* acc;           // [n][k] accept flags
     double* p_run;          // [V] running distribution of the sequential rule
     int32_t* accept_len;    // [n]
@@ -40,6 +40,7 @@ struct SampleArgs {
 };
 
 constexpr int SAMPLE_THREADS = 1024;
+constexpr int STATS_SPLIT = 8;  // workgroups per judging distribution in sample_stats_kernel
 
 __device__ __forceinline__ double block_sum_d(double v, double* sm) {
     v = wave_sum(v);
@@ -62,29 +63,54 @@ __device__ __forceinline__ double block_max_d(double v, double* sm) {
     return t;
 }
 
+// grid (k+1, n, STATS_SPLIT): slice s of the judging distribution (i, j)
 __global__ __launch_bounds__(256) void sample_stats_kernel(SampleArgs a) {
     __shared__ double sm[16];
-    const int j = blockIdx.x, i = blockIdx.y;
+    const int j = blockIdx.x, i = blockIdx.y, sl = blockIdx.z;
     const float* row = a.judge_row(i, j);
+    const int len = (a.V + STATS_SPLIT - 1) / STATS_SPLIT;
+    const int v0 = sl * len, v1 = min(a.V, v0 + len);
     float lm = -INFINITY;
-    for (int v = threadIdx.x; v < a.V; v += 256) lm = fmaxf(lm, row[v]);
+    for (int v = v0 + threadIdx.x; v < v1; v += 256) lm = fmaxf(lm, row[v]);
     const double zmax = block_max_d((double)lm, sm) / a.T;
     double s = 0.0;
-    for (int v = threadIdx.x; v < a.V; v += 256) s += exp((double)row[v] / a.T - zmax);
+    for (int v = v0 + threadIdx.x; v < v1; v += 256) s += exp((double)row[v] / a.T - zmax);
     const double Z = block_sum_d(s, sm);
     if (threadIdx.x == 0) {
-        double* st = a.stats + ((size_t)i * (a.k + 1) + j) * 2;
+        double* st = a.stats + (((size_t)i * (a.k + 1) + j) * STATS_SPLIT + sl) * 2;
         st[0] = zmax;
         st[1] = Z;
-        if (j < a.k) {
+        if (sl == 0 && j < a.k) {
             const int raw = a.tokens[i * a.k + j];
             if ((raw < 0 || raw >= a.V) && a.status) atomicOr(a.status, 1);
-            const int t = a.token(i, j);
-            const double p_t = exp((double)row[t] / a.T - zmax) / Z;
-            const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
-            a.acc[i * a.k + j] = lhs < p_t ? 1 : 0;
         }
     }
+}
+
+// max and normaliser of judging distribution (i, j): the slices merged in slice order
+__device__ __forceinline__ void merged_stats(const SampleArgs& a, int i, int j, double& zmax, double& Z) {
+    const double* st = a.stats + ((size_t)i * (a.k + 1) + j) * STATS_SPLIT * 2;
+    zmax = st[0];
+    for (int s = 1; s < STATS_SPLIT; ++s) zmax = fmax(zmax, st[2 * s]);
+    Z = 0.0;
+    for (int s = 0; s < STATS_SPLIT; ++s)
+        if (st[2 * s + 1] > 0.0) Z += st[2 * s + 1] * exp(st[2 * s] - zmax);
+}
+
+// accept flags of sequence i, positions from..k-1 (one thread each), into acc[]; ends with a barrier
+__device__ __forceinline__ void accept_flags(const SampleArgs& a, int i, int from) {
+    const int j = from + threadIdx.x;
+    if (j < a.k) {
+        double zmax, Z;
+        merged_stats(a, i, j, zmax, Z);
+        const float* row = a.judge_row(i, j);
+        const int t = a.token(i, j);
+        const double p_t = exp((double)row[t] / a.T - zmax) / Z;
+        const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
+        a.acc[i * a.k + j] = lhs < p_t ? 1 : 0;
+    }
+    __threadfence_block();
+    __syncthreads();
 }
 
 // Inverse CDF over non-negative weights w(v), v ascending: smallest v whose running sum exceeds
@@ -153,8 +179,9 @@ __device__ int block_inverse_cdf(F w, int V, double u, double* sm_d, int* sm_i) 
 // Correction / bonus token of sequence i after `a` accepted drafts.
 __device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_d, int* sm_i) {
     const float* row = a.judge_row(i, acc_len);
-    const double* st = a.stats + ((size_t)i * (a.k + 1) + acc_len) * 2;
-    const double zmax = st[0], Z = st[1], T = a.T;
+    double zmax, Z;
+    merged_stats(a, i, acc_len, zmax, Z);
+    const double T = a.T;
     const double u = (double)a.u[i * (a.k + 1) + a.k];
     auto pw = [=](int v) { return exp((double)row[v] / T - zmax) / Z; };
     if (acc_len < a.k) {
@@ -176,6 +203,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArg
     __shared__ double sm_d[16];
     __shared__ int sm_i[4];
     const int i = blockIdx.x;
+    accept_flags(a, i, 0);
     const int acc_len = leading_accepts(a, i, 0);
     const int tok = finish_token(a, i, acc_len, sm_d, sm_i);
     if (threadIdx.x == 0) {
@@ -190,7 +218,8 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
     const int tid = threadIdx.x;
     {
         const float* row = a.judge_row(0, 0);
-        const double zmax = a.stats[0], Z = a.stats[1];
+        double zmax, Z;
+        merged_stats(a, 0, 0, zmax, Z);
         for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
     }
     __syncthreads();
@@ -216,6 +245,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
         auto pw = [=](int v) { return pr[v]; };
         tok = block_inverse_cdf(pw, a.V, (double)a.u[(a.n - 1) * (a.k + 1) + a.k], sm_d, sm_i);
     } else {
+        accept_flags(a, sel, 1);
         acc_len = leading_accepts(a, sel, 1);
         tok = finish_token(a, sel, acc_len, sm_d, sm_i);
     }
