@@ -199,8 +199,14 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
                     1.4426950408889634f / sqrtf((float)D), ws.part, ws.attn, AT, PR};
         prof(DUO_PROF_ATTN, s);
-        if (D == 128) launch_attention<128>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
-        else launch_attention<64>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
+        if (NB <= 32 && MqT == 1) {  // short context, one query tile: the no-loop kernel
+            if (D == 128) DUO_LAUNCH((attn_small_kernel<128, 4>), dim3(1, Hkv), dim3(512), s, aa);
+            else DUO_LAUNCH((attn_small_kernel<64, 4>), dim3(1, Hkv), dim3(512), s, aa);
+        } else if (D == 128) {
+            launch_attention<128>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
+        } else {
+            launch_attention<64>(mtw, nwv, dim3(nchunks, Hkv, MG), aa, s);
+        }
         if (nchunks > 1) {
             prof(DUO_PROF_ATTN_COMB, s);
             if (D == 128) DUO_LAUNCH((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), s, aa);

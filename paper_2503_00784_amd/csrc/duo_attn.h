@@ -303,6 +303,190 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
     }
 }
 
+// Short contexts (at most 8 * BATCH blocks of 32 keys, up to 16 query rows per kv head): the whole head
+// in one workgroup of eight waves, no loop.  A wave requests the keys of ALL its blocks and the values
+// of the first one at once, forms every score, requests the remaining values into the registers the
+// keys just left, does one plain softmax over its keys and the P V products; then the waves are merged
+// by the same LDS tree and wave 0 writes the normalised output.  One memory latency for the keys and
+// one for the values, instead of one per block.
+template <int D, int BATCH>
+__global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
+    constexpr int KS = D / 32, DT = D / 16, NWV = 8, NBUF = NWV / 2;
+    __shared__ f32x4 lds_o[NBUF][DT * 64];
+    __shared__ float lds_ml[NBUF][2][16];
+
+    const int hk = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int MQ = a.plan.M * a.group;
+
+    const int r = c;  // column c of the one query tile is pair r = (row m, head gq of the group)
+    const bool ok = r < MQ;
+    const int m = ok ? r / a.group : 0, gq = ok ? r % a.group : 0;
+    const int R = a.plan.R;
+    const int vis_lo = !ok ? 0x7fffffff : (m < R ? 0 : R + ((m - R) / a.plan.k) * a.plan.k);
+    const int vis_hi = ok ? m : -1;
+    bf16x8 qf[KS], ql[KS];
+    {
+        const u16* qp = a.q + (size_t)m * a.ldq + (hk * a.group + gq) * D + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag8 f;
+            f.q = ok ? *reinterpret_cast<const u32x4*>(qp + ks * 32) : u32x4{0u, 0u, 0u, 0u};
+            qf[ks] = f.v;
+            f.q = ok ? *reinterpret_cast<const u32x4*>(qp + a.q_plane + ks * 32) : u32x4{0u, 0u, 0u, 0u};
+            ql[ks] = f.v;
+        }
+    }
+    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
+    const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
+    const int NB = (a.Ktot + 31) / 32;
+    // block b of this wave is global block wave + 8*b (round-robin keeps the waves within one block of each other)
+    int nb = (NB - wave + NWV - 1) / NWV;
+    nb = nb < 0 ? 0 : nb;
+
+    bf16x8 kf[BATCH][2][KS], vf[BATCH][DT];
+    auto load_v = [&](int b) {
+        const int kb = (wave + NWV * b) * 32;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vf[b][dt] = load_frag(vbase + (size_t)dt * 16 * a.max_seq + kb);
+    };
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        if (b < nb) {
+            const int kb = (wave + NWV * b) * 32;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                int key = kb + (c >> 2) * 8 + t * 4 + (c & 3);
+                key = key < a.Ktot ? key : a.Ktot - 1;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[b][t][ks] = load_frag(kbase + (size_t)key * D + ks * 32);
+            }
+        }
+    }
+    if (nb > 0) load_v(0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    float sc[BATCH][8];
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sc[b][j] = -INFINITY;
+        if (b < nb) {
+            const int kb = (wave + NWV * b) * 32;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = mfma16(kf[b][t][ks], ql[ks], acc);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = mfma16(kf[b][t][ks], qf[ks], acc);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sc[b][t * 4 + i] = acc[i] * a.scale_log2;
+            }
+            if (kb + 32 > a.plan.P) {  // block touches draft slots or the end
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int mk = kb + g * 8 + j - a.plan.P;
+                    const bool vis = (mk < R) | ((mk >= vis_lo) & (mk <= vis_hi));
+                    sc[b][j] = vis ? sc[b][j] : -INFINITY;
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int b = 1; b < BATCH; ++b)
+        if (b < nb) load_v(b);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // one softmax over all keys of this wave
+    float mx = -INFINITY;
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mx = fmaxf(mx, sc[b][j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_safe = mx == -INFINITY ? 0.f : mx;
+    float m_run = mx, l_run = 0.f;
+    f32x4 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        if (b < nb) {
+            const int kb = (wave + NWV * b) * 32;
+            if (kb + 32 > a.Ktot) {  // slots at or beyond Ktot may hold anything: zero their V
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    Frag8 f;
+                    f.v = vf[b][dt];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (kb + g * 8 + j >= a.Ktot) f.h[j] = 0;
+                    vf[b][dt] = f.v;
+                }
+            }
+            Frag8 pf, pl;  // softmax weights as bf16 pairs (hi + lo)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float p = exp2f(sc[b][j] - m_safe);
+                const u16 hi = f32_to_bf16(p);
+                pf.h[j] = hi;
+                pl.h[j] = f32_to_bf16(p - bf16_to_f32(hi));
+                l_run += p;
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                o[dt] = mfma16(vf[b][dt], pl.v, o[dt]);
+                o[dt] = mfma16(vf[b][dt], pf.v, o[dt]);
+            }
+        }
+    }
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+
+    // merge the eight waves through LDS in a fixed binary tree: wave w + s -> wave w for s = 4, 2, 1
+#pragma unroll
+    for (int s = NWV / 2; s >= 1; s >>= 1) {
+        if (wave >= s && wave < 2 * s) {
+            const int buf = wave - s;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) lds_o[buf][dt * 64 + lane] = o[dt];
+            if (g == 0) {
+                lds_ml[buf][0][c] = m_run;
+                lds_ml[buf][1][c] = l_run;
+            }
+        }
+        __syncthreads();
+        if (wave < s) {
+            const float mo = lds_ml[wave][0][c], lo = lds_ml[wave][1][c];
+            const float mn = fmaxf(m_run, mo);
+            const float ms = mn == -INFINITY ? 0.f : mn;
+            const float sa = exp2f(m_run - ms), sb = exp2f(mo - ms);
+            m_run = mn;
+            l_run = l_run * sa + lo * sb;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * sa + lds_o[wave][dt * 64 + lane] * sb;
+        }
+        __syncthreads();
+    }
+    if (wave != 0 || !ok) return;
+    const int col0 = (hk * a.group + gq) * D;
+    const float inv = 1.0f / l_run;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float v = o[dt][i] * inv;
+            const u16 hi = f32_to_bf16(v);
+            const int col = col0 + dt * 16 + g * 4 + i;
+            a.out[operand_offset(m, col, a.out_tiles)] = hi;
+            a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+        }
+}
+
 // Merge of the chunk partials when a head was split over several workgroups: one wave per (row, head).
 template <int D>
 __global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
