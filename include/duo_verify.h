@@ -210,7 +210,7 @@ int duo_skinny_gemm(const uint16_t *x_packed, const uint16_t *w_packed, float *y
 #define DUO_PROF_ATTN      2  /* masked attention over prefix + drafts (chunk partials) */
 #define DUO_PROF_ATTN_COMB 3  /* merge of the chunk partials (long contexts only) */
 #define DUO_PROF_OPROJ     4  /* O projection + residual */
-#define DUO_PROF_NORM      5  /* unused: the RMSNorms are folded into the projections */
+#define DUO_PROF_RESID_REDUCE 5 /* more than 16 rows: sum of the K-split O/down partial results + residual */
 #define DUO_PROF_GATEUP    6  /* gate/up projection + SwiGLU */
 #define DUO_PROF_DOWN      7  /* down projection + residual */
 #define DUO_PROF_LMHEAD    8  /* LM head */

@@ -25,7 +25,7 @@ EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample
            "duo_spec_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
            "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
-PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "rmsnorm", "gate_up_swiglu", "down_proj", "lm_head",
+PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "residual_reduce", "gate_up_swiglu", "down_proj", "lm_head",
                 "sample", "commit"]
 
 _u16p = C.POINTER(C.c_uint16)

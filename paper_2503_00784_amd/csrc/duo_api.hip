@@ -41,6 +41,8 @@ struct Workspace {
     double* p_run;
     int32_t* acc;
     float* ssq;      // [Mp][d/16] partial sums of squares of the residual stream (for the next RMSNorm)
+    float* ssq_full; // [Mp] complete sums of squares (written by the one-workgroup-per-row producers)
+    float* split;    // [WIDE_MAX_SPLIT][Mp][d] partial results of the K-split residual projections
     size_t q_plane;  // elements between the two query planes
     size_t total;
 };
@@ -83,6 +85,8 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.rope_s = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
     ws.logits = reinterpret_cast<float*>(take(Mp * V * 4));
     ws.ssq = reinterpret_cast<float*>(take(Mp * (d / 16) * 4));
+    ws.ssq_full = reinterpret_cast<float*>(take(Mp * 4));
+    ws.split = reinterpret_cast<float*>(take((size_t)WIDE_MAX_SPLIT * Mp * d * 4));
     carve_sampler(base, off, c.vocab, ws);
     ws.total = off;
     return ws;
@@ -150,6 +154,56 @@ void launch_attention(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_
     }
 }
 
+// A projection whose epilogue finishes the rows (QKV, gate/up, LM head).  Up to eight rows, and up to sixteen
+// when the matrix has few bands, every wave streams its own bands; beyond that the waves of a workgroup
+// share the activation operand through LDS.
+template <int NT, class Epi>
+void launch_projection(int M, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
+                       hipStream_t s) {
+    if (M <= 8 || (M <= 16 && tiles < 600)) {
+        launch_gemm_rows<NT>(M, true, X, W, K, tiles, rsc, epi, s);
+        return;
+    }
+    const int quads = pair_rows_for(M) / 4;
+    switch ((M + 15) / 16) {
+        case 1: launch_wide<1, NT>(X, W, K, tiles, quads, rsc, epi, s); break;
+        case 2: launch_wide<2, NT>(X, W, K, tiles, quads, rsc, epi, s); break;
+        case 3: launch_wide<3, NT>(X, W, K, tiles, quads, rsc, epi, s); break;
+        case 4: launch_wide<4, NT>(X, W, K, tiles, quads, rsc, epi, s); break;
+        default: launch_wide<5, NT>(X, W, K, tiles, quads, rsc, epi, s); break;
+    }
+}
+
+// x += act W^T (O and down projections, N = d_model columns) followed by the preparation of the next RMSNorm.
+// Few rows: one kernel (EpiResidual).  Many rows: K split over workgroups, partial results, and a small
+// second kernel that adds them in split order and does EpiResidual's work.
+static_assert(WIDE_MAX_SPLIT <= 8, "residual_reduce_kernel holds at most eight splits in registers");
+
+// Whether the residual projection over K input channels runs as K-split partial products + reduce kernel.
+bool residual_is_split(int M, int K) { return !(M <= 16 || (M <= 32 && K <= 6144)); }
+
+void launch_residual_projection(int M, const u16* X, const u16* W, int K, const EpiResidual& er, float* split,
+                                float* ssq_full, int cls, hipStream_t s) {
+    const RowScale none{nullptr, 0, 0.f, 0.f, nullptr};
+    const int MH = (M + 15) / 16, d = er.N;
+    if (!residual_is_split(M, K)) {
+        prof(cls, s);
+        launch_gemm_rows<1>(M, true, X, W, K, d / 16, none, er, s);
+        return;
+    }
+    int S = 1;
+    prof(cls, s);
+    switch (MH) {
+        case 2: S = launch_wide_split<2>(X, W, K, d, M, split, none, s); break;
+        case 3: S = launch_wide_split<3>(X, W, K, d, M, split, none, s); break;
+        case 4: S = launch_wide_split<4>(X, W, K, d, M, split, none, s); break;
+        default: S = launch_wide_split<5>(X, W, K, d, M, split, none, s); break;
+    }
+    prof(DUO_PROF_RESID_REDUCE, s);
+    DUO_LAUNCH(residual_reduce_kernel, dim3(M), dim3(512), s, split, S, (size_t)M * d, er.X, er.gain, er.h, d, er.pair_rows,
+               er.h_tiles, er.ssq_part, ssq_full);
+}
+
 // The target pass over the rows of `plan`: fills the cache slots P .. P+M-1 and writes fp32
 // logits [M][V] (row stride V) to `logits`.
 void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_kv_cache& cache,
@@ -160,12 +214,16 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const int qd = Hq * D, F = c.d_ff, V = c.vocab, group = Hq / Hkv;
 
     const int NP = d / 16;  // partial sums of squares per row (one per 16-column tile of the residual stream)
-    const RowScale norm{ws.ssq, NP, 1.0f / (float)d, c.rms_eps}, none{nullptr, 0, 0.f, 0.f};
+    // RMSNorm factors from the producer's partial sums, or from its complete row sums where it wrote them
+    // (embedding gather, K-split reduce) and the consumer is the LDS-shared kernel, which reads them directly.
+    const RowScale norm_part{ws.ssq, NP, 1.0f / (float)d, c.rms_eps, nullptr};
+    const RowScale norm_full{ws.ssq, NP, 1.0f / (float)d, c.rms_eps, ws.ssq_full};
+    const bool o_split = residual_is_split(M, qd), down_split = residual_is_split(M, F);
     prof(DUO_PROF_SETUP, s);
     DUO_LAUNCH(rope_table_kernel, dim3(M), dim3(64), s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
     prof(DUO_PROF_SETUP, s);
     DUO_LAUNCH(embed_kernel, dim3(M), dim3(256), s, w.embed, tokens, root_token, plan, V, cache.prefix_len,
-                       status, ws.x, w.g_attn[0], ws.h, d, PR, AT, ws.ssq);
+                       status, ws.x, w.g_attn[0], ws.h, d, PR, AT, ws.ssq, ws.ssq_full);
 
     // Attention launch shape.  Short contexts: one workgroup of 8 waves per (kv head, row group) does
     // the whole head and writes the output itself.  Long contexts: the keys are cut into chunks for
@@ -194,7 +252,8 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         u16* vc = cache.v + (size_t)l * Hkv * D * c.max_seq;
         EpiQKV eq{Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
         prof(DUO_PROF_QKV, s);
-        launch_gemm_rows<2>(M, true, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), norm, eq, s);
+        launch_projection<2>(M, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), (l == 0 || down_split) ? norm_full : norm_part,
+                             eq, s);
 
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
                     1.4426950408889634f / sqrtf((float)D), ws.part, ws.attn, AT, PR};
@@ -215,21 +274,19 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
 
         // the residual projections leave x, the next norm's operand u = x * gain and its partial sums
         EpiResidual eo{d, M, ws.x, d, w.g_ffn[l], ws.h, PR, AT, ws.ssq};
-        prof(DUO_PROF_OPROJ, s);
-        launch_gemm_rows<1>(M, true, ws.attn, w.wo[l], qd, d / 16, none, eo, s);
+        launch_residual_projection(M, ws.attn, w.wo[l], qd, eo, ws.split, ws.ssq_full, DUO_PROF_OPROJ, s);
 
         EpiSwiGLU eg{F, M, ws.act, AT, PR};
         prof(DUO_PROF_GATEUP, s);
-        launch_gemm_rows<2>(M, true, ws.h, w.w_gate_up[l], d, F / 16, norm, eg, s);
+        launch_projection<2>(M, ws.h, w.w_gate_up[l], d, F / 16, o_split ? norm_full : norm_part, eg, s);
 
         const u16* gnext = l + 1 < c.n_layers ? w.g_attn[l + 1] : w.g_final;
         EpiResidual ed{d, M, ws.x, d, gnext, ws.h, PR, AT, ws.ssq};
-        prof(DUO_PROF_DOWN, s);
-        launch_gemm_rows<1>(M, true, ws.act, w.w_down[l], F, d / 16, none, ed, s);
+        launch_residual_projection(M, ws.act, w.w_down[l], F, ed, ws.split, ws.ssq_full, DUO_PROF_DOWN, s);
     }
     EpiStoreF32 el{V, M, 2, logits, V};
     prof(DUO_PROF_LMHEAD, s);
-    launch_gemm_rows<2>(M, true, ws.h, w.lm_head, d, (V + 31) / 32, norm, el, s);
+    launch_projection<2>(M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
 }
 
 void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
@@ -375,7 +432,7 @@ int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, in
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
     EpiStoreF32 e{N, rows, 2, y, N};
-    launch_gemm_rows<2>(rows, false, x, w, K, (N + 31) / 32, RowScale{nullptr, 0, 0.f, 0.f}, e, s);
+    launch_gemm_rows<2>(rows, false, x, w, K, (N + 31) / 32, RowScale{nullptr, 0, 0.f, 0.f, nullptr}, e, s);
     return hip_ok(hipGetLastError(), "duo_skinny_gemm launch");
 }
 

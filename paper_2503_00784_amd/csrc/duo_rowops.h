@@ -3,6 +3,22 @@
 #include "duo_common.h"
 #include "duo_gemm.h"
 
+// Sum of `v` over the NWV * 64 threads of a workgroup in a fixed order (lanes by butterfly, then the waves
+// in index order); thread 0 stores it.
+template <int NWV>
+__device__ __forceinline__ void block_row_sum(float v, float* wsum, float* out) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = wsum[0];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) t += wsum[w];
+        *out = t;
+    }
+}
+
 // x[m] = E[token_m], plus what the first RMSNorm needs (see RowScale in duo_gemm.h): u = x * gain as
 // bf16 pairs in the QKV projection's operand buffer and the per-tile partial sums of x^2.  Also the
 // device-side input checks: token ids in range, device prefix length equal to the host's.
@@ -11,8 +27,10 @@ __global__ __launch_bounds__(256) void embed_kernel(const u16* __restrict__ embe
                                                      int root_token, RowPlan plan, int vocab, const int32_t* prefix_len,
                                                      int32_t* status, float* __restrict__ x, const u16* __restrict__ gain,
                                                      u16* __restrict__ h, int d, int pair_rows, int tiles,
-                                                     float* __restrict__ ssq_part) {
+                                                     float* __restrict__ ssq_part, float* __restrict__ ssq_full) {
+    __shared__ float wsum[4];
     const int m = blockIdx.x;
+    float total = 0.f;
     if (m == 0 && threadIdx.x == 0 && prefix_len && status && *prefix_len != plan.P)
         atomicOr(status, 2);
     int tok = m < plan.R ? root_token : tokens[m - plan.R];
@@ -38,9 +56,64 @@ __global__ __launch_bounds__(256) void embed_kernel(const u16* __restrict__ embe
         }
         *reinterpret_cast<u32x4*>(h + operand_offset(m, j8, tiles)) = hi.q;
         *reinterpret_cast<u32x4*>(h + operand_offset(pair_rows + m, j8, tiles)) = lo.q;
+        total += sq;
         sq += __shfl_xor(sq, 1, 64);  // two runs of eight = one 16-column tile
         if (!(threadIdx.x & 1)) ssq_part[(size_t)m * (d >> 4) + (j8 >> 4)] = sq;
     }
+    block_row_sum<4>(total, wsum, ssq_full + m);
+}
+
+// Second half of a residual projection whose K range was split over workgroups: x[m] += sum of the S
+// partial results (added in split order), then what EpiResidual does for the next RMSNorm: u = x * gain
+// as bf16 pairs in operand layout and the partial sums of x^2 per 16-column tile, plus, because one
+// workgroup sees the whole row, the row's complete sum of squares.
+// One workgroup (512 threads) per row, eight consecutive channels per thread and turn; the loads of all
+// splits are issued together (S <= 8, indices beyond S re-read the last split and are not added).
+__global__ __launch_bounds__(512) void residual_reduce_kernel(const float* __restrict__ part, int S, size_t split_stride,
+                                                               float* __restrict__ x, const u16* __restrict__ gain,
+                                                               u16* __restrict__ h, int d, int pair_rows, int tiles,
+                                                               float* __restrict__ ssq_part, float* __restrict__ ssq_full) {
+    __shared__ float wsum[8];
+    const int m = blockIdx.x;
+    float total = 0.f;
+    for (int j8 = threadIdx.x * 8; j8 < d; j8 += 512 * 8) {  // d is a multiple of 64: lanes leave in pairs
+        float* xr = x + (size_t)m * d + j8;
+        const float* pr = part + (size_t)m * d + j8;
+        f32x4 p0[8], p1[8];
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp) {
+            const float* ps = pr + (size_t)(sp < S ? sp : S - 1) * split_stride;
+            p0[sp] = *reinterpret_cast<const f32x4*>(ps);
+            p1[sp] = *reinterpret_cast<const f32x4*>(ps + 4);
+        }
+        f32x4 a0 = *reinterpret_cast<const f32x4*>(xr), a1 = *reinterpret_cast<const f32x4*>(xr + 4);
+        Frag8 gv, hi, lo;
+        gv.q = *reinterpret_cast<const u32x4*>(gain + j8);
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp) {
+            if (sp < S) {
+                a0 += p0[sp];
+                a1 += p1[sp];
+            }
+        }
+        *reinterpret_cast<f32x4*>(xr) = a0;
+        *reinterpret_cast<f32x4*>(xr + 4) = a1;
+        float sq = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float xv = j < 4 ? a0[j] : a1[j - 4];
+            sq += xv * xv;
+            const float u = xv * bf16_to_f32(gv.h[j]);
+            hi.h[j] = f32_to_bf16(u);
+            lo.h[j] = f32_to_bf16(u - bf16_to_f32(hi.h[j]));
+        }
+        *reinterpret_cast<u32x4*>(h + operand_offset(m, j8, tiles)) = hi.q;
+        *reinterpret_cast<u32x4*>(h + operand_offset(pair_rows + m, j8, tiles)) = lo.q;
+        total += sq;
+        sq += __shfl_xor(sq, 1, 64);
+        if (!(threadIdx.x & 1)) ssq_part[(size_t)m * (d >> 4) + (j8 >> 4)] = sq;
+    }
+    block_row_sum<8>(total, wsum, ssq_full + m);
 }
 
 // cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.

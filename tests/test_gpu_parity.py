@@ -161,9 +161,11 @@ def test_tiny_config_prefill_and_verify_chain(B):
         root = res.commit_token
 
 
-@pytest.mark.parametrize("n,k,mode,root", [(3, 5, 1, 17), (1, 16, 0, -1), (4, 16, 0, 3), (8, 8, 1, -1), (2, 1, 0, 5)])
+@pytest.mark.parametrize("n,k,mode,root", [(3, 5, 1, 17), (1, 16, 0, -1), (4, 16, 0, 3), (8, 8, 1, -1), (2, 1, 0, 5),
+                                            (3, 8, 0, -1), (2, 16, 1, 9), (5, 8, 0, -1), (1, 9, 0, -1)])
 def test_mid_config_gqa_ragged(B, n, k, mode, root):
-    """3 layers, 8 query / 2 KV heads of 64, vocab 4099 (not a multiple of 16), prefix 77."""
+    """3 layers, 8 query / 2 KV heads of 64, vocab 4099 (not a multiple of 16), prefix 77.  The row counts
+    (16, 16, 65, 64, 3, 24, 33, 40, 9) cover every row-tile count of both projection kernels."""
     shape = inputs.MID
     say(f"MID n={n} k={k} mode={mode} root={root}")
     w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False)
