@@ -204,6 +204,13 @@ void launch_residual_projection(int M, const u16* X, const u16* W, int K, const 
                er.h_tiles, er.ssq_part, ssq_full);
 }
 
+template <int D>
+void launch_attention_shared(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_t s) {
+    if (mtw == 2) DUO_LAUNCH((attn_shared_kernel<D, 2, 8>), grid, dim3(512), s, a);
+    else if (nwv == 8) DUO_LAUNCH((attn_shared_kernel<D, 1, 8>), grid, dim3(512), s, a);
+    else DUO_LAUNCH((attn_shared_kernel<D, 1, 4>), grid, dim3(256), s, a);
+}
+
 // The target pass over the rows of `plan`: fills the cache slots P .. P+M-1 and writes fp32
 // logits [M][V] (row stride V) to `logits`.
 void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_kv_cache& cache,
@@ -234,8 +241,22 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const int mtw = MqT >= 2 ? 2 : 1;
     const int MG = (MqT + mtw - 1) / mtw;
     const int mq_pad = Mp * group;
+    // More than two query tiles per kv head: the kernel that stages K/V blocks in LDS for all query tiles.
+    const bool shared_kv = MqT > 2;
+    int sh_mtw = 1, sh_nwv = 4, sh_zg = 1;
     int nwv, bpw, nchunks;
-    if (NB <= 32) {
+    if (shared_kv) {
+        // one query tile per wave, about 256 workgroups (one per compute unit): measured best for 4 tiles x 32 heads and 16 tiles x 8 heads
+        sh_mtw = MqT > 16 ? 2 : 1;
+        sh_nwv = MqT > 4 ? 8 : 4;
+        sh_zg = (MqT + sh_nwv * sh_mtw - 1) / (sh_nwv * sh_mtw);
+        int target = (256 + Hkv * sh_zg - 1) / (Hkv * sh_zg);
+        target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
+        bpw = (NB + target - 1) / target;  // blocks per chunk
+        bpw = bpw < 2 ? 2 : bpw;
+        nchunks = (NB + bpw - 1) / bpw;
+        nwv = sh_nwv;
+    } else if (NB <= 32) {
         nwv = (mtw == 2 && D == 128) ? 4 : 8;  // register budget of the two-tile, 128-channel variant
         bpw = (NB + nwv - 1) / nwv;
         nchunks = 1;
@@ -258,7 +279,11 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
                     1.4426950408889634f / sqrtf((float)D), ws.part, ws.attn, AT, PR};
         prof(DUO_PROF_ATTN, s);
-        if (NB <= 32 && MqT == 1) {  // short context, one query tile: the no-loop kernel
+        if (shared_kv) {
+            const dim3 grid(nchunks, Hkv, sh_zg);
+            if (D == 128) launch_attention_shared<128>(sh_mtw, sh_nwv, grid, aa, s);
+            else launch_attention_shared<64>(sh_mtw, sh_nwv, grid, aa, s);
+        } else if (NB <= 32 && MqT == 1) {  // short context, one query tile: the no-loop kernel
             if (D == 128) DUO_LAUNCH((attn_small_kernel<128, 4>), dim3(1, Hkv), dim3(512), s, aa);
             else DUO_LAUNCH((attn_small_kernel<64, 4>), dim3(1, Hkv), dim3(512), s, aa);
         } else if (D == 128) {

@@ -38,26 +38,41 @@ struct AttnArgs {
     int out_tiles, pair_rows;
 };
 
-// Merge the chunk partials of one (row, query head) in chunk order, normalise, store as a bf16 pair
-// (hi = operand row m, lo = operand row m + pair_rows).  Called by one wave; lane handles D/64 channels.
+// Merge the chunk partials (at most 64) of one (row, query head), normalise, store as a bf16 pair
+// (hi = operand row m, lo = operand row m + pair_rows).  Called by one wave.  Lane cb takes chunk cb's
+// max and sum (one load each instead of a chain of them), the maximum and the weighted sum are formed by
+// fixed butterflies; the outputs are then added in chunk order, lane handling D/64 channels, four
+// chunks' loads in flight at a time.
 template <int D>
 __device__ __forceinline__ void attn_merge_row(const AttnArgs& a, int hk, int r, int lane) {
     const int m = r / a.group, gq = r % a.group;
     const float* pp = a.part + ((size_t)hk * a.mq_pad + r) * a.nchunks * (D + 4);
-    float mx = -INFINITY;
-    for (int cb = 0; cb < a.nchunks; ++cb) mx = fmaxf(mx, pp[(size_t)cb * (D + 4) + D]);
-    float L = 0.f;
+    const bool has = lane < a.nchunks;
+    const float mc = has ? pp[(size_t)lane * (D + 4) + D] : -INFINITY;
+    const float lc = has ? pp[(size_t)lane * (D + 4) + D + 1] : 0.f;
+    float mx = mc;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    const float w = mc == -INFINITY ? 0.f : exp2f(mc - mx);  // this lane's chunk weight
+    float L = lc * w;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) L += __shfl_xor(L, o, 64);
     float acc[D / 64];
 #pragma unroll
     for (int e = 0; e < D / 64; ++e) acc[e] = 0.f;
-    for (int cb = 0; cb < a.nchunks; ++cb) {
-        const float* p = pp + (size_t)cb * (D + 4);
-        const float mc = p[D];
-        if (mc == -INFINITY) continue;
-        const float w = exp2f(mc - mx);
-        L += p[D + 1] * w;
+    for (int cb0 = 0; cb0 < a.nchunks; cb0 += 4) {
+        float v[4][D / 64], wc[4];
 #pragma unroll
-        for (int e = 0; e < D / 64; ++e) acc[e] += p[lane + e * 64] * w;
+        for (int i = 0; i < 4; ++i) {
+            const int cb = cb0 + i < a.nchunks ? cb0 + i : a.nchunks - 1;
+            wc[i] = cb0 + i < a.nchunks ? __shfl(w, cb, 64) : 0.f;
+#pragma unroll
+            for (int e = 0; e < D / 64; ++e) v[i][e] = pp[(size_t)cb * (D + 4) + lane + e * 64];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < D / 64; ++e) acc[e] += v[i][e] * wc[i];
     }
     const int col0 = (hk * a.group + gq) * D;
 #pragma unroll
@@ -197,15 +212,13 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
             // the weights enter the MFMA as a bf16 pair hi + lo (16 mantissa bits): rounding them to a
             // single bf16 would add as much noise to O as the bf16 rounding of O itself
             Frag8 pf, pl;
-            float ps = 0.f;
+            float pw[8], ps = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float p = exp2f(sc[j] - m_safe);
-                const u16 hi = f32_to_bf16(p);
-                pf.h[j] = hi;
-                pl.h[j] = f32_to_bf16(p - bf16_to_f32(hi));
-                ps += p;
+                pw[j] = exp2f(sc[j] - m_safe);
+                ps += pw[j];
             }
+            split_bf16x8(pw, pf.q, pl.q);
             l_run[mt] = l_run[mt] * alpha + ps;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
@@ -429,14 +442,13 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
                 }
             }
             Frag8 pf, pl;  // softmax weights as bf16 pairs (hi + lo)
+            float pw[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float p = exp2f(sc[b][j] - m_safe);
-                const u16 hi = f32_to_bf16(p);
-                pf.h[j] = hi;
-                pl.h[j] = f32_to_bf16(p - bf16_to_f32(hi));
-                l_run += p;
+                pw[j] = exp2f(sc[b][j] - m_safe);
+                l_run += pw[j];
             }
+            split_bf16x8(pw, pf.q, pl.q);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 o[dt] = mfma16(vf[b][dt], pl.v, o[dt]);
@@ -485,6 +497,229 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
             a.out[operand_offset(m, col, a.out_tiles)] = hi;
             a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
         }
+}
+
+// Many query rows per kv head (more than two 16-row query tiles: many draft rows and/or a large GQA
+// group).  The kernels above give every wave its own keys and ALL query tiles, which does not fit the
+// registers beyond two tiles, so more tiles meant more workgroups re-reading the same keys.  Here it is
+// the other way round: a workgroup takes one (kv head, key chunk) and stages each 32-key block of K and
+// V^T once in LDS, in MFMA operand layout (the same 1 KiB tiles the other kernels load straight into
+// registers); each wave owns MTW query tiles and runs over all blocks of the chunk, so nothing is merged
+// between waves.  Two register sets hold the blocks on their way from global memory to LDS (two blocks
+// ahead of the MFMAs), two LDS buffers
+// alternate, one barrier per block.
+template <int D, int MTW, int NWV>
+__global__ __launch_bounds__(NWV * 64) void attn_shared_kernel(AttnArgs a) {
+    constexpr int KS = D / 32, DT = D / 16;
+    constexpr int KT = 2 * KS;         // K tiles per block (2 key halves x KS)
+    constexpr int TILES = KT + DT;     // 1 KiB tiles per block
+    constexpr int TPW = (TILES + NWV - 1) / NWV;  // tiles a wave moves per block
+    __shared__ u32x4 lds_kv[2][TILES * 64];
+
+    const int cb = blockIdx.x, hk = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar: MFMA ignores EXEC
+    const int c = lane & 15, g = lane >> 4;
+    const int MQ = a.plan.M * a.group;
+    const int tile0 = (blockIdx.z * NWV + wave) * MTW;  // first query tile of this wave
+
+    bf16x8 qf[MTW][KS], ql[MTW][KS];
+    int vis_lo[MTW], vis_hi[MTW];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        const int r = (tile0 + mt) * 16 + c;
+        const bool ok = r < MQ;
+        const int m = ok ? r / a.group : 0, gq = ok ? r % a.group : 0;
+        const int R = a.plan.R;
+        vis_lo[mt] = !ok ? 0x7fffffff : (m < R ? 0 : R + ((m - R) / a.plan.k) * a.plan.k);
+        vis_hi[mt] = ok ? m : -1;
+        const u16* qp = a.q + (size_t)m * a.ldq + (hk * a.group + gq) * D + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag8 f;
+            f.q = ok ? *reinterpret_cast<const u32x4*>(qp + ks * 32) : u32x4{0u, 0u, 0u, 0u};
+            qf[mt][ks] = f.v;
+            f.q = ok ? *reinterpret_cast<const u32x4*>(qp + a.q_plane + ks * 32) : u32x4{0u, 0u, 0u, 0u};
+            ql[mt][ks] = f.v;
+        }
+    }
+    f32x4 o[MTW][DT];
+    float m_run[MTW], l_run[MTW];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        m_run[mt] = -INFINITY;
+        l_run[mt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
+    const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
+    const int NB = (a.Ktot + 31) / 32;
+    const int b0 = cb * a.blocks_per_wave;  // here: blocks per chunk
+    int nb = NB - b0;
+    nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
+
+    // Tile j of a block: j < KT is K tile (t = j / KS, ks = j % KS): lane (c, g) holds key
+    // kb + 8*(c/4) + 4t + c%4, channels 32ks + 8g .. +8; otherwise V^T tile dt = j - KT: channel 16dt + c,
+    // keys kb + 8g .. +8 (zeroed at and beyond Ktot, where the cache may hold anything).  Wave w moves
+    // tiles w * TPW .. + TPW (whole cache lines of the K rows); block indices past the last block are clamped (loaded, never used).
+    constexpr int NSET = 2;  // register sets = blocks in flight (more did not pay: the loop is bound by its MFMA and VALU work)
+    u32x4 st[NSET][TPW];
+    auto g_load = [&](int set, int ib) {
+        const int kb = min(b0 + ib, NB - 1) * 32;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int j = wave * TPW + i;  // scalar
+            if (TILES % NWV == 0 || j < TILES) {
+                if (j < KT) {
+                    int key = kb + (c >> 2) * 8 + (j / KS) * 4 + (c & 3);
+                    key = key < a.Ktot ? key : a.Ktot - 1;
+                    st[set][i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)key * D + (j % KS) * 32);
+                } else {
+                    st[set][i] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(j - KT) * 16 * a.max_seq + kb);
+                }
+            }
+        }
+    };
+    auto l_store = [&](int set, int buf, int ib) {
+        const int kb = min(b0 + ib, NB - 1) * 32;
+        const bool tail = kb + 32 > a.Ktot;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int j = wave * TPW + i;
+            if (TILES % NWV == 0 || j < TILES) {
+                u32x4 v = st[set][i];
+                if (tail && j >= KT) {
+                    Frag8 f;
+                    f.q = v;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (kb + g * 8 + e >= a.Ktot) f.h[e] = 0;
+                    v = f.q;
+                }
+                lds_kv[buf][j * 64 + lane] = v;
+            }
+        }
+    };
+    auto frag = [&](int buf, int j) {
+        Frag8 f;
+        f.q = lds_kv[buf][j * 64 + lane];
+        return f.v;
+    };
+    auto use_block = [&](int buf, int kb) {
+        const bool masked = kb + 32 > a.plan.P;  // block touches draft slots or the end
+        float scs[MTW][8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            bf16x8 kf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[ks] = frag(buf, t * KS + ks);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt) {  // hi and lo query parts in separate chains: shorter dependent runs
+                f32x4 acc_l = {0.f, 0.f, 0.f, 0.f}, acc_h = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    acc_l = mfma16(kf[ks], ql[mt][ks], acc_l);
+                    acc_h = mfma16(kf[ks], qf[mt][ks], acc_h);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) scs[mt][t * 4 + i] = (acc_l[i] + acc_h[i]) * a.scale_log2;
+            }
+        }
+        Frag8 pf[MTW], pl[MTW];
+        float alpha[MTW];
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            float* sc = scs[mt];
+            if (masked) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int mk = kb + g * 8 + j - a.plan.P;
+                    const bool vis = (mk < a.plan.R) | ((mk >= vis_lo[mt]) & (mk <= vis_hi[mt]));
+                    sc[j] = vis ? sc[j] : -INFINITY;
+                }
+            }
+            float bm = sc[0];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) bm = fmaxf(bm, sc[j]);
+            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float m_new = fmaxf(m_run[mt], bm);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            alpha[mt] = exp2f(m_run[mt] - m_safe);
+            m_run[mt] = m_new;
+            float pw[8], ps = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                pw[j] = exp2f(sc[j] - m_safe);
+                ps += pw[j];
+            }
+            split_bf16x8(pw, pf[mt].q, pl[mt].q);  // softmax weights as bf16 pairs (hi + lo)
+            l_run[mt] = l_run[mt] * alpha[mt] + ps;
+            // the running maximum rarely moves after the first blocks: rescale only when some row's did
+            if (__ballot(alpha[mt] != 1.0f) != 0) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) o[mt][dt] = o[mt][dt] * alpha[mt];
+            }
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const bf16x8 vf = frag(buf, KT + dt);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt) {
+                f32x4 acc = mfma16(vf, pl[mt].v, o[mt][dt]);
+                o[mt][dt] = mfma16(vf, pf[mt].v, acc);
+            }
+        }
+    };
+
+    // Block ib travels in register set ib % NSET and is used from LDS buffer ib % 2.  NSET blocks are in
+    // flight per workgroup; indices are static because the loop body covers NSET blocks.  Iterations past
+    // the chunk's end move clamped blocks and compute nothing.
+#pragma unroll
+    for (int i = 0; i < NSET; ++i) g_load(i, i);
+    l_store(0, 0, 0);
+    g_load(0, NSET);
+    for (int ib0 = 0; ib0 < nb; ib0 += NSET) {
+#pragma unroll
+        for (int u = 0; u < NSET; ++u) {
+            const int ib = ib0 + u;
+            __syncthreads();  // buffer u % 2 is complete; every wave is done with the other one
+            l_store((u + 1) % NSET, (u + 1) & 1, ib + 1);
+            g_load((u + 1) % NSET, ib + 1 + NSET);
+            if (ib < nb) use_block(u & 1, (b0 + ib) * 32);
+        }
+    }
+
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        l_run[mt] += __shfl_xor(l_run[mt], 16, 64);
+        l_run[mt] += __shfl_xor(l_run[mt], 32, 64);
+        const int r = (tile0 + mt) * 16 + c;
+        if (r >= MQ) continue;
+        if (a.nchunks == 1) {
+            const int m = r / a.group, col0 = (hk * a.group + r % a.group) * D;
+            const float inv = 1.0f / l_run[mt];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = o[mt][dt][i] * inv;
+                    const u16 hi = f32_to_bf16(v);
+                    const int col = col0 + dt * 16 + g * 4 + i;
+                    a.out[operand_offset(m, col, a.out_tiles)] = hi;
+                    a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+                }
+        } else {
+            float* pp = a.part + (((size_t)hk * a.mq_pad + r) * a.nchunks + cb) * (D + 4);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(pp + dt * 16 + g * 4) = o[mt][dt];
+            if (g == 0) {
+                pp[D] = m_run[mt];
+                pp[D + 1] = l_run[mt];
+            }
+        }
+    }
 }
 
 // Merge of the chunk partials when a head was split over several workgroups: one wave per (row, head).

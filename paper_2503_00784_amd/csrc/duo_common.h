@@ -37,6 +37,23 @@ __device__ __forceinline__ u16 f32_to_bf16(float f) {
     return (u16)(u >> 16);
 }
 
+// Two floats -> two bf16 (round to nearest even) in one register, a in the low half: the hardware conversion.
+typedef __bf16 hwbf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    const hwbf16x2 v = __builtin_convertvector(f32x2{a, b}, hwbf16x2);
+    return __builtin_bit_cast(uint32_t, v);
+}
+// x[0..7] -> hi = bf16(x), lo = bf16(x - hi), as MFMA operand registers
+__device__ __forceinline__ void split_bf16x8(const float (&x)[8], u32x4& hi, u32x4& lo) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t h = pack_bf16x2(x[2 * j], x[2 * j + 1]);
+        hi[j] = h;
+        lo[j] = pack_bf16x2(x[2 * j] - __uint_as_float(h << 16), x[2 * j + 1] - __uint_as_float(h & 0xffff0000u));
+    }
+}
+
 union Frag8 {  // eight bf16 values = one 16-byte load = one MFMA operand
     bf16x8 v;
     u32x4 q;
