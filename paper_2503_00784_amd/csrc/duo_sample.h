@@ -114,63 +114,85 @@ __device__ __forceinline__ void accept_flags(const SampleArgs& a, int i, int fro
 }
 
 // Inverse CDF over non-negative weights w(v), v ascending: smallest v whose running sum exceeds
-// u * total.  Each thread owns a contiguous segment; segment sums are scanned in thread order.
+// u * total.  Every wave owns a contiguous chunk of the vocabulary and reads it 64 consecutive ids at a
+// time (coalesced; the loads of a chunk do not depend on each other).  First the chunk sums, added over
+// the waves in index order, locate the chunk where the running sum crosses the target; then that wave
+// alone narrows it down (lane segments, then a scan inside the crossing segment).
 // Returns (to every thread) the token, or -1 if the total is zero.
 template <class F>
 __device__ int block_inverse_cdf(F w, int V, double u, double* sm_d, int* sm_i) {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const int seg = (V + nt - 1) / nt;
-    const int v0 = tid * seg, v1 = min(V, v0 + seg);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nw = blockDim.x >> 6;
+    const int chunk = ((V + nw - 1) / nw + 63) / 64 * 64;
+    const int c0 = wave * chunk, c1 = min(V, c0 + chunk);
     double local = 0.0;
     int lastpos = -1;
-    for (int v = v0; v < v1; ++v) {
+#pragma unroll 4
+    for (int v = c0 + lane; v < c1; v += 64) {
         const double x = w(v);
         local += x;
         if (x > 0.0) lastpos = v;
     }
-    // exclusive scan of the segment sums: within a wave by shuffles, across waves serially
-    const int wave = tid >> 6, lane = tid & 63, nw = nt >> 6;
-    double incl = local;
+    const double csum = wave_sum(local);
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const double y = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += y;
+    for (int o = 32; o > 0; o >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, o, 64));
+    __syncthreads();
+    if (lane == 0) {
+        sm_d[wave] = csum;
+        sm_i[4 + wave] = lastpos;
     }
     __syncthreads();
-    if (lane == 63) sm_d[wave] = incl;
-    __syncthreads();
-    double base = 0.0, total = 0.0;
-    for (int ww = 0; ww < nw; ++ww) {
-        if (ww == wave) base = total;
-        total += sm_d[ww];
-    }
+    double total = 0.0;
+    for (int ww = 0; ww < nw; ++ww) total += sm_d[ww];
     if (!(total > 0.0)) return -1;
-    const double excl = base + (incl - local);
     const double target = u * total;
-    const bool mine = excl + local > target;
-    // first thread whose inclusive sum exceeds the target / last positive weight overall
-    __syncthreads();
-    if (tid == 0) {
-        sm_i[0] = 0x7FFFFFFF;
-        sm_i[1] = -1;
+    // the first chunk whose inclusive sum exceeds the target, and the running sum before it
+    int owner = -1, last_all = -1;
+    double base = 0.0, run = 0.0;
+    for (int ww = 0; ww < nw; ++ww) {
+        if (owner < 0 && run + sm_d[ww] > target) {
+            owner = ww;
+            base = run;
+        }
+        run += sm_d[ww];
+        last_all = max(last_all, sm_i[4 + ww]);
     }
-    __syncthreads();
-    if (mine) atomicMin(&sm_i[0], tid);
-    atomicMax(&sm_i[1], lastpos);
-    __syncthreads();
-    const int first = sm_i[0];
-    if (first == 0x7FFFFFFF) return sm_i[1];  // rounding left no crossing: largest positive id
-    if (tid == first) {
-        double s = 0.0;
-        int tok = lastpos;
-        for (int v = v0; v < v1; ++v) {
-            s += w(v);
-            if (excl + s > target) {
-                tok = v;
-                break;
+    if (owner < 0) return last_all;  // rounding left no crossing: largest id with positive weight
+    if (wave == owner) {
+        // Lane l re-adds ids [c0 + l*per, +per) of the chunk; a scan over the lanes finds the lane whose
+        // segment holds the crossing; the wave then walks that segment 64 ids at a time.
+        const int per = chunk >> 6;
+        const int s0 = c0 + lane * per, s1 = min(c1, s0 + per);
+        double seg = 0.0;
+#pragma unroll 4
+        for (int v = s0; v < s1; ++v) seg += w(v);
+        double incl = seg;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double y = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += y;
+        }
+        const unsigned long long hit = __ballot(base + incl > target);
+        int tok = -1;
+        if (hit) {
+            const int hl = __ffsll((long long)hit) - 1;
+            double before = base + __shfl(incl - seg, hl, 64);  // running sum in front of that segment
+            const int h0 = c0 + hl * per, h1 = min(c1, h0 + per);
+            for (int v0 = h0; v0 < h1 && tok < 0; v0 += 64) {
+                const int v = v0 + lane;
+                const double x = v < h1 ? w(v) : 0.0;
+                double ix = x;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const double y = __shfl_up(ix, o, 64);
+                    if (lane >= o) ix += y;
+                }
+                const unsigned long long h2 = __ballot(before + ix > target);
+                if (h2) tok = v0 + __ffsll((long long)h2) - 1;
+                before += __shfl(ix, 63, 64);
             }
         }
-        sm_i[2] = tok;
+        // the chunk sum crossed but, in this summation order, no prefix did: its last positive id
+        if (lane == 0) sm_i[2] = tok >= 0 ? tok : sm_i[4 + wave];
     }
     __syncthreads();
     return sm_i[2];
@@ -181,12 +203,14 @@ __device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_
     const float* row = a.judge_row(i, acc_len);
     double zmax, Z;
     merged_stats(a, i, acc_len, zmax, Z);
-    const double T = a.T;
+    // reciprocals once per call instead of two divisions per vocabulary entry (the single workgroup is
+    // bound by its double-precision arithmetic); the results differ from the quotients by an ulp at most
+    const double iT = 1.0 / a.T, iZ = 1.0 / Z;
     const double u = (double)a.u[i * (a.k + 1) + a.k];
-    auto pw = [=](int v) { return exp((double)row[v] / T - zmax) / Z; };
+    auto pw = [=](int v) { return exp((double)row[v] * iT - zmax) * iZ; };
     if (acc_len < a.k) {
         const float* qrow = a.q + ((size_t)i * a.k + acc_len) * a.V;
-        auto rw = [=](int v) { return fmax(exp((double)row[v] / T - zmax) / Z - (double)qrow[v], 0.0); };
+        auto rw = [=](int v) { return fmax(exp((double)row[v] * iT - zmax) * iZ - (double)qrow[v], 0.0); };
         const int tok = block_inverse_cdf(rw, a.V, u, sm_d, sm_i);
         if (tok >= 0) return tok;  // else: the residual vanished (p == q), fall back to p
     }
@@ -201,7 +225,7 @@ __device__ __forceinline__ int leading_accepts(const SampleArgs& a, int i, int f
 
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArgs a) {
     __shared__ double sm_d[16];
-    __shared__ int sm_i[4];
+    __shared__ int sm_i[4 + 16];
     const int i = blockIdx.x;
     accept_flags(a, i, 0);
     const int acc_len = leading_accepts(a, i, 0);
@@ -214,7 +238,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArg
 
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs a) {
     __shared__ double sm_d[16];
-    __shared__ int sm_i[4];
+    __shared__ int sm_i[4 + 16];
     const int tid = threadIdx.x;
     {
         const float* row = a.judge_row(0, 0);
