@@ -38,6 +38,11 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--k-sweep", default="", help="comma-separated draft lengths, e.g. 2,4,8,16: also time one sequence of k "
+                    "tokens on the same model and prefix (verify latency vs tokens verified) and add \"k_sweep\" to the line")
+    ap.add_argument("--draft-step-ms", type=float, default=0.0,
+                    help="with --k-sweep: time of one draft-model step on the host; adds the cost coefficient c(k) and the "
+                    "balanced draft budget gamma")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -160,6 +165,39 @@ def main() -> int:
            "verify_latency_ms": round(ms_per_step, 4), "algorithmic_bytes": algo_bytes,
            "achieved_hbm_GBps": round(achieved, 1), "frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
            "roofline": roofline, "kernels": kernels}
+
+    if args.k_sweep:
+        from paper_2503_00784_amd import budget
+        curve = []
+        for kk in [int(t) for t in args.k_sweep.split(",") if t]:
+            qk, tk, uk = inputs.make_draft(shape.vocab, 1, kk, seed=args.seed + 100 + kk)
+            d_tk, d_qk, d_uk = dev(tk), dev(qk), dev(uk)
+
+            def step_k():
+                eng.set_prefix_len(P)
+                eng.verify(d_tk, d_qk, d_uk)
+
+            with torch.cuda.stream(stream):
+                for _ in range(3):
+                    step_k()
+                stream.synchronize()
+                gk = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gk, stream=stream):
+                    step_k()
+                for _ in range(10):
+                    gk.replay()
+                stream.synchronize()
+                t5 = time.perf_counter()
+                for _ in range(50):
+                    gk.replay()
+                stream.synchronize()
+                curve.append((kk, (time.perf_counter() - t5) * 1e3 / 50))
+        out["k_sweep"] = {"n_seq": 1, "prefix_len": P, "ms_by_k": {str(kk): round(ms, 4) for kk, ms in curve}}
+        if args.draft_step_ms > 0:
+            out["k_sweep"]["draft_step_ms"] = args.draft_step_ms
+            out["k_sweep"]["cost_coefficient_by_k"] = {str(kk): round(c, 2)
+                                                       for kk, c in budget.cost_coefficient(curve, args.draft_step_ms).items()}
+            out["k_sweep"]["draft_budget"] = budget.draft_budget(curve, args.draft_step_ms)
 
     if not args.no_cpu_baseline:
         from oracle import duo_oracle as O

@@ -188,6 +188,47 @@ int duo_spec_sample(const float *logits, const float *root_logits, int vocab,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Alg. 2 in the form the paper lists it, for one round of the pipelined loop of Alg. 1: the pass
+ * scores the l tokens that the previous round appended without verifying them (the unverified
+ * suffix), then
+ *   - verifies them in order (accept token m iff u_m * q_m(t) < p_m(t)); at the first rejection the
+ *     token is replaced by a draw from norm(max(0, p_m - q_m)) and everything after it is dropped;
+ *   - if all l were accepted, judges ONLY THE FIRST TOKEN of each of s new draft sequences, in index
+ *     order, against the target distribution after the last scored token, replacing that
+ *     distribution by its normalised residual after every rejection; the first accepted sequence is
+ *     taken whole (its first token verified, the rest becoming the next round's unverified suffix);
+ *   - if none is accepted, draws one token from the final residual.
+ * Inputs (device): unverified_tokens int32 [l]; unverified_probs fp32 [l][vocab] (the draft
+ * distributions they were drawn from); uniforms fp32 [l + 1]: u_0 .. u_{l-1} and the uniform of the
+ * final draw; first_tokens int32 [s], first_probs fp32 [s][vocab], uniforms_first fp32 [s] (s may be
+ * 0: then the pointers may be NULL and the last case applies).  call->n must be 1, call->k = l,
+ * call->select_mode must hold a valid value and is otherwise ignored, root_token / host_prefix_len as in
+ * duo_verify; s <= DUO_MAX_ROWS.
+ * Outputs: out->accept_len[0] = number of accepted suffix tokens a (0..l); out->commit =
+ * {index of the accepted new sequence or -1, a, emitted token or -1 when a sequence was accepted,
+ * new prefix length P + R + a}; out->next_token[0] = the emitted token or -1.  The keys/values of
+ * the accepted suffix tokens stay where the pass wrote them (slots P + R ..) and *prefix_len becomes
+ * P + R + a.  An accepted sequence is not in the cache yet: the next round passes its first token as
+ * root_token and the rest as the unverified suffix.
+ */
+int duo_verify_deferred(const duo_model_config *cfg, const duo_weights *w, duo_kv_cache *cache,
+                        const int32_t *unverified_tokens, const float *unverified_probs, const float *uniforms,
+                        const int32_t *first_tokens, const float *first_probs, const float *uniforms_first,
+                        int s, const duo_call *call, duo_result *out,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The sampling half of duo_verify_deferred on logits the caller supplies (fp32 [R + l][vocab], row
+ * stride vocab; root_logits judge the first suffix token when call->root_token < 0).  No KV cache is
+ * touched; `workspace` needs duo_sample_workspace_bytes(vocab, 1, l) bytes.
+ */
+int duo_deferred_sample(const float *logits, const float *root_logits, int vocab,
+                        const int32_t *unverified_tokens, const float *unverified_probs, const float *uniforms,
+                        const int32_t *first_tokens, const float *first_probs, const float *uniforms_first,
+                        int s, const duo_call *call, duo_result *out,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * One skinny weight-streaming product, the building block of the target pass:
  * y[m][n] = sum_k x[m][k] * w[n][k]; x from duo_pack_activations (rows <= DUO_MAX_ROWS), w from
  * duo_pack_matrix (N x K, K % 32 == 0), y fp32 [rows][N] row-major.

@@ -22,7 +22,7 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
+           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
            "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
 PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "residual_reduce", "gate_up_swiglu", "down_proj", "lm_head",
@@ -83,6 +83,12 @@ def load() -> C.CDLL:
     lib.duo_sample_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     lib.duo_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Call),
                                     C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_verify_deferred.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(KVCache), C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                        C.POINTER(Call), C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_deferred_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_int, C.POINTER(Call), C.POINTER(Result), C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
     lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.duo_packed_elems.argtypes = [C.c_int, C.c_int]
     lib.duo_packed_elems.restype = C.c_size_t
@@ -91,8 +97,8 @@ def load() -> C.CDLL:
     lib.duo_pack_gate_up.argtypes = [C.POINTER(ModelConfig), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.duo_pack_activations.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     for name in ("duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-                 "duo_spec_sample", "duo_skinny_gemm", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
-                 "duo_pack_activations"):
+                 "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_pack_matrix",
+                 "duo_pack_qkv", "duo_pack_gate_up", "duo_pack_activations"):
         getattr(lib, name).restype = C.c_int
     lib.duo_profile_enable.argtypes = [C.c_int]
     lib.duo_profile_enable.restype = C.c_int
@@ -295,6 +301,23 @@ class VerifyEngine:
                                  C.byref(res), self.workspace.data_ptr(), self.ws_bytes, _stream_ptr())
         _check(rc, "duo_verify")
 
+    def verify_deferred(self, unverified_tokens, unverified_probs, uniforms, first_tokens=None, first_probs=None,
+                        uniforms_first=None, temperature: float = 1.0, root_token: int = -1, logits_out=None) -> None:
+        """Enqueue one round of Alg. 2 as listed (duo_verify_deferred) on torch's current stream.
+        unverified_tokens int32 [l], unverified_probs fp32 [l][V], uniforms fp32 [l+1]; first_tokens int32 [s],
+        first_probs fp32 [s][V], uniforms_first fp32 [s] (all three None for s = 0)."""
+        l = int(unverified_tokens.shape[0])
+        s_new = 0 if first_tokens is None else int(first_tokens.shape[0])
+        call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, int(root_token), self.host_prefix_len)
+        res = Result(self.accept_len.data_ptr(), self.next_token.data_ptr(), self.commit.data_ptr(),
+                     self.status.data_ptr(), _ptr(logits_out))
+        rc = self.lib.duo_verify_deferred(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),
+                                          unverified_tokens.data_ptr(), unverified_probs.data_ptr(), uniforms.data_ptr(),
+                                          _ptr(first_tokens), _ptr(first_probs), _ptr(uniforms_first), s_new,
+                                          C.byref(call), C.byref(res), self.workspace.data_ptr(), self.ws_bytes,
+                                          _stream_ptr())
+        _check(rc, "duo_verify_deferred")
+
     def results(self, n: int) -> Dict[str, object]:
         """Synchronise and fetch the outputs of the last verify call."""
         self.torch.cuda.synchronize()
@@ -331,6 +354,37 @@ def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temper
     c = commit.cpu().numpy()
     return {"accept_len": accept_len.cpu().numpy(), "next_token": next_token.cpu().numpy(), "selected": int(c[0]),
             "commit_len": int(c[1]), "commit_token": int(c[2]), "new_prefix_len": int(c[3]),
+            "status": int(status.cpu().numpy()[0])}
+
+
+def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, uniforms, first_tokens=None,
+                    first_probs=None, uniforms_first=None, temperature: float = 1.0, has_root: bool = False,
+                    prefix_len: int = 0) -> Dict[str, object]:
+    """duo_deferred_sample on device tensors; returns host results."""
+    import torch
+    lib = load()
+    l = int(unverified_tokens.shape[0])
+    s_new = 0 if first_tokens is None else int(first_tokens.shape[0])
+    vocab = logits.shape[-1]
+    nbytes = C.c_size_t(0)
+    _check(lib.duo_sample_workspace_bytes(vocab, 1, l, C.byref(nbytes)), "duo_sample_workspace_bytes")
+    dev = logits.device
+    ws = torch.empty(nbytes.value, dtype=torch.uint8, device=dev)
+    accept_len = torch.zeros(1, dtype=torch.int32, device=dev)
+    next_token = torch.zeros(1, dtype=torch.int32, device=dev)
+    commit = torch.zeros(4, dtype=torch.int32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, 0 if has_root else -1, int(prefix_len))
+    res = Result(accept_len.data_ptr(), next_token.data_ptr(), commit.data_ptr(), status.data_ptr(), None)
+    rc = lib.duo_deferred_sample(logits.data_ptr(), _ptr(root_logits), vocab, unverified_tokens.data_ptr(),
+                                 unverified_probs.data_ptr(), uniforms.data_ptr(), _ptr(first_tokens), _ptr(first_probs),
+                                 _ptr(uniforms_first), s_new, C.byref(call), C.byref(res), ws.data_ptr(), nbytes.value,
+                                 _stream_ptr())
+    _check(rc, "duo_deferred_sample")
+    torch.cuda.synchronize()
+    c = commit.cpu().numpy()
+    return {"accept_len": int(accept_len.cpu().numpy()[0]), "next_token": int(next_token.cpu().numpy()[0]),
+            "selected": int(c[0]), "commit_len": int(c[1]), "commit_token": int(c[2]), "new_prefix_len": int(c[3]),
             "status": int(status.cpu().numpy()[0])}
 
 

@@ -453,6 +453,85 @@ int duo_spec_sample(const float* logits, const float* root_logits, int vocab, co
     return hip_ok(hipGetLastError(), "duo_spec_sample launch");
 }
 
+// checks shared by the two deferred entry points
+static int check_deferred(const duo_call* call, int vocab, const int32_t* first_tokens, const float* first_probs,
+                          const float* uniforms_first, int s) {
+    int rc = check_call(call, vocab);
+    if (rc) return rc;
+    if (call->n != 1) return DUO_ERR_SHAPE;
+    if (s < 0 || s > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
+    if (s > 0 && (!first_tokens || !first_probs || !uniforms_first)) return DUO_ERR_NULL;
+    return DUO_OK;
+}
+
+static void enqueue_deferred_sampling(const SampleArgs& sa, const DeferredArgs& da, hipStream_t s) {
+    prof(DUO_PROF_SAMPLE, s);
+    DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, 1, STATS_SPLIT), dim3(256), s, sa);
+    prof(DUO_PROF_SAMPLE, s);
+    DUO_LAUNCH(sample_deferred_kernel, dim3(1), dim3(SAMPLE_THREADS), s, sa, da);
+}
+
+int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* cache,
+                        const int32_t* unverified_tokens, const float* unverified_probs, const float* uniforms,
+                        const int32_t* first_tokens, const float* first_probs, const float* uniforms_first, int s_new,
+                        const duo_call* call, duo_result* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if ((rc = check_weights(cfg, w))) return rc;
+    if (!cache || !cache->k || !cache->v || !cache->prefix_len || !unverified_tokens || !unverified_probs || !uniforms ||
+        !workspace)
+        return DUO_ERR_NULL;
+    if ((rc = check_deferred(call, cfg->vocab, first_tokens, first_probs, uniforms_first, s_new))) return rc;
+    if ((rc = check_result(out))) return rc;
+    const int R = call->root_token >= 0 ? 1 : 0;
+    if (!R && !cache->root_logits) return DUO_ERR_NULL;
+    const int M = R + call->k;
+    if ((long long)call->host_prefix_len + M > cfg->max_seq) return DUO_ERR_CAPACITY;
+    if (!aligned16(cache->k) || !aligned16(cache->v) || !aligned16(workspace) || !aligned16(unverified_probs) ||
+        (out->logits_out && !aligned16(out->logits_out)))
+        return DUO_ERR_ALIGN;
+    const Workspace ws = carve(*cfg, M, workspace);
+    if (workspace_bytes < ws.total) return DUO_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
+    const RowPlan plan{call->host_prefix_len, R, 1, call->k, M};
+    float* logits = out->logits_out ? out->logits_out : ws.logits;
+    enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s);
+    SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, 1, call->k, R, call->host_prefix_len,
+                  (double)call->temperature, unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run,
+                  out->accept_len, out->next_token, out->commit, out->status};
+    enqueue_deferred_sampling(sa, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, cache->prefix_len}, s);
+    return hip_ok(hipGetLastError(), "duo_verify_deferred launch");
+}
+
+int duo_deferred_sample(const float* logits, const float* root_logits, int vocab, const int32_t* unverified_tokens,
+                        const float* unverified_probs, const float* uniforms, const int32_t* first_tokens,
+                        const float* first_probs, const float* uniforms_first, int s_new, const duo_call* call,
+                        duo_result* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (vocab < 2) return DUO_ERR_SHAPE;
+    int rc = check_deferred(call, vocab, first_tokens, first_probs, uniforms_first, s_new);
+    if (rc) return rc;
+    if ((rc = check_result(out))) return rc;
+    const int R = call->root_token >= 0 ? 1 : 0;
+    if (!logits || !unverified_tokens || !unverified_probs || !uniforms || !workspace || (!R && !root_logits))
+        return DUO_ERR_NULL;
+    if (!aligned16(workspace)) return DUO_ERR_ALIGN;
+    if (workspace_bytes < sample_ws_bytes(vocab)) return DUO_ERR_WORKSPACE;
+    Workspace ws{};
+    size_t off = 0;
+    carve_sampler(static_cast<char*>(workspace), off, vocab, ws);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
+    SampleArgs sa{logits, vocab, root_logits, vocab, 1, call->k, R, call->host_prefix_len, (double)call->temperature,
+                  unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
+                  out->commit, out->status};
+    enqueue_deferred_sampling(sa, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, nullptr}, s);
+    return hip_ok(hipGetLastError(), "duo_deferred_sample launch");
+}
+
 int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, int N, int K, void* hip_stream) {
     if (!x || !w || !y) return DUO_ERR_NULL;
     if (rows < 1 || rows > DUO_MAX_ROWS || N < 1 || K < 32 || K % 32) return DUO_ERR_SHAPE;

@@ -9,6 +9,8 @@
 //                         correction token from norm(max(0, p - q)) or the bonus token from p
 //   sample_paper_kernel   the sequential first-token rule over the n sequences, with the
 //                         running distribution replaced by its residual after each rejection
+//   sample_deferred_kernel  Alg. 2 as listed: verify the unverified suffix, then judge only the first
+//                         tokens of the new sequences
 //   commit_kernel         picks the sequence to keep, moves its accepted K/V next to the prefix
 #pragma once
 #include "duo_common.h"
@@ -236,6 +238,31 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArg
     }
 }
 
+// The sequential first-token rule of Alg. 2 over s candidate sequences: p_run (already filled with the
+// judging distribution) is tested against each first token in index order and replaced by its normalised
+// residual after every rejection.  Returns the accepted sequence or -1 (same value in every thread).
+// Candidate i has token first_tok[i * tok_stride], draft distribution first_q + i * q_stride, uniform
+// first_u[i * u_stride].
+__device__ int sequential_first_tokens(double* p_run, int V, int s, const int32_t* first_tok, int tok_stride,
+                                       const float* first_q, size_t q_stride, const float* first_u, int u_stride,
+                                       double* sm_d) {
+    const int tid = threadIdx.x;
+    for (int i = 0; i < s; ++i) {
+        int t = first_tok[i * tok_stride];
+        t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+        const float* qrow = first_q + (size_t)i * q_stride;
+        const double lhs = (double)first_u[i * u_stride] * (double)qrow[t];
+        if (lhs < p_run[t]) return i;  // same value in every thread
+        double sum = 0.0;
+        for (int v = tid; v < V; v += SAMPLE_THREADS) sum += fmax(p_run[v] - (double)qrow[v], 0.0);
+        const double Rm = block_sum_d(sum, sm_d);
+        if (Rm > 0.0)
+            for (int v = tid; v < V; v += SAMPLE_THREADS) p_run[v] = fmax(p_run[v] - (double)qrow[v], 0.0) / Rm;
+        __syncthreads();
+    }
+    return -1;
+}
+
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs a) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
@@ -247,22 +274,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
         for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
     }
     __syncthreads();
-    int sel = -1;
-    for (int i = 0; i < a.n; ++i) {
-        const int t = a.token(i, 0);
-        const float* qrow = a.q + (size_t)i * a.k * a.V;
-        const double lhs = (double)a.u[i * (a.k + 1)] * (double)qrow[t];
-        if (lhs < a.p_run[t]) {  // same value in every thread
-            sel = i;
-            break;
-        }
-        double s = 0.0;
-        for (int v = tid; v < a.V; v += SAMPLE_THREADS) s += fmax(a.p_run[v] - (double)qrow[v], 0.0);
-        const double Rm = block_sum_d(s, sm_d);
-        if (Rm > 0.0)
-            for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = fmax(a.p_run[v] - (double)qrow[v], 0.0) / Rm;
-        __syncthreads();
-    }
+    const int sel = sequential_first_tokens(a.p_run, a.V, a.n, a.tokens, a.k, a.q, (size_t)a.k * a.V, a.u, a.k + 1, sm_d);
     int acc_len = 0, tok;
     if (sel < 0) {
         const double* pr = a.p_run;
@@ -282,6 +294,54 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
         a.commit[1] = acc_len;
         a.commit[2] = tok;
         a.commit[3] = a.P + a.R + acc_len;
+    }
+}
+
+// Alg. 2 as listed (one round of the pipelined loop): the k = l rows of the single sequence are the
+// unverified suffix; after it, only the first tokens of s new sequences are judged.  One workgroup.
+struct DeferredArgs {
+    const int32_t* first_tokens;  // [s]
+    const float* first_probs;     // [s][V]
+    const float* uniforms_first;  // [s]
+    int s;
+    int32_t* prefix_len;  // device prefix length to advance, may be NULL (sampling only)
+};
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleArgs a, DeferredArgs d) {
+    __shared__ double sm_d[16];
+    __shared__ int sm_i[4 + 16];
+    const int tid = threadIdx.x;
+    if (tid < d.s && a.status) {
+        const int t = d.first_tokens[tid];
+        if (t < 0 || t >= a.V) atomicOr(a.status, 1);
+    }
+    accept_flags(a, 0, 0);
+    const int acc_len = leading_accepts(a, 0, 0);
+    int sel = -1, tok = -1;
+    if (acc_len < a.k) {
+        tok = finish_token(a, 0, acc_len, sm_d, sm_i);  // residual draw at the first rejection
+    } else {
+        const float* row = a.judge_row(0, a.k);  // the distribution after the last scored token
+        double zmax, Z;
+        merged_stats(a, 0, a.k, zmax, Z);
+        for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
+        __syncthreads();
+        sel = sequential_first_tokens(a.p_run, a.V, d.s, d.first_tokens, 1, d.first_probs, (size_t)a.V, d.uniforms_first, 1,
+                                      sm_d);
+        if (sel < 0) {
+            const double* pr = a.p_run;
+            auto pw = [=](int v) { return pr[v]; };
+            tok = block_inverse_cdf(pw, a.V, (double)a.u[a.k], sm_d, sm_i);
+        }
+    }
+    if (tid == 0) {
+        a.accept_len[0] = acc_len;
+        a.next_token[0] = tok;
+        a.commit[0] = sel;
+        a.commit[1] = acc_len;
+        a.commit[2] = tok;
+        a.commit[3] = a.P + a.R + acc_len;
+        if (d.prefix_len) *d.prefix_len = a.P + a.R + acc_len;
     }
 }
 

@@ -1,0 +1,143 @@
+"""GPU parity of the deferred form (Alg. 2 as the paper lists it): duo_deferred_sample on the oracle's own
+logits, bit-exact against oracle.duodec_verify_alg2, and duo_verify_deferred end to end."""
+import numpy as np
+import pytest
+
+from oracle import duo_oracle as O
+from paper_2503_00784_amd import inputs
+from tests.gpu_util import logits_close, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2503_00784_amd import binding
+    binding.load()
+    return binding
+
+
+def _oracle_outcome(x, x_tilde, judge_logits, p_n_logits, q_unv, u_unv, first_tok, first_q, u_first, r_final, T):
+    """duodec_verify_alg2 on fp32 logits; returns (x_new, x_tilde_new)."""
+    p_unv = [O.target_probs(judge_logits[m], T) for m in range(len(x_tilde))]
+    p_n = O.target_probs(p_n_logits, T)
+    xhat = [[int(t)] for t in first_tok]  # only the first token of a new sequence matters to the verifier
+    return O.duodec_verify_alg2(list(x) + list(x_tilde), list(x_tilde), [q.astype(np.float64) for q in q_unv], p_unv, p_n,
+                                xhat, [q.astype(np.float64) for q in first_q], [float(u) for u in u_unv],
+                                [float(u) for u in u_first], float(r_final))
+
+
+def _gpu_outcome(x, x_tilde, got, first_tok):
+    """The same pair (x_new, x_tilde_new) from the library's outputs."""
+    a = got["accept_len"]
+    assert got["commit_len"] == a
+    if a < len(x_tilde):
+        assert got["selected"] == -1
+        return list(x) + list(x_tilde[:a]) + [got["next_token"]], []
+    if got["selected"] >= 0:
+        assert got["next_token"] == -1 and got["commit_token"] == -1
+        return list(x) + list(x_tilde) + [int(first_tok[got["selected"]])], []
+    return list(x) + list(x_tilde) + [got["next_token"]], []
+
+
+def _case(V, l, s, seed, scenario, peaked):
+    g = np.random.default_rng(seed * 977 + l * 31 + s)
+    scale = 4.0 if peaked else 1.28
+    root = g.normal(0, scale, V).astype(np.float32)
+    logits = g.normal(0, scale, (l, V)).astype(np.float32)
+    q, toks, u = inputs.make_draft(V, 1, l, seed=seed)
+    fq, ftoks, fu = inputs.make_draft(V, max(s, 1), 1, seed=seed + 50)
+    fq, ftoks, fu = fq[:s, 0], ftoks[:s, 0].copy(), fu[:s, 0].copy()
+    u = u[0].copy()  # [l + 1]
+    toks = toks[0].copy()
+    if scenario == "accept_all":      # every suffix token passes (u = 0 accepts whenever p(t) > 0)
+        u[:l] = 0.0
+    elif scenario == "second_new":    # suffix passes, first new sequence likely fails, second passes
+        u[:l] = 0.0
+        if s >= 2:
+            fu[0], fu[1] = 0.999, 0.0
+    elif scenario == "none_new":      # suffix passes, every new sequence is tested with a large uniform
+        u[:l] = 0.0
+        fu[:] = 0.999
+    elif scenario == "argmax":        # suffix tokens are the target's argmax: high acceptance without forcing u
+        for m in range(l):
+            toks[m] = int(np.argmax(root if m == 0 else logits[m - 1]))
+    return root, logits, q[0], toks, u, fq, ftoks, fu
+
+
+@pytest.mark.parametrize("V,l,s", [(4099, 5, 3), (32000, 8, 2), (32000, 1, 1), (50, 3, 0), (128256, 16, 4), (1031, 2, 8)])
+@pytest.mark.parametrize("scenario", ["random", "accept_all", "second_new", "none_new", "argmax"])
+def test_deferred_sampler_bit_exact_on_identical_logits(B, V, l, s, scenario):
+    branches = set()
+    for seed in range(2):
+        say(f"deferred sampler V={V} l={l} s={s} scenario={scenario} seed={seed}")
+        T = 0.9 if seed == 1 else 1.0
+        root, logits, q, toks, u, fq, ftoks, fu = _case(V, l, s, seed, scenario, peaked=(scenario == "argmax"))
+        judge = [root] + [logits[m] for m in range(l - 1)]
+        x = [1, 2, 3]
+        ref = _oracle_outcome(x, toks.tolist(), judge, logits[l - 1], q, u[:l], ftoks, fq, fu, u[l], T)
+        got = B.deferred_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u),
+                                to_dev(ftoks) if s else None, to_dev(fq) if s else None, to_dev(fu) if s else None,
+                                temperature=T, has_root=False, prefix_len=3)
+        assert got["status"] == 0
+        assert got["new_prefix_len"] == 3 + got["accept_len"]
+        out = _gpu_outcome(x, toks.tolist(), got, ftoks)
+        assert out[0] == ref[0], (out, ref, got)
+        branches.add("reject" if got["accept_len"] < l else ("sequence" if got["selected"] >= 0 else "final"))
+    say(f"  branches taken: {sorted(branches)}")
+    if scenario == "none_new" and s == 0:
+        assert branches == {"final"}
+
+
+def test_deferred_sampler_flags_out_of_range_first_token(B):
+    root, logits, q, toks, u, fq, ftoks, fu = _case(50, 2, 2, 0, "accept_all", False)
+    ftoks[1] = 50
+    got = B.deferred_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u), to_dev(ftoks), to_dev(fq),
+                            to_dev(fu))
+    assert got["status"] & B.STATUS_TOKEN_CLAMPED
+
+
+@pytest.mark.parametrize("l,s,root_token,scenario", [(6, 3, 11, "accept_all"), (9, 2, -1, "random"), (4, 0, 7, "none_new")])
+def test_verify_deferred_end_to_end(B, l, s, root_token, scenario):
+    """MID shape (GQA, ragged vocabulary): the fused call's logits against the oracle's forward pass, its decision
+    against Alg. 2 evaluated on those same logits, and the cache state it leaves."""
+    import torch
+    shape = inputs.MID
+    V = shape.vocab
+    w = inputs.make_weights(shape, seed=3, threads=16)
+    oshape = O.shape_from(shape)
+    eng = B.VerifyEngine(shape, w, 192)
+    prefix = inputs.make_prefix_ids(shape, 61, seed=3)
+    eng.prefill(prefix.tolist())
+    cache = O.prefill(oshape, w, prefix.tolist(), 192)
+    P = cache.prefix_len
+    _, _, q, toks, u, fq, ftoks, fu = _case(V, l, s, 1, scenario, False)
+    R = 1 if root_token >= 0 else 0
+    say(f"deferred end to end l={l} s={s} root={root_token} scenario={scenario}")
+    lg = torch.empty((R + l, V), dtype=torch.float32, device="cuda")
+    eng.verify_deferred(to_dev(toks), to_dev(q), to_dev(u), to_dev(ftoks) if s else None, to_dev(fq) if s else None,
+                        to_dev(fu) if s else None, root_token=root_token, logits_out=lg)
+    got = eng.results(1)
+    assert got["status"] == 0
+    gl = lg.cpu().numpy()
+    ol = O.verify_forward(oshape, w, cache, toks.reshape(1, l), root_token=root_token)
+    ok, max_abs, worst = logits_close(gl, ol)
+    say(f"  logits max abs err {max_abs:.3e} (worst err/bound {worst:.3f})")
+    assert ok
+    # decision: Alg. 2 on the logits the library itself produced (the sampler is bit-exact on identical logits)
+    root_logits = eng.root_logits.cpu().numpy()
+    judge = [gl[0] if R else root_logits] + [gl[R + m] for m in range(l - 1)]
+    ref = _oracle_outcome([0], toks.tolist(), judge, gl[R + l - 1], q, u[:l], ftoks, fq, fu, u[l], 1.0)
+    res = {"accept_len": int(got["accept_len"][0]), "next_token": int(got["next_token"][0]), "selected": got["selected"],
+           "commit_len": got["commit_len"], "commit_token": got["commit_token"]}
+    out = _gpu_outcome([0], toks.tolist(), res, ftoks)
+    assert out[0] == ref[0], (out, ref, got)
+    a = res["accept_len"]
+    assert got["new_prefix_len"] == P + R + a == got["device_prefix_len"]
+    # cache: prefix + root row + accepted suffix rows equal the oracle's rows (bf16 storage, one-ulp flips allowed)
+    kg, vg = eng.cache_to_host()
+    upto = P + R + a
+    kd = np.abs(O.bf16_bits_to_f64(kg[:, :, :upto]) - cache.k[:, :, :upto]).max()
+    vd = np.abs(O.bf16_bits_to_f64(vg[:, :, :upto]) - cache.v[:, :, :upto]).max()
+    say(f"  accepted {a} of {l}; cache max abs diff k {kd:.3e} v {vd:.3e}")
+    assert kd <= 0.07 and vd <= 0.07
