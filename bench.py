@@ -48,7 +48,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the verify step of one model replica); "
-              f"--gpus {args.gpus} is not supported. See DESIGN.md for how the path would shard.", file=sys.stderr)
+              f"--gpus {args.gpus} is not supported.", file=sys.stderr)
         return 2
 
     import numpy as np
