@@ -154,13 +154,13 @@ void launch_attention(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_
     }
 }
 
-// A projection whose epilogue finishes the rows (QKV, gate/up, LM head).  Up to eight rows, and up to sixteen
-// when the matrix has few bands, every wave streams its own bands; beyond that the waves of a workgroup
-// share the activation operand through LDS.
+// A projection whose epilogue finishes the rows (QKV, gate/up, LM head).  Up to eight rows every wave streams
+// its own bands and reads the activations itself; beyond that the waves of a workgroup share the activation
+// operand through LDS.
 template <int NT, class Epi>
 void launch_projection(int M, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
                        hipStream_t s) {
-    if (M <= 8 || (M <= 16 && tiles < 600)) {
+    if (M <= 8) {
         launch_gemm_rows<NT>(M, true, X, W, K, tiles, rsc, epi, s);
         return;
     }

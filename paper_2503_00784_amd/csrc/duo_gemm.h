@@ -201,76 +201,104 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 
 // Variant for more than eight rows (M = 9..80, i.e. MH = 1..5 tiles of hi rows plus as many of lo rows).
 // With that many rows the activation operand is no longer negligible next to the weights: every wave of the
-// kernel above re-reads all 2*MH tiles of it per K step.  Here a workgroup of NG x NK waves shares it through
-// LDS: the waves copy the operand tiles of a round (NK * AG K steps) into one of two staging buffers while
-// they compute on the other (global memory -> registers one round, registers -> LDS the next), NG waves side by side take NG different groups of NT weight bands (each weight
-// byte still goes from HBM straight into one wave's registers, PF steps ahead), and NK waves split the
-// round's steps between them.  hi and lo products accumulate into the same registers.  The grid's y
-// dimension splits K across workgroups for matrices with few bands (partial results, see EpiStoreF32).
-template <int MH, int NT, int NG, int NK, int PF, int AG, class Epi>
-__global__ __launch_bounds__(NG * NK * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W, int K,
-                                                                  int split_steps, int ntiles, int quads, RowScale rsc,
-                                                                  Epi epi) {
-    constexpr int MT = 2 * MH, NWV = NG * NK, NTH = NWV * 64;
-    constexpr int RS = NK * AG;        // K steps per round
-    constexpr int BUF = RS * MT * 64;  // 16-byte chunks per staging buffer
-    constexpr int CPT = (BUF + NTH - 1) / NTH;
-    constexpr int RED = NK > 1 ? NWV * MH * NT * 64 : 0;
-    constexpr int LDSN = 2 * BUF > RED ? 2 * BUF : RED;
-    static_assert(PF == 2 * AG && AG % 2 == 0, "the weight slots cover two rounds of an even number of steps");
-    // dependent MFMAs on one accumulator need other MFMAs in between: few tiles -> separate lo accumulators
-    constexpr bool SEP = MH * NT < 4;
+// kernel above re-reads all 2*MH tiles of it per K step.  Here the NG consumer waves of a workgroup share it
+// through LDS, each taking its own group of NT weight bands (every weight byte still goes from HBM straight
+// into one wave's registers, PF steps ahead); hi and lo products accumulate into the same registers (for few
+// tiles into separate ones, so that dependent MFMAs on one accumulator have others in between), and the
+// epilogue runs straight from the accumulators: a lane's quad is an output quad.  The grid's y dimension
+// splits K across workgroups for matrices with few bands (partial results, see EpiStoreF32).  All loads of
+// the main loop are unconditional with clamped indices and invalid steps multiply by zero: no branches, so
+// the counted waits stay exact.
+//
+// One extra wave per workgroup does nothing but move the activation operand:
+// wave NG copies the operand tiles of round r + 2 from global memory straight into a three-deep ring of
+// LDS buffers (16-byte global -> LDS loads, no registers, no LDS store instructions) while the NG consumer
+// waves stream their weight bands and compute on round r.  The consumers' memory counter then tracks the
+// weight stream alone, PF steps ahead, and their registers hold weights and accumulators only.
+// One barrier per round (AG K steps) hands a filled buffer over and takes a drained one back.
+template <int MH, int NT, int NG, int PF, int AG, class Epi>
+__global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W,
+                                                                     int K, int split_steps, int ntiles, int quads,
+                                                                     RowScale rsc, Epi epi) {
+    constexpr int MT = 2 * MH, NTH = (NG + 1) * 64;
+    constexpr int BUF = AG * MT * 64;  // 16-byte chunks per ring buffer (one round)
+    constexpr int NBUF = 3;
+    constexpr int L = AG * MT;  // global -> LDS loads per round
+    constexpr int U = PF / AG;  // rounds per turn of the weight slots
+    static_assert(PF % AG == 0 && AG % 2 == 0 && L <= 63, "slots cover whole rounds; a round's loads fit the memory counter");
+    constexpr bool SEP = MH * NT < 4;  // few tiles: separate lo accumulators
     constexpr int MA = SEP ? MT : MH;
-    __shared__ u32x4 lds[LDSN];
+    __shared__ u32x4 lds[NBUF * BUF];
     __shared__ float row_scale[MH * 16];
 
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar, see above
-    const int ng = wave % NG, nk = wave / NG;
-    const int tile_raw = blockIdx.x * NG + ng;
-    const bool live = tile_raw < ntiles;
-    const int tile = live ? tile_raw : ntiles - 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar: MFMA ignores EXEC
     const int steps = K >> 5;
     const int k0 = blockIdx.y * split_steps;
     const int ns = min(steps - k0, split_steps);  // K steps of this split (the host makes it positive)
-    const int rounds = (ns + RS - 1) / RS;
+    const int rounds = (ns + AG - 1) / AG;
+    const int rounds_run = (rounds + U - 1) / U * U;  // what the consumers' unrolled loop executes
+    const u32x4* xg = reinterpret_cast<const u32x4*>(X) + (size_t)k0 * MT * 64 + lane;
 
+    if (rsc.full) {
+        for (int m = threadIdx.x; m < quads * 4; m += NTH) row_scale[m] = 1.0f / sqrtf(rsc.full[m] * rsc.inv_d + rsc.eps);
+    } else if (rsc.part) {
+        const int nrows = quads * 4;
+        f32x4 rsv[RowScale::MAXQ];
+        for (int r0 = wave * 8; r0 < nrows; r0 += (NG + 1) * 8) {
+            rsc.load(rsv, r0, nrows, lane);
+            rsc.reduce(rsv, row_scale, r0, nrows, lane);
+        }
+    }
+
+    if (wave == NG) {
+        // ---- producer: round r goes to ring buffer r % 3; steps past the end re-read the last step
+        auto issue = [&](int r) {
+            const int b = r % NBUF;
+#pragma unroll
+            for (int i = 0; i < L; ++i) {
+                int st = r * AG + i / MT;
+                st = st < ns ? st : ns - 1;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xg + ((size_t)st * MT + i % MT) * 64),
+                                                 (__attribute__((address_space(3))) void*)(lds + b * BUF + i * 64), 16, 0, 0);
+            }
+        };
+        // The barriers of this wave are bare s_barrier instructions behind a counted wait: a fence here would
+        // wait for ALL outstanding loads, including the round just requested.  vmcnt(L) = everything but the
+        // youngest round has landed in LDS (expcnt and lgkmcnt fields left at their maxima).
+        constexpr int WAIT_ALL_BUT_ONE_ROUND = (L & 15) | ((L >> 4) << 14) | (7 << 4) | (15 << 8);
+        issue(0);
+        issue(1);
+        __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_ROUND & ~(15 << 8));  // and lgkmcnt(0): this wave's row scales are written
+        __builtin_amdgcn_s_barrier();
+        for (int r = 0; r < rounds_run; ++r) {
+            issue(r + 2);  // its buffer was drained in round r - 1
+            __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_ROUND);  // round r + 1 has landed
+            __builtin_amdgcn_s_barrier();
+        }
+        return;
+    }
+
+    // ---- consumers
+    const int tile_raw = blockIdx.x * NG + wave;
+    const bool live = tile_raw < ntiles;
+    const int tile = live ? tile_raw : ntiles - 1;
     const u16* wp[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) wp[t] = W + ((size_t)(tile * NT + t) * steps + k0) * 512 + lane * 8;
-    const u32x4* xg = reinterpret_cast<const u32x4*>(X) + (size_t)k0 * MT * 64;
-
     f32x4 acc[MA][NT];
 #pragma unroll
     for (int m = 0; m < MA; ++m)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
     bf16x8 bb[PF][NT];
-    u32x4 sreg[2][CPT];  // operand chunks on their way from global memory to LDS (rounds r + 1 and r + 2)
-    bf16x8 af[2][MT];    // operand tiles of the current and the next step
-    // Every load below is unconditional, with indices past the end clamped to the last step, and invalid
-    // steps multiply by zero: the main loop has no branches, so the counted waits stay exact.
-    // i-th step of this wave: round i / AG, position nk * AG + i % AG in it
-    auto w_load = [&](int p, int i) {
-        int ls = (i / AG) * RS + nk * AG + (i % AG);
-        ls = ls < ns ? ls : ns - 1;
+    bf16x8 af[2][MT];
+    auto w_load = [&](int p, int i) {  // i-th K step, clamped
+        const int ls = i < ns ? i : ns - 1;
 #pragma unroll
         for (int t = 0; t < NT; ++t) bb[p][t] = load_frag(wp[t] + (size_t)ls * 512);
     };
-    // chunk q of this thread in round r: global memory -> register, and register -> staging buffer b
-    auto a_load = [&](int set, int q, int r) {
-        const int ch = threadIdx.x + q * NTH;
-        if (BUF % NTH == 0 || ch < BUF) {
-            const int st = r * RS + ch / (MT * 64);
-            sreg[set][q] = xg[st < ns ? (size_t)r * BUF + ch : (size_t)(ns - 1) * MT * 64 + ch % (MT * 64)];
-        }
-    };
-    auto a_store = [&](int set, int q, int b) {
-        const int ch = threadIdx.x + q * NTH;
-        if (BUF % NTH == 0 || ch < BUF) lds[b * BUF + ch] = sreg[set][q];
-    };
-    auto a_frags = [&](int slot, int b, int w) {  // this wave's w-th step of the round staged in buffer b
-        const u32x4* ab = lds + b * BUF + (nk * AG + w) * MT * 64 + lane;
+    auto a_frags = [&](int slot, int r, int w) {  // step w of round r
+        const u32x4* ab = lds + (r % NBUF) * BUF + w * MT * 64 + lane;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             Frag8 f;
@@ -278,56 +306,26 @@ __global__ __launch_bounds__(NG * NK * 64) void gemm_wide_kernel(const u16* __re
             af[slot][mt] = f.v;
         }
     };
-
     typename Epi::Pre pre;
-    const int first_mh = NK > 1 ? nk : 0;  // the first row tile this wave finishes
-    const bool has_pre = live && first_mh < MH && first_mh * 4 + (lane >> 4) < quads;
-    if (has_pre) epi.prefetch(tile, first_mh * 4 + (lane >> 4), lane & 15, pre);
-#pragma unroll
-    for (int q = 0; q < CPT; ++q) a_load(0, q, 0);
+    const bool has_pre = live && (lane >> 4) < quads;
+    if (has_pre) epi.prefetch(tile, lane >> 4, lane & 15, pre);
 #pragma unroll
     for (int p = 0; p < PF; ++p) w_load(p, p);
     __builtin_amdgcn_sched_barrier(0);
-    if (rsc.full) {
-        for (int m = threadIdx.x; m < quads * 4; m += NTH) row_scale[m] = 1.0f / sqrtf(rsc.full[m] * rsc.inv_d + rsc.eps);
-    } else if (rsc.part) {
-        const int nrows = quads * 4;
-        f32x4 rsv[RowScale::MAXQ];
-        for (int r0 = wave * 8; r0 < nrows; r0 += NWV * 8) {
-            rsc.load(rsv, r0, nrows, lane);
-            rsc.reduce(rsv, row_scale, r0, nrows, lane);
-        }
-    }
-#pragma unroll
-    for (int q = 0; q < CPT; ++q) {
-        a_store(0, q, 0);
-        a_load(1, q, 1);
-    }
-#pragma unroll
-    for (int q = 0; q < CPT; ++q) a_load(0, q, 2);
-    __syncthreads();
+    __syncthreads();  // round 0 is in LDS, the row scales are written
     a_frags(0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    // Round r computes on staging buffer r % 2.  Spread over its steps, so that no step issues more than its
-    // share of memory instructions, the chunks of round r + 1 (requested two rounds ago, like the weights
-    // consumed now) move from registers into the other buffer and the chunks of round r + 3 are requested.
-    // The operand tiles of a step are read from LDS one step ahead of their MFMAs.
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int r0 = 0; r0 < rounds; r0 += 2) {
+    for (int r0 = 0; r0 < rounds; r0 += U) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int r = r0 + u;  // may be one past the last round: that round multiplies by zero
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + u;  // may run past the last round: those steps multiply by zero
 #pragma unroll
             for (int w = 0; w < AG; ++w) {
                 const int p = u * AG + w;
-#pragma unroll
-                for (int q = w * CPT / AG; q < (w + 1) * CPT / AG; ++q) {
-                    a_store((u + 1) & 1, q, (u + 1) & 1);
-                    a_load((u + 1) & 1, q, r + 3);
-                }
-                if (w + 1 < AG) a_frags((p + 1) & 1, u, w + 1);
-                const bool valid = r * RS + nk * AG + w < ns;
+                if (w + 1 < AG) a_frags((p + 1) & 1, r, w + 1);
+                const bool valid = r * AG + w < ns;
                 bf16x8 b[NT];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) b[t] = valid ? bb[p][t] : zero;
@@ -340,57 +338,30 @@ __global__ __launch_bounds__(NG * NK * 64) void gemm_wide_kernel(const u16* __re
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
                         acc[SEP ? MH + mh : mh][t] = mfma16(af[p & 1][MH + mh], b[t], acc[SEP ? MH + mh : mh][t]);
-                w_load(p, (r + 2) * AG + w);
+                w_load(p, (r + U) * AG + w);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            __syncthreads();
-            a_frags(0, (u + 1) & 1, 0);
+            __syncthreads();  // round r + 1 is in LDS; round r's buffer may be refilled
+            a_frags(0, r + 1, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 
-    // A lane's accumulator quad is rows 16*mh + 4*(lane/16) .. +3, column lane%16 of its tile: one output quad.
-    auto finish = [&](int mh, f32x4 (&v)[NT], bool use_pre) {
-        const int qi = mh * 4 + (lane >> 4);
-        if (qi < quads) {
-            if (rsc.part) {
+    if (live) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
-            }
-            epi.store(tile, qi, lane & 15, v, pre, use_pre);
-        }
-    };
-    if (NK == 1) {
-        if (live) {
-#pragma unroll
-            for (int mh = 0; mh < MH; ++mh) {
-                f32x4 v[NT];
-#pragma unroll
-                for (int t = 0; t < NT; ++t) v[t] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
-                finish(mh, v, mh == 0);
-            }
-        }
-    } else {
-        f32x4* red = reinterpret_cast<f32x4*>(lds);  // the last round's barrier has passed: staging is free
-#pragma unroll
-        for (int mh = 0; mh < MH; ++mh)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                red[((wave * MH + mh) * NT + t) * 64 + lane] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
-        __syncthreads();
-        if (live) {
-            for (int mh = nk; mh < MH; mh += NK) {  // K parts added in wave order
+        for (int mh = 0; mh < MH; ++mh) {
+            const int qi = mh * 4 + (lane >> 4);
+            if (qi < quads) {
                 f32x4 v[NT];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    f32x4 sum = red[((ng * MH + mh) * NT + t) * 64 + lane];
+                    v[t] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
+                    if (rsc.part) {
 #pragma unroll
-                    for (int kk = 1; kk < NK; ++kk) sum += red[(((kk * NG + ng) * MH + mh) * NT + t) * 64 + lane];
-                    v[t] = sum;
+                        for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
+                    }
                 }
-                finish(mh, v, mh == nk);
+                epi.store(tile, qi, lane & 15, v, pre, mh == 0);
             }
         }
     }
@@ -606,34 +577,32 @@ static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16*
 }
 
 // ---- more than eight rows: the LDS-shared variant ---------------------------------------------------
-// Launch shapes measured on the 7B projections (16..80 rows).  NG waves side by side; weight slots PF and
-// steps per round AG grow with the staging buffer that fits (2 * AG * 2*MH KiB of LDS).
+// Launch shapes measured on the 7B / 8B projections (16..80 rows): 8 weight slots, rounds of 4 K steps, and
+// as many consumer waves side by side as keeps the grid just within one workgroup per compute unit.
 constexpr int WIDE_MAX_SPLIT = 8;
+constexpr int WIDE_PF = 8, WIDE_AG = 4;
 
-template <int MH, int NT, int NG, int PF, int AG, class Epi>
+template <int MH, int NT, int NG, class Epi>
 static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int splits, const RowScale& rsc,
                                    const Epi& epi, hipStream_t s, int* splits_out) {
     const int steps = K >> 5;
     int split_steps = (steps + splits - 1) / splits;
-    split_steps = (split_steps + AG - 1) / AG * AG;  // whole rounds, so that only the last split has a ragged end
+    split_steps = (split_steps + WIDE_AG - 1) / WIDE_AG * WIDE_AG;  // whole rounds: only the last split has a ragged end
     const int S = (steps + split_steps - 1) / split_steps;
     if (splits_out) *splits_out = S;
-    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, 1, PF, AG, Epi>), dim3((tiles + NG - 1) / NG, S), dim3(NG * 64), s, X, W, K,
-               split_steps, tiles, quads, rsc, epi);
+    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, WIDE_PF, WIDE_AG, Epi>), dim3((tiles + NG - 1) / NG, S), dim3((NG + 1) * 64), s, X, W,
+               K, split_steps, tiles, quads, rsc, epi);
 }
 
 // Projections with many bands (QKV, gate/up, LM head): no K split, the epilogue finishes the rows.
 template <int MH, int NT, class Epi>
 static inline void launch_wide(const u16* X, const u16* W, int K, int tiles, int quads, const RowScale& rsc, const Epi& epi,
                                hipStream_t s) {
-    if constexpr (MH <= 2) {
-        if (tiles < 512) launch_wide_cfg<MH, NT, 2, 16, 8>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-        else if (MH == 1) launch_wide_cfg<MH, NT, 4, 8, 4>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-        else launch_wide_cfg<MH, NT, 4, 16, 8>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-    } else {
-        if (tiles < 512 && MH <= 4) launch_wide_cfg<MH, NT, 2, 8, 4>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-        else launch_wide_cfg<MH, NT, 4, 8, 4>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-    }
+    const int ng = (tiles + 255) / 256;
+    if (ng <= 1) launch_wide_cfg<MH, NT, 1>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    else if (ng == 2) launch_wide_cfg<MH, NT, 2>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    else if (ng == 3) launch_wide_cfg<MH, NT, 3>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    else launch_wide_cfg<MH, NT, 4>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
 }
 
 // Projections with few bands (O, down): K is split over the grid's y dimension and the workgroups store
@@ -644,7 +613,7 @@ static inline int launch_wide_split(const u16* X, const u16* W, int K, int N, in
     EpiStoreF32 e{N, M, 1, part, N, (size_t)M * N};
     const int quads = pair_rows_for(M) / 4;
     int S = 1;
-    if constexpr (MH == 3 || MH == 4) launch_wide_cfg<MH, 1, 4, 8, 4>(X, W, K, N / 16, quads, 4, rsc, e, s, &S);
-    else launch_wide_cfg<MH, 1, 8, 8, 4>(X, W, K, N / 16, quads, WIDE_MAX_SPLIT, rsc, e, s, &S);
+    if (K >= 8192) launch_wide_cfg<MH, 1, 8>(X, W, K, N / 16, quads, WIDE_MAX_SPLIT, rsc, e, s, &S);
+    else launch_wide_cfg<MH, 1, 4>(X, W, K, N / 16, quads, 4, rsc, e, s, &S);
     return S;
 }
