@@ -161,7 +161,7 @@ template <int NT, class Epi>
 void launch_projection(int M, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
                        hipStream_t s) {
     if (M <= 8) {
-        launch_gemm_rows<NT>(M, true, X, W, K, tiles, rsc, epi, s);
+        if (!launch_wide_half<NT>(X, W, K, tiles, rsc, epi, s)) launch_gemm_rows<NT>(M, true, X, W, K, tiles, rsc, epi, s);
         return;
     }
     const int quads = pair_rows_for(M) / 4;

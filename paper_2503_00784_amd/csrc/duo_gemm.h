@@ -210,23 +210,27 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 // the main loop are unconditional with clamped indices and invalid steps multiply by zero: no branches, so
 // the counted waits stay exact.
 //
+// With HALF the operand is the single tile of up to eight rows (hi rows 0..7, lo rows 8..15 of the same tile),
+// as the kernel above uses it; the two halves of the sums are then 32 lanes apart.
+//
 // One extra wave per workgroup does nothing but move the activation operand:
 // wave NG copies the operand tiles of round r + 2 from global memory straight into a three-deep ring of
 // LDS buffers (16-byte global -> LDS loads, no registers, no LDS store instructions) while the NG consumer
 // waves stream their weight bands and compute on round r.  The consumers' memory counter then tracks the
 // weight stream alone, PF steps ahead, and their registers hold weights and accumulators only.
 // One barrier per round (AG K steps) hands a filled buffer over and takes a drained one back.
-template <int MH, int NT, int NG, int PF, int AG, class Epi>
+template <int MH, int NT, int NG, int PF, int AG, class Epi, bool HALF = false>
 __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W,
                                                                      int K, int split_steps, int ntiles, int quads,
                                                                      RowScale rsc, Epi epi) {
-    constexpr int MT = 2 * MH, NTH = (NG + 1) * 64;
+    static_assert(!HALF || MH == 1, "the shared-tile layout holds at most eight rows");
+    constexpr int MT = HALF ? 1 : 2 * MH, NTH = (NG + 1) * 64;
     constexpr int BUF = AG * MT * 64;  // 16-byte chunks per ring buffer (one round)
     constexpr int NBUF = 3;
     constexpr int L = AG * MT;  // global -> LDS loads per round
     constexpr int U = PF / AG;  // rounds per turn of the weight slots
     static_assert(PF % AG == 0 && AG % 2 == 0 && L <= 63, "slots cover whole rounds; a round's loads fit the memory counter");
-    constexpr bool SEP = MH * NT < 4;  // few tiles: separate lo accumulators
+    constexpr bool SEP = !HALF && MH * NT < 4;  // few tiles: separate lo accumulators
     constexpr int MA = SEP ? MT : MH;
     __shared__ u32x4 lds[NBUF * BUF];
     __shared__ float row_scale[MH * 16];
@@ -333,11 +337,14 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
                 for (int mh = 0; mh < MH; ++mh)
 #pragma unroll
                     for (int t = 0; t < NT; ++t) acc[mh][t] = mfma16(af[p & 1][mh], b[t], acc[mh][t]);
+                if (!HALF) {
 #pragma unroll
-                for (int mh = 0; mh < MH; ++mh)
+                    for (int mh = 0; mh < MH; ++mh)
 #pragma unroll
-                    for (int t = 0; t < NT; ++t)
-                        acc[SEP ? MH + mh : mh][t] = mfma16(af[p & 1][MH + mh], b[t], acc[SEP ? MH + mh : mh][t]);
+                        for (int t = 0; t < NT; ++t)
+                            acc[SEP ? MH + mh : mh][t] =
+                                mfma16(af[p & 1][HALF ? 0 : MH + mh], b[t], acc[SEP ? MH + mh : mh][t]);
+                }
                 w_load(p, (r + U) * AG + w);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -347,19 +354,25 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
         }
     }
 
-    if (live) {
+    if (live) {  // wave-uniform
 #pragma unroll
         for (int mh = 0; mh < MH; ++mh) {
             const int qi = mh * 4 + (lane >> 4);
-            if (qi < quads) {
-                f32x4 v[NT];
+            f32x4 v[NT];
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    v[t] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
-                    if (rsc.part) {
+            for (int t = 0; t < NT; ++t) {
+                v[t] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
+                if (HALF) {  // rows 0..7 hold the hi sums, rows 8..15 (32 lanes further on) the lo sums; all lanes take part
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[t][i] += __shfl_xor(v[t][i], 32, 64);
+                }
+            }
+            if (qi < quads) {
+                if (rsc.part) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
 #pragma unroll
                         for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
-                    }
                 }
                 epi.store(tile, qi, lane & 15, v, pre, mh == 0);
             }
@@ -582,7 +595,7 @@ static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16*
 constexpr int WIDE_MAX_SPLIT = 8;
 constexpr int WIDE_PF = 8, WIDE_AG = 4;
 
-template <int MH, int NT, int NG, class Epi>
+template <int MH, int NT, int NG, class Epi, bool HALF = false>
 static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int splits, const RowScale& rsc,
                                    const Epi& epi, hipStream_t s, int* splits_out) {
     const int steps = K >> 5;
@@ -590,7 +603,7 @@ static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles,
     split_steps = (split_steps + WIDE_AG - 1) / WIDE_AG * WIDE_AG;  // whole rounds: only the last split has a ragged end
     const int S = (steps + split_steps - 1) / split_steps;
     if (splits_out) *splits_out = S;
-    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, WIDE_PF, WIDE_AG, Epi>), dim3((tiles + NG - 1) / NG, S), dim3((NG + 1) * 64), s, X, W,
+    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, WIDE_PF, WIDE_AG, Epi, HALF>), dim3((tiles + NG - 1) / NG, S), dim3((NG + 1) * 64), s, X, W,
                K, split_steps, tiles, quads, rsc, epi);
 }
 
@@ -603,6 +616,18 @@ static inline void launch_wide(const u16* X, const u16* W, int K, int tiles, int
     else if (ng == 2) launch_wide_cfg<MH, NT, 2>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
     else if (ng == 3) launch_wide_cfg<MH, NT, 3>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
     else launch_wide_cfg<MH, NT, 4>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+}
+
+// Up to eight rows (hi and lo halves in one operand tile): the same kernel pays for matrices of 257..768 workgroup
+// tiles (measured at 4096 input channels: 20.6 against 21.4 us for 384 tiles, 32.0 against 33.5 us for 688; not
+// for 1000 tiles).  Returns false when the caller should use gemm_skinny_kernel.
+template <int NT, class Epi>
+static inline bool launch_wide_half(const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
+                                    hipStream_t s) {
+    if (tiles <= 256 || tiles > 768) return false;
+    if (tiles <= 512) launch_wide_cfg<1, NT, 1, Epi, true>(X, W, K, tiles, 2, 1, rsc, epi, s, nullptr);
+    else launch_wide_cfg<1, NT, 3, Epi, true>(X, W, K, tiles, 2, 1, rsc, epi, s, nullptr);
+    return true;
 }
 
 // Projections with few bands (O, down): K is split over the grid's y dimension and the workgroups store
