@@ -20,7 +20,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by what
 # the same counter reads for a copy of known size): these cannot be read from inside the process, so the figures
 # of the committed counter summary (profiles/c1_hbm_traffic.md) are repeated here, keyed by workload and kernel.
-MEASURED_TRAFFIC_BYTES = {("C1", "gate_up_swiglu"): 181952182}
+MEASURED_TRAFFIC_BYTES = {("C1", "gate_up_swiglu"): 181977918}
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
