@@ -193,9 +193,10 @@ def test_verify_is_repeatable_and_flags_prefix_mismatch(B):
     assert eng.results(2)["status"] & B.STATUS_PREFIX_MISMATCH
 
 
-@pytest.mark.parametrize("name", ["C1", "C3"])
-def test_full_size_7b_shape(B, name):
-    """Llama-2-7B geometry at the benchmark's launch configuration, synthetic prefix cache."""
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4"])
+def test_full_size_shapes(B, name):
+    """Llama-2-7B (C1-C3) and Llama-3-8B GQA (C4) geometry at the benchmark's launch configuration, synthetic
+    prefix cache: every logit of every row against the oracle, accept lengths away from ties."""
     wl = inputs.WORKLOADS[name]
     shape, P, n, k = wl.shape, wl.prefix_len, wl.n_seq, wl.k_draft
     say(f"{name}: generating weights")
