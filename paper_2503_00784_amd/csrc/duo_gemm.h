@@ -218,20 +218,25 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 // LDS buffers (16-byte global -> LDS loads, no registers, no LDS store instructions) while the NG consumer
 // waves stream their weight bands and compute on round r.  The consumers' memory counter then tracks the
 // weight stream alone, PF steps ahead, and their registers hold weights and accumulators only.
-// One barrier per round (AG K steps) hands a filled buffer over and takes a drained one back.
-template <int MH, int NT, int NG, int PF, int AG, class Epi, bool HALF = false>
-__global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W,
-                                                                     int K, int split_steps, int ntiles, int quads,
-                                                                     RowScale rsc, Epi epi) {
-    static_assert(!HALF || MH == 1, "the shared-tile layout holds at most eight rows");
-    constexpr int MT = HALF ? 1 : 2 * MH, NTH = (NG + 1) * 64;
-    constexpr int BUF = AG * MT * 64;  // 16-byte chunks per ring buffer (one round)
+// One barrier per round hands a filled buffer over and takes a drained one back.  Matrices with few bands
+// put NK waves on each band group: they split the K steps of every round (NK * AG steps) between them and
+// add their partial sums through LDS in wave order at the end.
+template <int MH, int NT, int NG, int NK, int PF, int AG, class Epi, bool HALF = false>
+__global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W,
+                                                                      int K, int split_steps, int ntiles, int quads,
+                                                                      RowScale rsc, Epi epi) {
+    static_assert(!HALF || (MH == 1 && NK == 1), "the shared-tile layout holds at most eight rows");
+    constexpr int MT = HALF ? 1 : 2 * MH, NC = NG * NK, NTH = (NC + 1) * 64;
+    constexpr int RS = NK * AG;        // K steps per round
+    constexpr int BUF = RS * MT * 64;  // 16-byte chunks per ring buffer (one round)
     constexpr int NBUF = 3;
-    constexpr int L = AG * MT;  // global -> LDS loads per round
+    constexpr int L = RS * MT;  // global -> LDS loads per round
     constexpr int U = PF / AG;  // rounds per turn of the weight slots
     static_assert(PF % AG == 0 && AG % 2 == 0 && L <= 63, "slots cover whole rounds; a round's loads fit the memory counter");
     constexpr bool SEP = !HALF && MH * NT < 4;  // few tiles: separate lo accumulators
     constexpr int MA = SEP ? MT : MH;
+    constexpr int RED = NK > 1 ? NC * MH * NT * 64 : 0;  // partial sums of the K-splitting waves (reuses the ring)
+    static_assert(RED <= NBUF * BUF, "the partial sums fit the ring buffers");
     __shared__ u32x4 lds[NBUF * BUF];
     __shared__ float row_scale[MH * 16];
 
@@ -239,7 +244,7 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
     const int steps = K >> 5;
     const int k0 = blockIdx.y * split_steps;
     const int ns = min(steps - k0, split_steps);  // K steps of this split (the host makes it positive)
-    const int rounds = (ns + AG - 1) / AG;
+    const int rounds = (ns + RS - 1) / RS;
     const int rounds_run = (rounds + U - 1) / U * U;  // what the consumers' unrolled loop executes
     const u32x4* xg = reinterpret_cast<const u32x4*>(X) + (size_t)k0 * MT * 64 + lane;
 
@@ -248,19 +253,19 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
     } else if (rsc.part) {
         const int nrows = quads * 4;
         f32x4 rsv[RowScale::MAXQ];
-        for (int r0 = wave * 8; r0 < nrows; r0 += (NG + 1) * 8) {
+        for (int r0 = wave * 8; r0 < nrows; r0 += (NC + 1) * 8) {
             rsc.load(rsv, r0, nrows, lane);
             rsc.reduce(rsv, row_scale, r0, nrows, lane);
         }
     }
 
-    if (wave == NG) {
+    if (wave == NC) {
         // ---- producer: round r goes to ring buffer r % 3; steps past the end re-read the last step
         auto issue = [&](int r) {
             const int b = r % NBUF;
 #pragma unroll
             for (int i = 0; i < L; ++i) {
-                int st = r * AG + i / MT;
+                int st = r * RS + i / MT;
                 st = st < ns ? st : ns - 1;
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xg + ((size_t)st * MT + i % MT) * 64),
                                                  (__attribute__((address_space(3))) void*)(lds + b * BUF + i * 64), 16, 0, 0);
@@ -279,11 +284,17 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
             __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_ROUND);  // round r + 1 has landed
             __builtin_amdgcn_s_barrier();
         }
+        if (NK > 1) {  // the consumers reuse the ring for their partial sums: nothing may land in it any more
+            __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));  // vmcnt(0)
+            __builtin_amdgcn_s_barrier();                      // ring is quiet
+            __builtin_amdgcn_s_barrier();                      // partial sums are written
+        }
         return;
     }
 
-    // ---- consumers
-    const int tile_raw = blockIdx.x * NG + wave;
+    // ---- consumers: wave (ng, nk) takes band group ng and, of every round, the K steps nk * AG .. + AG
+    const int ng = wave % NG, nk = wave / NG;
+    const int tile_raw = blockIdx.x * NG + ng;
     const bool live = tile_raw < ntiles;
     const int tile = live ? tile_raw : ntiles - 1;
     const u16* wp[NT];
@@ -296,13 +307,14 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
         for (int t = 0; t < NT; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     bf16x8 bb[PF][NT];
     bf16x8 af[2][MT];
-    auto w_load = [&](int p, int i) {  // i-th K step, clamped
-        const int ls = i < ns ? i : ns - 1;
+    auto w_load = [&](int p, int i) {  // i-th step of this wave: round i / AG, position nk * AG + i % AG in it; clamped
+        int ls = (i / AG) * RS + nk * AG + (i % AG);
+        ls = ls < ns ? ls : ns - 1;
 #pragma unroll
         for (int t = 0; t < NT; ++t) bb[p][t] = load_frag(wp[t] + (size_t)ls * 512);
     };
-    auto a_frags = [&](int slot, int r, int w) {  // step w of round r
-        const u32x4* ab = lds + (r % NBUF) * BUF + w * MT * 64 + lane;
+    auto a_frags = [&](int slot, int r, int w) {  // this wave's step w of round r
+        const u32x4* ab = lds + (r % NBUF) * BUF + (nk * AG + w) * MT * 64 + lane;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             Frag8 f;
@@ -311,8 +323,9 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
         }
     };
     typename Epi::Pre pre;
-    const bool has_pre = live && (lane >> 4) < quads;
-    if (has_pre) epi.prefetch(tile, lane >> 4, lane & 15, pre);
+    const int first_mh = NK > 1 ? nk : 0;  // the first row tile this wave finishes
+    const bool has_pre = live && first_mh < MH && first_mh * 4 + (lane >> 4) < quads;
+    if (has_pre) epi.prefetch(tile, first_mh * 4 + (lane >> 4), lane & 15, pre);
 #pragma unroll
     for (int p = 0; p < PF; ++p) w_load(p, p);
     __builtin_amdgcn_sched_barrier(0);
@@ -329,7 +342,7 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
             for (int w = 0; w < AG; ++w) {
                 const int p = u * AG + w;
                 if (w + 1 < AG) a_frags((p + 1) & 1, r, w + 1);
-                const bool valid = r * AG + w < ns;
+                const bool valid = r * RS + nk * AG + w < ns;
                 bf16x8 b[NT];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) b[t] = valid ? bb[p][t] : zero;
@@ -354,27 +367,55 @@ __global__ __launch_bounds__((NG + 1) * 64) void gemm_wide_kernel(const u16* __r
         }
     }
 
-    if (live) {  // wave-uniform
+    // A lane's accumulator quad is rows 16*mh + 4*(lane/16) .. +3, column lane%16 of its tile: one output quad.
+    auto finish = [&](int mh, f32x4 (&v)[NT], bool use_pre) {
+        if (HALF) {  // rows 0..7 hold the hi sums, rows 8..15 (32 lanes further on) the lo sums; all lanes take part
 #pragma unroll
-        for (int mh = 0; mh < MH; ++mh) {
-            const int qi = mh * 4 + (lane >> 4);
-            f32x4 v[NT];
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                v[t] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
-                if (HALF) {  // rows 0..7 hold the hi sums, rows 8..15 (32 lanes further on) the lo sums; all lanes take part
+                for (int i = 0; i < 4; ++i) v[t][i] += __shfl_xor(v[t][i], 32, 64);
+        }
+        const int qi = mh * 4 + (lane >> 4);
+        if (qi < quads) {
+            if (rsc.part) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) v[t][i] += __shfl_xor(v[t][i], 32, 64);
-                }
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
             }
-            if (qi < quads) {
-                if (rsc.part) {
+            epi.store(tile, qi, lane & 15, v, pre, use_pre);
+        }
+    };
+    if (NK == 1) {
+        if (live) {  // wave-uniform
 #pragma unroll
-                    for (int t = 0; t < NT; ++t)
+            for (int mh = 0; mh < MH; ++mh) {
+                f32x4 v[NT];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
+                for (int t = 0; t < NT; ++t) v[t] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
+                finish(mh, v, mh == 0);
+            }
+        }
+    } else {
+        f32x4* red = reinterpret_cast<f32x4*>(lds);
+        __syncthreads();  // the producer has seen its last load land: the ring is quiet
+#pragma unroll
+        for (int mh = 0; mh < MH; ++mh)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                red[((wave * MH + mh) * NT + t) * 64 + lane] = SEP ? acc[mh][t] + acc[MA - MH + mh][t] : acc[mh][t];
+        __syncthreads();
+        if (live) {
+            for (int mh = nk; mh < MH; mh += NK) {  // K parts added in wave order
+                f32x4 v[NT];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    f32x4 sum = red[((ng * MH + mh) * NT + t) * 64 + lane];
+#pragma unroll
+                    for (int kk = 1; kk < NK; ++kk) sum += red[(((kk * NG + ng) * MH + mh) * NT + t) * 64 + lane];
+                    v[t] = sum;
                 }
-                epi.store(tile, qi, lane & 15, v, pre, mh == 0);
+                finish(mh, v, mh == nk);
             }
         }
     }
@@ -595,27 +636,31 @@ static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16*
 constexpr int WIDE_MAX_SPLIT = 8;
 constexpr int WIDE_PF = 8, WIDE_AG = 4;
 
-template <int MH, int NT, int NG, class Epi, bool HALF = false>
+template <int MH, int NT, int NG, int NK, class Epi, bool HALF = false>
 static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int splits, const RowScale& rsc,
                                    const Epi& epi, hipStream_t s, int* splits_out) {
+    // rounds of NK * AG K steps; a round's operand tiles (2*MH per step) must fit the producer's counted wait
+    constexpr int AG = (NK * WIDE_AG * (HALF ? 1 : 2 * MH) <= 63) ? WIDE_AG : 2;
+    constexpr int RS = NK * AG;
     const int steps = K >> 5;
     int split_steps = (steps + splits - 1) / splits;
-    split_steps = (split_steps + WIDE_AG - 1) / WIDE_AG * WIDE_AG;  // whole rounds: only the last split has a ragged end
+    split_steps = (split_steps + RS - 1) / RS * RS;  // whole rounds: only the last split has a ragged end
     const int S = (steps + split_steps - 1) / split_steps;
     if (splits_out) *splits_out = S;
-    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, WIDE_PF, WIDE_AG, Epi, HALF>), dim3((tiles + NG - 1) / NG, S), dim3((NG + 1) * 64), s, X, W,
-               K, split_steps, tiles, quads, rsc, epi);
+    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, NK, WIDE_PF, AG, Epi, HALF>), dim3((tiles + NG - 1) / NG, S),
+               dim3((NG * NK + 1) * 64), s, X, W, K, split_steps, tiles, quads, rsc, epi);
 }
 
 // Projections with many bands (QKV, gate/up, LM head): no K split, the epilogue finishes the rows.
 template <int MH, int NT, class Epi>
 static inline void launch_wide(const u16* X, const u16* W, int K, int tiles, int quads, const RowScale& rsc, const Epi& epi,
                                hipStream_t s) {
+    // few bands: two waves per band group split K, so that four SIMDs per compute unit issue MFMAs
     const int ng = (tiles + 255) / 256;
-    if (ng <= 1) launch_wide_cfg<MH, NT, 1>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-    else if (ng == 2) launch_wide_cfg<MH, NT, 2>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-    else if (ng == 3) launch_wide_cfg<MH, NT, 3>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
-    else launch_wide_cfg<MH, NT, 4>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    if (ng <= 1) launch_wide_cfg<MH, NT, 1, 2>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    else if (ng == 2) launch_wide_cfg<MH, NT, 2, 2>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    else if (ng == 3) launch_wide_cfg<MH, NT, 3, 1>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
+    else launch_wide_cfg<MH, NT, 4, 1>(X, W, K, tiles, quads, 1, rsc, epi, s, nullptr);
 }
 
 // Up to eight rows (hi and lo halves in one operand tile): the same kernel pays for matrices of 257..768 workgroup
@@ -625,8 +670,8 @@ template <int NT, class Epi>
 static inline bool launch_wide_half(const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
                                     hipStream_t s) {
     if (tiles <= 256 || tiles > 768) return false;
-    if (tiles <= 512) launch_wide_cfg<1, NT, 1, Epi, true>(X, W, K, tiles, 2, 1, rsc, epi, s, nullptr);
-    else launch_wide_cfg<1, NT, 3, Epi, true>(X, W, K, tiles, 2, 1, rsc, epi, s, nullptr);
+    if (tiles <= 512) launch_wide_cfg<1, NT, 1, 1, Epi, true>(X, W, K, tiles, 2, 1, rsc, epi, s, nullptr);
+    else launch_wide_cfg<1, NT, 3, 1, Epi, true>(X, W, K, tiles, 2, 1, rsc, epi, s, nullptr);
     return true;
 }
 
@@ -638,7 +683,7 @@ static inline int launch_wide_split(const u16* X, const u16* W, int K, int N, in
     EpiStoreF32 e{N, M, 1, part, N, (size_t)M * N};
     const int quads = pair_rows_for(M) / 4;
     int S = 1;
-    if (K >= 8192) launch_wide_cfg<MH, 1, 8>(X, W, K, N / 16, quads, WIDE_MAX_SPLIT, rsc, e, s, &S);
-    else launch_wide_cfg<MH, 1, 4>(X, W, K, N / 16, quads, 4, rsc, e, s, &S);
+    if (K >= 8192) launch_wide_cfg<MH, 1, 8, 1>(X, W, K, N / 16, quads, WIDE_MAX_SPLIT, rsc, e, s, &S);
+    else launch_wide_cfg<MH, 1, 4, 1>(X, W, K, N / 16, quads, 4, rsc, e, s, &S);
     return S;
 }
