@@ -162,16 +162,32 @@ def test_tiny_config_prefill_and_verify_chain(B):
 
 
 @pytest.mark.parametrize("n,k,mode,root", [(3, 5, 1, 17), (1, 16, 0, -1), (4, 16, 0, 3), (8, 8, 1, -1), (2, 1, 0, 5),
-                                            (3, 8, 0, -1), (2, 16, 1, 9), (5, 8, 0, -1), (1, 9, 0, -1)])
+                                            (3, 8, 0, -1), (2, 16, 1, 9), (5, 8, 0, -1), (1, 9, 0, -1), (5, 16, 0, -1),
+                                            (1, 1, 0, -1)])
 def test_mid_config_gqa_ragged(B, n, k, mode, root):
     """3 layers, 8 query / 2 KV heads of 64, vocab 4099 (not a multiple of 16), prefix 77.  The row counts
-    (16, 16, 65, 64, 3, 24, 33, 40, 9) cover every row-tile count of both projection kernels."""
+    (16, 16, 65, 64, 3, 24, 33, 40, 9, 80, 1) cover every row-tile count of both projection kernels, the
+    largest call the library takes (80 rows) and the smallest (one token)."""
     shape = inputs.MID
     say(f"MID n={n} k={k} mode={mode} root={root}")
     w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False)
     got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 31 + k, mode=mode, root_token=root)
     if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
         _check_cache(eng, cache, cache.prefix_len)
+
+
+def test_cache_filled_to_the_last_slot(B):
+    """prefix + rows == max_seq exactly: the last cache slot is written and read; one more row is refused."""
+    shape = inputs.MID
+    n, k, P = 2, 8, 48  # 16 rows, cache of 64 slots
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, P + n * k, seed=7, synthetic_cache=True)
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=3, mode=0, root_token=-1)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len)
+    eng.set_prefix_len(P)
+    q, toks, u = inputs.make_draft(shape.vocab, n, k, seed=3)
+    with pytest.raises(B.DuoError):  # 48 + 1 + 16 rows do not fit 64 slots
+        eng.verify(to_dev(toks), to_dev(q), to_dev(u), root_token=5)
 
 
 def test_verify_is_repeatable_and_flags_prefix_mismatch(B):
