@@ -502,26 +502,70 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
 // Many query rows per kv head (more than two 16-row query tiles: many draft rows and/or a large GQA
 // group).  The kernels above give every wave its own keys and ALL query tiles, which does not fit the
 // registers beyond two tiles, so more tiles meant more workgroups re-reading the same keys.  Here it is
-// the other way round: a workgroup takes one (kv head, key chunk) and stages each 32-key block of K and
-// V^T once in LDS, in MFMA operand layout (the same 1 KiB tiles the other kernels load straight into
-// registers); each wave owns MTW query tiles and runs over all blocks of the chunk, so nothing is merged
-// between waves.  Two register sets hold the blocks on their way from global memory to LDS (two blocks
-// ahead of the MFMAs), two LDS buffers
-// alternate, one barrier per block.
+// the other way round: a workgroup takes one (kv head, key chunk); each 32-key block of K and V^T is put
+// in LDS once, in MFMA operand layout (the same 1 KiB tiles the other kernels load straight into
+// registers), and each of the NWV consumer waves owns MTW query tiles and runs over all blocks of the
+// chunk, so nothing is merged between waves.  One extra wave does nothing but move the blocks: 16-byte
+// global -> LDS loads (no registers, no LDS store instructions) into a ring of three buffers, two blocks
+// ahead of the MFMAs; its barriers are bare s_barrier instructions behind a counted wait.  One barrier per
+// block hands a filled buffer over and takes a drained one back.
 template <int D, int MTW, int NWV>
-__global__ __launch_bounds__(NWV * 64) void attn_shared_kernel(AttnArgs a) {
+__global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a) {
     constexpr int KS = D / 32, DT = D / 16;
-    constexpr int KT = 2 * KS;         // K tiles per block (2 key halves x KS)
-    constexpr int TILES = KT + DT;     // 1 KiB tiles per block
-    constexpr int TPW = (TILES + NWV - 1) / NWV;  // tiles a wave moves per block
-    __shared__ u32x4 lds_kv[2][TILES * 64];
+    constexpr int KT = 2 * KS;      // K tiles per block (2 key halves x KS)
+    constexpr int TILES = KT + DT;  // 1 KiB tiles per block
+    constexpr int NBUF = 3;
+    static_assert(TILES <= 63, "a block's loads fit the memory counter");
+    __shared__ u32x4 lds_kv[NBUF][TILES * 64];
 
     const int cb = blockIdx.x, hk = blockIdx.y;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar: MFMA ignores EXEC
     const int c = lane & 15, g = lane >> 4;
+    const int NB = (a.Ktot + 31) / 32;
+    const int b0 = cb * a.blocks_per_wave;  // here: blocks per chunk
+    int nb = NB - b0;
+    nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
+
+    if (wave == NWV) {
+        // ---- producer.  Tile j < KT is K tile (t = j / KS, ks = j % KS): lane (c, g) fetches key
+        // kb + 8*(c/4) + 4t + c%4 (clamped to the last key in play), channels 32ks + 8g .. +8; otherwise V^T
+        // tile dt = j - KT: channel 16dt + c, keys kb + 8g .. +8.  Blocks past the last one are clamped.
+        const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
+        const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
+        auto issue = [&](int ib) {
+            const int kb = min(b0 + ib, NB - 1) * 32;
+            u32x4* dst = lds_kv[ib % NBUF];
+#pragma unroll
+            for (int j = 0; j < TILES; ++j) {
+                const u16* src;
+                if (j < KT) {
+                    int key = kb + (c >> 2) * 8 + (j / KS) * 4 + (c & 3);
+                    key = key < a.Ktot ? key : a.Ktot - 1;
+                    src = kbase + (size_t)key * D + (j % KS) * 32;
+                } else {
+                    src = vbase + (size_t)(j - KT) * 16 * a.max_seq + kb;
+                }
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)(dst + j * 64), 16, 0, 0);
+            }
+        };
+        // vmcnt(TILES): everything but the youngest block has landed (expcnt, lgkmcnt fields at their maxima)
+        constexpr int WAIT_ALL_BUT_ONE_BLOCK = (TILES & 15) | ((TILES >> 4) << 14) | (7 << 4) | (15 << 8);
+        issue(0);
+        issue(1);
+        __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);
+        __builtin_amdgcn_s_barrier();
+        for (int ib = 0; ib < nb; ++ib) {
+            issue(ib + 2);  // its buffer was drained in iteration ib - 1
+            __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);  // block ib + 1 has landed
+            __builtin_amdgcn_s_barrier();
+        }
+        return;
+    }
+
+    // ---- consumers
     const int MQ = a.plan.M * a.group;
     const int tile0 = (blockIdx.z * NWV + wave) * MTW;  // first query tile of this wave
-
     bf16x8 qf[MTW][KS], ql[MTW][KS];
     int vis_lo[MTW], vis_hi[MTW];
 #pragma unroll
@@ -551,69 +595,20 @@ __global__ __launch_bounds__(NWV * 64) void attn_shared_kernel(AttnArgs a) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-
-    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
-    const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
-    const int NB = (a.Ktot + 31) / 32;
-    const int b0 = cb * a.blocks_per_wave;  // here: blocks per chunk
-    int nb = NB - b0;
-    nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
-
-    // Tile j of a block: j < KT is K tile (t = j / KS, ks = j % KS): lane (c, g) holds key
-    // kb + 8*(c/4) + 4t + c%4, channels 32ks + 8g .. +8; otherwise V^T tile dt = j - KT: channel 16dt + c,
-    // keys kb + 8g .. +8 (zeroed at and beyond Ktot, where the cache may hold anything).  Wave w moves
-    // tiles w * TPW .. + TPW (whole cache lines of the K rows); block indices past the last block are clamped (loaded, never used).
-    constexpr int NSET = 2;  // register sets = blocks in flight (more did not pay: the loop is bound by its MFMA and VALU work)
-    u32x4 st[NSET][TPW];
-    auto g_load = [&](int set, int ib) {
-        const int kb = min(b0 + ib, NB - 1) * 32;
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int j = wave * TPW + i;  // scalar
-            if (TILES % NWV == 0 || j < TILES) {
-                if (j < KT) {
-                    int key = kb + (c >> 2) * 8 + (j / KS) * 4 + (c & 3);
-                    key = key < a.Ktot ? key : a.Ktot - 1;
-                    st[set][i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)key * D + (j % KS) * 32);
-                } else {
-                    st[set][i] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(j - KT) * 16 * a.max_seq + kb);
-                }
-            }
-        }
-    };
-    auto l_store = [&](int set, int buf, int ib) {
-        const int kb = min(b0 + ib, NB - 1) * 32;
-        const bool tail = kb + 32 > a.Ktot;
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int j = wave * TPW + i;
-            if (TILES % NWV == 0 || j < TILES) {
-                u32x4 v = st[set][i];
-                if (tail && j >= KT) {
-                    Frag8 f;
-                    f.q = v;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (kb + g * 8 + e >= a.Ktot) f.h[e] = 0;
-                    v = f.q;
-                }
-                lds_kv[buf][j * 64 + lane] = v;
-            }
-        }
-    };
-    auto frag = [&](int buf, int j) {
-        Frag8 f;
-        f.q = lds_kv[buf][j * 64 + lane];
-        return f.v;
-    };
-    auto use_block = [&](int buf, int kb) {
+    auto use_block = [&](const u32x4* buf, int kb) {
         const bool masked = kb + 32 > a.plan.P;  // block touches draft slots or the end
+        const bool tail = kb + 32 > a.Ktot;      // slots at or beyond Ktot may hold anything: zero their V
+        auto frag = [&](int j) {
+            Frag8 f;
+            f.q = buf[j * 64 + lane];
+            return f;
+        };
         float scs[MTW][8];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             bf16x8 kf[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[ks] = frag(buf, t * KS + ks);
+            for (int ks = 0; ks < KS; ++ks) kf[ks] = frag(t * KS + ks).v;
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt) {  // hi and lo query parts in separate chains: shorter dependent runs
                 f32x4 acc_l = {0.f, 0.f, 0.f, 0.f}, acc_h = {0.f, 0.f, 0.f, 0.f};
@@ -664,31 +659,24 @@ __global__ __launch_bounds__(NWV * 64) void attn_shared_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            const bf16x8 vf = frag(buf, KT + dt);
+            Frag8 vf = frag(KT + dt);
+            if (tail) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (kb + g * 8 + e >= a.Ktot) vf.h[e] = 0;
+            }
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt) {
-                f32x4 acc = mfma16(vf, pl[mt].v, o[mt][dt]);
-                o[mt][dt] = mfma16(vf, pf[mt].v, acc);
+                f32x4 acc = mfma16(vf.v, pl[mt].v, o[mt][dt]);
+                o[mt][dt] = mfma16(vf.v, pf[mt].v, acc);
             }
         }
     };
 
-    // Block ib travels in register set ib % NSET and is used from LDS buffer ib % 2.  NSET blocks are in
-    // flight per workgroup; indices are static because the loop body covers NSET blocks.  Iterations past
-    // the chunk's end move clamped blocks and compute nothing.
-#pragma unroll
-    for (int i = 0; i < NSET; ++i) g_load(i, i);
-    l_store(0, 0, 0);
-    g_load(0, NSET);
-    for (int ib0 = 0; ib0 < nb; ib0 += NSET) {
-#pragma unroll
-        for (int u = 0; u < NSET; ++u) {
-            const int ib = ib0 + u;
-            __syncthreads();  // buffer u % 2 is complete; every wave is done with the other one
-            l_store((u + 1) % NSET, (u + 1) & 1, ib + 1);
-            g_load((u + 1) % NSET, ib + 1 + NSET);
-            if (ib < nb) use_block(u & 1, (b0 + ib) * 32);
-        }
+    __syncthreads();  // block 0 is in LDS
+    for (int ib = 0; ib < nb; ++ib) {
+        use_block(lds_kv[ib % NBUF], (b0 + ib) * 32);
+        __syncthreads();  // block ib + 1 is in LDS; block ib's buffer may be refilled
     }
 
 #pragma unroll
