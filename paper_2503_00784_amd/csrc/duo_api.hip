@@ -208,7 +208,8 @@ template <int D>
 void launch_attention_shared(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_t s) {
     if (mtw == 2) DUO_LAUNCH((attn_shared_kernel<D, 2, 7>), grid, dim3(512), s, a);  // 8 waves: 256 registers each
     else if (nwv == 8) DUO_LAUNCH((attn_shared_kernel<D, 1, 8>), grid, dim3(576), s, a);
-    else DUO_LAUNCH((attn_shared_kernel<D, 1, 4>), grid, dim3(320), s, a);
+    else if (nwv == 4) DUO_LAUNCH((attn_shared_kernel<D, 1, 4>), grid, dim3(320), s, a);
+    else DUO_LAUNCH((attn_shared_kernel<D, 1, 2>), grid, dim3(192), s, a);
 }
 
 // The target pass over the rows of `plan`: fills the cache slots P .. P+M-1 and writes fp32
@@ -241,14 +242,15 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const int mtw = MqT >= 2 ? 2 : 1;
     const int MG = (MqT + mtw - 1) / mtw;
     const int mq_pad = Mp * group;
-    // More than two query tiles per kv head: the kernel that stages K/V blocks in LDS for all query tiles.
-    const bool shared_kv = MqT > 2;
+    // Two or more query tiles per kv head: the kernel that stages K/V blocks in LDS for all query tiles
+    // (two tiles on a short context stay with the per-wave kernel, which then needs no chunk merge).
+    const bool shared_kv = MqT > 2 || (MqT == 2 && NB > 32);
     int sh_mtw = 1, sh_nwv = 4, sh_zg = 1;
     int nwv, bpw, nchunks;
     if (shared_kv) {
         // one query tile per wave, about 256 workgroups (one per compute unit): measured best for 4 tiles x 32 heads and 16 tiles x 8 heads
         sh_mtw = MqT > 16 ? 2 : 1;
-        sh_nwv = MqT > 16 ? 7 : (MqT > 4 ? 8 : 4);
+        sh_nwv = MqT > 16 ? 7 : (MqT > 4 ? 8 : (MqT > 2 ? 4 : 2));
         sh_zg = (MqT + sh_nwv * sh_mtw - 1) / (sh_nwv * sh_mtw);
         int target = (256 + Hkv * sh_zg - 1) / (Hkv * sh_zg);
         target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
