@@ -228,7 +228,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const RowScale norm_full{ws.ssq, NP, 1.0f / (float)d, c.rms_eps, ws.ssq_full};
     const bool o_split = residual_is_split(M, qd), down_split = residual_is_split(M, F);
     prof(DUO_PROF_SETUP, s);
-    DUO_LAUNCH(rope_table_kernel, dim3(M), dim3(64), s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s);
+    DUO_LAUNCH(rope_table_kernel, dim3(M), dim3(64), s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s, status);
     prof(DUO_PROF_SETUP, s);
     DUO_LAUNCH(embed_kernel, dim3(M), dim3(256), s, w.embed, tokens, root_token, plan, V, cache.prefix_len,
                        status, ws.x, w.g_attn[0], ws.h, d, PR, AT, ws.ssq, ws.ssq_full);
@@ -324,10 +324,14 @@ void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const du
     prof(DUO_PROF_SAMPLE, s);
     DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, sa.n, STATS_SPLIT), dim3(256), s, sa);
     prof(DUO_PROF_SAMPLE, s);
-    if (mode == DUO_SELECT_INDEPENDENT_LONGEST)
-        DUO_LAUNCH(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa);
-    else
+    if (mode == DUO_SELECT_INDEPENDENT_LONGEST) {
+        // one sequence: nothing to choose and nothing to move, the finish kernel writes the commit itself
+        const bool self_commit = sa.n == 1;
+        DUO_LAUNCH(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
+        if (self_commit) return;
+    } else {
         DUO_LAUNCH(sample_paper_kernel, dim3(1), dim3(SAMPLE_THREADS), s, sa);
+    }
     CommitArgs ca{kc, vc, c ? c->n_kv_heads : 1, c ? c->head_dim : 0, c ? c->max_seq : 0, sa.P, sa.R, sa.n, sa.k, mode,
                   sa.accept_len, sa.next_token, sa.commit, prefix_len};
     const dim3 grid = kc ? dim3(c->n_kv_heads, c->n_layers) : dim3(1, 1);
@@ -388,8 +392,7 @@ int duo_verify(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* 
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
-    const RowPlan plan{call->host_prefix_len, R, call->n, call->k, M};
+    const RowPlan plan{call->host_prefix_len, R, call->n, call->k, M};  // the pass's first kernel clears *status
     float* logits = out->logits_out ? out->logits_out : ws.logits;
     enqueue_forward(*cfg, *w, *cache, draft_tokens, call->root_token, plan, ws, logits, out->status, s);
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, call->n, call->k, R, call->host_prefix_len,
@@ -415,8 +418,7 @@ int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, status, 1, 0);
-    const RowPlan plan{host_prefix_len, 0, 1, m, m};
+    const RowPlan plan{host_prefix_len, 0, 1, m, m};  // the pass's first kernel clears *status
     enqueue_forward(*cfg, *w, *cache, tokens, -1, plan, ws, ws.logits, status, s);
     DUO_LAUNCH(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), s,
                        ws.logits + (size_t)(m - 1) * cfg->vocab, cache->root_logits, cfg->vocab, cache->prefix_len,
@@ -497,8 +499,7 @@ int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_k
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
-    const RowPlan plan{call->host_prefix_len, R, 1, call->k, M};
+    const RowPlan plan{call->host_prefix_len, R, 1, call->k, M};  // the pass's first kernel clears *status
     float* logits = out->logits_out ? out->logits_out : ws.logits;
     enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s);
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, 1, call->k, R, call->host_prefix_len,

@@ -116,9 +116,12 @@ __global__ __launch_bounds__(512) void residual_reduce_kernel(const float* __res
     block_row_sum<8>(total, wsum, ssq_full + m);
 }
 
-// cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.
-__global__ void rope_table_kernel(RowPlan plan, int D, double theta, float* __restrict__ rc, float* __restrict__ rs) {
+// cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.  As the first kernel of a
+// pass it also clears the status word that the later kernels OR their flags into.
+__global__ void rope_table_kernel(RowPlan plan, int D, double theta, float* __restrict__ rc, float* __restrict__ rs,
+                                  int32_t* status) {
     const int m = blockIdx.x, half = D / 2;
+    if (m == 0 && threadIdx.x == 0 && status) *status = 0;
     if (m >= plan.M) return;
     for (int d = threadIdx.x; d < half; d += blockDim.x) {
         const double ang = (double)plan.pos(m) * pow(theta, -2.0 * (double)d / (double)D);

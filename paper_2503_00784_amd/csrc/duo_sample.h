@@ -225,7 +225,9 @@ __device__ __forceinline__ int leading_accepts(const SampleArgs& a, int i, int f
     return n;
 }
 
-__global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArgs a) {
+// self_commit (single-sequence calls): also write the commit record and advance the device prefix length, which
+// otherwise commit_kernel does after choosing among the sequences.
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArgs a, int self_commit, int32_t* prefix_len) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
     const int i = blockIdx.x;
@@ -235,6 +237,13 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArg
     if (threadIdx.x == 0) {
         a.accept_len[i] = acc_len;
         a.next_token[i] = tok;
+        if (self_commit) {
+            a.commit[0] = 0;
+            a.commit[1] = acc_len;
+            a.commit[2] = tok;
+            a.commit[3] = a.P + a.R + acc_len;
+            if (prefix_len) *prefix_len = a.P + a.R + acc_len;
+        }
     }
 }
 
