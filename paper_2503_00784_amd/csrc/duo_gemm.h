@@ -225,7 +225,7 @@ template <int MH, int NT, int NG, int NK, int PF, int AG, class Epi, bool HALF =
 __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W,
                                                                       int K, int split_steps, int ntiles, int quads,
                                                                       RowScale rsc, Epi epi) {
-    static_assert(!HALF || (MH == 1 && NK == 1), "the shared-tile layout holds at most eight rows");
+    static_assert(!HALF || MH == 1, "the shared-tile layout holds at most eight rows");
     constexpr int MT = HALF ? 1 : 2 * MH, NC = NG * NK, NTH = (NC + 1) * 64;
     constexpr int RS = NK * AG;        // K steps per round
     constexpr int BUF = RS * MT * 64;  // 16-byte chunks per ring buffer (one round)
