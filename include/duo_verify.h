@@ -99,10 +99,19 @@ int duo_pack_gate_up(const duo_model_config *cfg, const uint16_t *w_gate, const 
  * ((rows + 15) / 16) * 16 * K elements. */
 int duo_pack_activations(const uint16_t *src, int rows, int K, uint16_t *dst, void *hip_stream);
 
-/* KV cache, bf16, caller-owned.  Keys are stored after the rotary embedding as
- * k[layer][kv_head][slot][head_dim]; values are stored TRANSPOSED as
- * v[layer][kv_head][head_dim][slot] so that the P*V product reads eight consecutive slots of
- * one channel with a single 16-byte load.  Slots [0, *prefix_len) hold the shared prefix. */
+/* KV cache, bf16, caller-owned: k and v each hold n_layers * n_kv_heads planes of max_seq * head_dim
+ * elements (plane index layer * n_kv_heads + kv_head).  Inside a plane both are stored as the 1 KiB tiles the
+ * attention kernels feed to the matrix cores, 32 slots at a time, so that a wavefront fetches a tile with one
+ * fully coalesced load.  Keys are stored after the rotary embedding.  With D = head_dim, block B = slot / 32
+ * and w = slot % 32, the element (slot, channel d) of a plane is at
+ *   K: ((((B*2 + t) * (D/32) + d/32) * 64 + ((d%32)/8) * 16 + 4*(w/8) + w%4) * 8 + d%8,  t = (w%8)/4
+ *   V: (((B * (D/16) + d/16) * 64 + (w/8) * 16 + d%16) * 8 + w%8
+ * (V is in effect transposed: a lane's eight consecutive elements are eight consecutive slots of one channel).
+ * duo_k_cache_offset / duo_v_cache_offset evaluate these on the host.  Slots [0, *prefix_len) hold the shared
+ * prefix. */
+size_t duo_k_cache_offset(int head_dim, int slot, int channel);
+size_t duo_v_cache_offset(int head_dim, int slot, int channel);
+
 typedef struct duo_kv_cache {
     uint16_t *k;
     uint16_t *v;

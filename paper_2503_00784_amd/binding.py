@@ -22,7 +22,8 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
+           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_k_cache_offset",
+           "duo_v_cache_offset", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
            "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
 PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "residual_reduce", "gate_up_swiglu", "down_proj", "lm_head",
@@ -92,6 +93,9 @@ def load() -> C.CDLL:
     lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.duo_packed_elems.argtypes = [C.c_int, C.c_int]
     lib.duo_packed_elems.restype = C.c_size_t
+    for name in ("duo_k_cache_offset", "duo_v_cache_offset"):
+        getattr(lib, name).argtypes = [C.c_int, C.c_int, C.c_int]
+        getattr(lib, name).restype = C.c_size_t
     lib.duo_pack_matrix.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     lib.duo_pack_qkv.argtypes = [C.POINTER(ModelConfig), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.duo_pack_gate_up.argtypes = [C.POINTER(ModelConfig), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -147,6 +151,40 @@ def workspace_bytes(cfg: ModelConfig, max_rows: int) -> int:
     out = C.c_size_t(0)
     _check(load().duo_workspace_bytes(C.byref(cfg), max_rows, C.byref(out)), "duo_workspace_bytes")
     return out.value
+
+
+# KV-cache layouts (the formulas of include/duo_verify.h as tensor reshapes; argument marshalling only).
+# Row layout [..., slot, D] <-> tiled plane [..., max_seq * D].
+def k_rows_to_tiles(k):
+    """slot = (B, q, t, r) with w = 8q + 4t + r, channel = (ks, g, j)  ->  (B, t, ks, g, q, r, j)."""
+    *lead, S, D = k.shape
+    x = k.reshape(*lead, S // 32, 4, 2, 4, D // 32, 4, 8)
+    n = len(lead)
+    return x.permute(*range(n), n, n + 2, n + 4, n + 5, n + 1, n + 3, n + 6).contiguous().reshape(*lead, S * D)
+
+
+def k_tiles_to_rows(kt, D):
+    *lead, SD = kt.shape
+    S = SD // D
+    x = kt.reshape(*lead, S // 32, 2, D // 32, 4, 4, 4, 8)  # (B, t, ks, g, q, r, j)
+    n = len(lead)
+    return x.permute(*range(n), n, n + 4, n + 1, n + 5, n + 2, n + 3, n + 6).contiguous().reshape(*lead, S, D)
+
+
+def v_rows_to_tiles(v):
+    """slot = (B, g, j), channel = (dt, c)  ->  (B, dt, g, c, j)."""
+    *lead, S, D = v.shape
+    x = v.reshape(*lead, S // 32, 4, 8, D // 16, 16)
+    n = len(lead)
+    return x.permute(*range(n), n, n + 3, n + 1, n + 4, n + 2).contiguous().reshape(*lead, S * D)
+
+
+def v_tiles_to_rows(vt, D):
+    *lead, SD = vt.shape
+    S = SD // D
+    x = vt.reshape(*lead, S // 32, D // 16, 4, 16, 8)  # (B, dt, g, c, j)
+    n = len(lead)
+    return x.permute(*range(n), n, n + 2, n + 4, n + 1, n + 3).contiguous().reshape(*lead, S, D)
 
 
 def _ptr(t) -> Optional[int]:
@@ -239,8 +277,9 @@ class VerifyEngine:
         self.max_seq = max_seq
         self.weights = weights if weights is not None else DeviceWeights(shape, host_weights, device)
         L, H, D = shape.n_layers, shape.n_kv_heads, shape.head_dim
-        self.k = torch.zeros((L, H, max_seq, D), dtype=torch.int16, device=device)
-        self.vT = torch.zeros((L, H, D, max_seq), dtype=torch.int16, device=device)
+        # planes of max_seq * D elements in the library's tiled layouts (see k_rows_to_tiles / v_rows_to_tiles)
+        self.k = torch.zeros((L, H, max_seq * D), dtype=torch.int16, device=device)
+        self.vT = torch.zeros((L, H, max_seq * D), dtype=torch.int16, device=device)
         self.prefix_len = torch.zeros(1, dtype=torch.int32, device=device)
         self.root_logits = torch.zeros(shape.vocab, dtype=torch.float32, device=device)
         self.ws_bytes = workspace_bytes(self.cfg, max_rows)
@@ -256,11 +295,13 @@ class VerifyEngine:
     # ---- cache management (plain copies, no arithmetic)
     def load_cache(self, k_bits: np.ndarray, v_bits: np.ndarray, prefix_len: int,
                    root_logits: Optional[np.ndarray]) -> None:
-        """k_bits, v_bits: uint16 [L][Hkv][max_seq][D] (row layout); V is transposed on upload."""
+        """k_bits, v_bits: uint16 [L][Hkv][max_seq][D] (row layout); rearranged into the tiled layouts on upload."""
         torch = self.torch
-        self.k.copy_(torch.from_numpy(np.ascontiguousarray(k_bits).view(np.int16)))
+        k = torch.from_numpy(np.ascontiguousarray(k_bits).view(np.int16)).to(self.device)
+        self.k.copy_(k_rows_to_tiles(k).reshape(self.k.shape))
+        del k
         v = torch.from_numpy(np.ascontiguousarray(v_bits).view(np.int16)).to(self.device)
-        self.vT.copy_(v.permute(0, 1, 3, 2))
+        self.vT.copy_(v_rows_to_tiles(v).reshape(self.vT.shape))
         del v
         self.set_prefix_len(prefix_len)
         if root_logits is not None:
@@ -272,8 +313,9 @@ class VerifyEngine:
 
     def cache_to_host(self):
         """(k, v) as uint16 [L][Hkv][max_seq][D] in the row layout."""
-        k = self.k.cpu().numpy().view(np.uint16)
-        v = self.vT.permute(0, 1, 3, 2).contiguous().cpu().numpy().view(np.uint16)
+        D = self.shape.head_dim
+        k = k_tiles_to_rows(self.k, D).cpu().numpy().view(np.uint16)
+        v = v_tiles_to_rows(self.vT, D).cpu().numpy().view(np.uint16)
         return k, v
 
     # ---- entry points

@@ -275,7 +275,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
 
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
-        u16* vc = cache.v + (size_t)l * Hkv * D * c.max_seq;
+        u16* vc = cache.v + (size_t)l * Hkv * c.max_seq * D;
         EpiQKV eq{Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
         prof(DUO_PROF_QKV, s);
         launch_projection<2>(M, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), (l == 0 || down_split) ? norm_full : norm_part,
@@ -545,6 +545,9 @@ int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, in
     launch_gemm_rows<2>(rows, false, x, w, K, (N + 31) / 32, RowScale{nullptr, 0, 0.f, 0.f, nullptr}, e, s);
     return hip_ok(hipGetLastError(), "duo_skinny_gemm launch");
 }
+
+size_t duo_k_cache_offset(int head_dim, int slot, int channel) { return k_cache_offset(head_dim, slot, channel); }
+size_t duo_v_cache_offset(int head_dim, int slot, int channel) { return v_cache_offset(head_dim, slot, channel); }
 
 size_t duo_packed_elems(int N, int K) {
     if (N < 1 || K < 1) return 0;

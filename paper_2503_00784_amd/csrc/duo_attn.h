@@ -24,8 +24,8 @@ struct AttnArgs {
     const u16* q;  // queries as bf16 pairs: hi plane [rows][Hq*D], lo plane q_plane elements further on
     int ldq;
     size_t q_plane;
-    const u16* kc;  // this layer: [Hkv][max_seq][D]
-    const u16* vc;  // this layer: [Hkv][D][max_seq]
+    const u16* kc;  // this layer: [Hkv] planes of max_seq * D elements, tiled (k_cache_offset)
+    const u16* vc;  // this layer: [Hkv] planes of max_seq * D elements, tiled (v_cache_offset)
     int max_seq, group;
     RowPlan plan;
     int Ktot;             // P + M keys in play
@@ -133,28 +133,26 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
         for (int dt = 0; dt < DT; ++dt) o[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
-    const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
+    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + lane * 8;  // tiles are contiguous: lane l reads bytes 16*l ..
+    const u16* vbase = a.vc + (size_t)hk * a.max_seq * D + lane * 8;
     const int b0 = (cb * NWV + wave) * a.blocks_per_wave;
     int nb = (a.Ktot + 31) / 32 - b0;  // this wave's blocks
     nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
 
-    // K rows and V^T rows of one 32-key block, in MFMA operand layout.  S^T tile t, MFMA row 4g'+i' is
-    // key kb + 8g' + 4t + i'; V^T operand dt is (channel dt*16 + c, keys kb + 8g .. +8).
+    // K and V^T tiles of one 32-key block, stored in MFMA operand layout.  S^T tile t, MFMA row 4g'+i' is
+    // key kb + 8g' + 4t + i'; V^T operand dt is (channel dt*16 + c, keys kb + 8g .. +8).  Slots of the block at or
+    // beyond Ktot may hold anything: their scores are replaced by -inf (a select), their values zeroed.
     bf16x8 kf[2][2][KS], vf[2][DT];  // double buffered: the next block is loaded while this one is used
     auto load_k = [&](int buf, int kb) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            int key = kb + (c >> 2) * 8 + t * 4 + (c & 3);
-            key = key < a.Ktot ? key : a.Ktot - 1;
-            const u16* kp = kbase + (size_t)key * D;
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[buf][t][ks] = load_frag(kp + ks * 32);
-        }
+            for (int ks = 0; ks < KS; ++ks)
+                kf[buf][t][ks] = load_frag(kbase + ((size_t)((kb >> 5) * 2 + t) * KS + ks) * 512);
     };
     auto load_v = [&](int buf, int kb) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = load_frag(vbase + (size_t)dt * 16 * a.max_seq + kb);
+        for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = load_frag(vbase + ((size_t)(kb >> 5) * DT + dt) * 512);
     };
     // scores of block kb (buffer buf), then request the next block's values (kb_next < 0: none), then
     // softmax and P V; the next block's keys were requested before the call
@@ -351,8 +349,8 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
             ql[ks] = f.v;
         }
     }
-    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
-    const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
+    const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + lane * 8;
+    const u16* vbase = a.vc + (size_t)hk * a.max_seq * D + lane * 8;
     const int NB = (a.Ktot + 31) / 32;
     // block b of this wave is global block wave + 8*b (round-robin keeps the waves within one block of each other)
     int nb = (NB - wave + NWV - 1) / NWV;
@@ -362,19 +360,16 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
     auto load_v = [&](int b) {
         const int kb = (wave + NWV * b) * 32;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[b][dt] = load_frag(vbase + (size_t)dt * 16 * a.max_seq + kb);
+        for (int dt = 0; dt < DT; ++dt) vf[b][dt] = load_frag(vbase + ((size_t)(kb >> 5) * DT + dt) * 512);
     };
 #pragma unroll
     for (int b = 0; b < BATCH; ++b) {
         if (b < nb) {
-            const int kb = (wave + NWV * b) * 32;
+            const int blk = wave + NWV * b;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                int key = kb + (c >> 2) * 8 + t * 4 + (c & 3);
-                key = key < a.Ktot ? key : a.Ktot - 1;
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) kf[b][t][ks] = load_frag(kbase + (size_t)key * D + ks * 32);
-            }
+                for (int ks = 0; ks < KS; ++ks) kf[b][t][ks] = load_frag(kbase + ((size_t)(blk * 2 + t) * KS + ks) * 512);
         }
     }
     if (nb > 0) load_v(0);
@@ -527,24 +522,17 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
 
     if (wave == NWV) {
-        // ---- producer.  Tile j < KT is K tile (t = j / KS, ks = j % KS): lane (c, g) fetches key
-        // kb + 8*(c/4) + 4t + c%4 (clamped to the last key in play), channels 32ks + 8g .. +8; otherwise V^T
-        // tile dt = j - KT: channel 16dt + c, keys kb + 8g .. +8.  Blocks past the last one are clamped.
-        const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + g * 8;
-        const u16* vbase = a.vc + ((size_t)hk * D + c) * a.max_seq + g * 8;
+        // ---- producer.  The cache stores the tiles as they are needed (see k_cache_offset / v_cache_offset):
+        // tile j < KT of a block is K tile (t = j / KS, ks = j % KS), otherwise V^T tile dt = j - KT; each is 1 KiB,
+        // lane l takes bytes 16*l ..  Blocks past the last one are clamped.
+        const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + lane * 8;
+        const u16* vbase = a.vc + (size_t)hk * a.max_seq * D + lane * 8;
         auto issue = [&](int ib) {
-            const int kb = min(b0 + ib, NB - 1) * 32;
+            const int blk = min(b0 + ib, NB - 1);
             u32x4* dst = lds_kv[ib % NBUF];
 #pragma unroll
             for (int j = 0; j < TILES; ++j) {
-                const u16* src;
-                if (j < KT) {
-                    int key = kb + (c >> 2) * 8 + (j / KS) * 4 + (c & 3);
-                    key = key < a.Ktot ? key : a.Ktot - 1;
-                    src = kbase + (size_t)key * D + (j % KS) * 32;
-                } else {
-                    src = vbase + (size_t)(j - KT) * 16 * a.max_seq + kb;
-                }
+                const u16* src = j < KT ? kbase + ((size_t)blk * KT + j) * 512 : vbase + ((size_t)blk * DT + (j - KT)) * 512;
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                                  (__attribute__((address_space(3))) void*)(dst + j * 64), 16, 0, 0);
             }

@@ -95,6 +95,26 @@ __device__ __forceinline__ double wave_max(double v) {
     return v;
 }
 
+// KV-cache layout inside one (layer, kv head) plane of max_seq * D elements.  Both caches are stored as the
+// 1 KiB MFMA operand tiles the attention kernels consume, 32 slots (one key block) at a time, so that a wave
+// fetches a tile with one fully coalesced load (lane l reads bytes 16*l .. 16*l+15) instead of sixteen half
+// cache lines.
+//   K: block B = slot / 32 holds 2 * D/32 tiles, tile (t, ks) = 16 keys x 32 channels.  Lane (c = l % 16,
+//      g = l / 16) holds key 8*(c/4) + 4*t + c%4 of the block, channels 32*ks + 8*g .. +8: the key order
+//      that lets the score accumulator of a lane be the softmax-weight operand of the same lane.
+//   V: block B holds D/16 tiles, tile dt = 16 channels x 32 keys.  Lane (c, g) holds channel 16*dt + c,
+//      keys 8*g .. 8*g+7 of the block (V transposed: the P*V product contracts over keys).
+__host__ __device__ __forceinline__ size_t k_cache_offset(int D, int slot, int d) {
+    const int B = slot >> 5, w = slot & 31, q = w >> 3, t = (w >> 2) & 1, r = w & 3;
+    const int ks = d >> 5, g = (d >> 3) & 3, j = d & 7;
+    return ((((size_t)B * 2 + t) * (D >> 5) + ks) * 64 + g * 16 + q * 4 + r) * 8 + j;
+}
+__host__ __device__ __forceinline__ size_t v_cache_offset(int D, int slot, int d) {
+    const int B = slot >> 5, w = slot & 31, g = w >> 3, j = w & 7;
+    const int dt = d >> 4, c = d & 15;
+    return (((size_t)B * (D >> 4) + dt) * 64 + g * 16 + c) * 8 + j;
+}
+
 // Row bookkeeping of one pass: row m -> (sequence, index in sequence, position, slot).
 struct RowPlan {
     int P;       // prefix length

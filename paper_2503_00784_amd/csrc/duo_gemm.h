@@ -526,14 +526,14 @@ struct EpiSwiGLU {
 // Fused Q/K/V projection: a workgroup's two bands are rows d.. and d + D/2.. of one head, the two
 // halves of a rotary pair, so the rotation is thread-local.  Q goes to the query buffer as a bf16 pair
 // (hi plane, lo plane), K
-// (rotated) and V into their cache slots; V is stored transposed [head][d][slot].
+// (rotated) and V into their cache slots (tiled layouts, see k_cache_offset / v_cache_offset).
 struct EpiQKV {
     int Hq, Hkv, D, half, bph;  // bph = (D/2)/16 workgroup tiles per head
     u16* q_out;  // hi plane; the lo plane starts q_plane elements further on
     int ldq;
     size_t q_plane;
-    u16* kc;  // this layer: [Hkv][max_seq][D]
-    u16* vc;  // this layer: [Hkv][D][max_seq]
+    u16* kc;  // this layer: [Hkv] planes of max_seq * D elements in the tiled layouts (k_cache_offset,
+    u16* vc;  //             v_cache_offset)
     int max_seq;
     const float* rope_cos;  // [rows][D/2]
     const float* rope_sin;
@@ -572,14 +572,14 @@ struct EpiQKV {
                     q[q_plane] = f32_to_bf16(rl - bf16_to_f32(l1));
                     q[q_plane + half] = f32_to_bf16(rh - bf16_to_f32(h1));
                 } else {
-                    u16* kp = kc + ((size_t)(head - Hq) * max_seq + plan.slot(m)) * D + d;
-                    kp[0] = f32_to_bf16(rl);
-                    kp[half] = f32_to_bf16(rh);
+                    u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
+                    kp[k_cache_offset(D, plan.slot(m), d)] = f32_to_bf16(rl);
+                    kp[k_cache_offset(D, plan.slot(m), d + half)] = f32_to_bf16(rh);
                 }
             } else {
-                u16* vp = vc + ((size_t)(head - Hq - Hkv) * D + d) * max_seq + plan.slot(m);
-                vp[0] = f32_to_bf16(lo);
-                vp[(size_t)half * max_seq] = f32_to_bf16(hi);
+                u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
+                vp[v_cache_offset(D, plan.slot(m), d)] = f32_to_bf16(lo);
+                vp[v_cache_offset(D, plan.slot(m), d + half)] = f32_to_bf16(hi);
             }
         }
     }

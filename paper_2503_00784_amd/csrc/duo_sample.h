@@ -355,8 +355,8 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleA
 }
 
 struct CommitArgs {
-    u16* kc;  // [L][Hkv][max_seq][D]
-    u16* vc;  // [L][Hkv][D][max_seq]
+    u16* kc;  // [L][Hkv] planes of max_seq * D elements, tiled layouts (k_cache_offset, v_cache_offset)
+    u16* vc;
     int Hkv, D, max_seq;
     int P, R, n, k, mode;
     const int32_t* accept_len;
@@ -388,11 +388,12 @@ __global__ __launch_bounds__(256) void commit_kernel(CommitArgs a) {
         const int hk = blockIdx.x, l = blockIdx.y;
         const int src = a.P + a.R + sel * a.k, dst = a.P + a.R;
         u16* kp = a.kc + ((size_t)l * a.Hkv + hk) * a.max_seq * a.D;
-        for (int e = threadIdx.x; e < len * a.D; e += 256) kp[(size_t)dst * a.D + e] = kp[(size_t)src * a.D + e];
-        u16* vp = a.vc + ((size_t)l * a.Hkv + hk) * a.D * a.max_seq;
+        u16* vp = a.vc + ((size_t)l * a.Hkv + hk) * a.max_seq * a.D;
+        // source rows [src, src + len) and destination rows [dst, dst + len) never overlap: src - dst = sel * k >= len
         for (int e = threadIdx.x; e < len * a.D; e += 256) {
-            const int d = e / len, j = e - d * len;
-            vp[(size_t)d * a.max_seq + dst + j] = vp[(size_t)d * a.max_seq + src + j];
+            const int j = e / a.D, d = e - j * a.D;
+            kp[k_cache_offset(a.D, dst + j, d)] = kp[k_cache_offset(a.D, src + j, d)];
+            vp[v_cache_offset(a.D, dst + j, d)] = vp[v_cache_offset(a.D, src + j, d)];
         }
     }
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {

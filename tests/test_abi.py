@@ -149,3 +149,30 @@ def test_input_generators_are_seeded_and_shaped():
     wl = inputs.WORKLOADS["C3"]
     assert abs(wl.algorithmic_bytes() / 1e9 - 15.362) < 0.005 and abs(wl.shape.weight_bytes() / 1e9 - 13.214) < 0.005
     assert abs(inputs.WORKLOADS["C1"].algorithmic_bytes() / 1e9 - 13.483) < 0.005
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_kv_cache_layout_formulas_agree_with_the_binding(D):
+    """The tiled KV-cache layouts: the library's host-side offset functions, the formulas printed in the header and
+    the binding's reshapes address the same element; the reshapes are inverses of each other."""
+    import torch
+    lib = B.load()
+    S = 96
+    rows = torch.arange(S * D, dtype=torch.int32).reshape(1, 1, S, D)  # unique values, leading [layer][head] axes
+    kt, vt = B.k_rows_to_tiles(rows), B.v_rows_to_tiles(rows)
+    assert kt.shape == (1, 1, S * D) and vt.shape == (1, 1, S * D)
+    g = np.random.default_rng(D)
+    for slot, d in zip(g.integers(0, S, 200), g.integers(0, D, 200)):
+        slot, d = int(slot), int(d)
+        Bk, w = slot // 32, slot % 32
+        t = (w % 8) // 4
+        k_off = ((((Bk * 2 + t) * (D // 32) + d // 32) * 64 + ((d % 32) // 8) * 16 + 4 * (w // 8) + w % 4) * 8 + d % 8)
+        v_off = (((Bk * (D // 16) + d // 16) * 64 + (w // 8) * 16 + d % 16) * 8 + w % 8)
+        assert lib.duo_k_cache_offset(D, slot, d) == k_off
+        assert lib.duo_v_cache_offset(D, slot, d) == v_off
+        assert int(kt[0, 0, k_off]) == int(rows[0, 0, slot, d])
+        assert int(vt[0, 0, v_off]) == int(rows[0, 0, slot, d])
+    assert torch.equal(B.k_tiles_to_rows(kt, D), rows)
+    assert torch.equal(B.v_tiles_to_rows(vt, D), rows)
+    # every offset is hit exactly once
+    assert sorted(kt.flatten().tolist()) == sorted(rows.flatten().tolist())
