@@ -318,13 +318,13 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
 // in one workgroup of eight waves, no loop.  A wave requests the keys of ALL its blocks and the values
 // of the first one at once, forms every score, requests the remaining values into the registers the
 // keys just left, does one plain softmax over its keys and the P V products; then the waves are merged
-// by the same LDS tree and wave 0 writes the normalised output.  One memory latency for the keys and
+// through LDS in one step and every wave writes one 16-channel tile of the normalised output.  One memory latency for the keys and
 // one for the values, instead of one per block.
 template <int D, int BATCH>
 __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
-    constexpr int KS = D / 32, DT = D / 16, NWV = 8, NBUF = NWV / 2;
-    __shared__ f32x4 lds_o[NBUF][DT * 64];
-    __shared__ float lds_ml[NBUF][2][16];
+    constexpr int KS = D / 32, DT = D / 16, NWV = 8;
+    __shared__ f32x4 lds_o[NWV][DT * 64];
+    __shared__ float lds_ml[NWV][2][16];
 
     const int hk = blockIdx.y;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -454,44 +454,38 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
 
-    // merge the eight waves through LDS in a fixed binary tree: wave w + s -> wave w for s = 4, 2, 1
+    // Merge of the eight waves in one step: every wave leaves its unnormalised output, maximum and sum in LDS;
+    // after one barrier wave w combines channel tile w of all eight (in wave order), normalises and stores it.
 #pragma unroll
-    for (int s = NWV / 2; s >= 1; s >>= 1) {
-        if (wave >= s && wave < 2 * s) {
-            const int buf = wave - s;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) lds_o[buf][dt * 64 + lane] = o[dt];
-            if (g == 0) {
-                lds_ml[buf][0][c] = m_run;
-                lds_ml[buf][1][c] = l_run;
-            }
-        }
-        __syncthreads();
-        if (wave < s) {
-            const float mo = lds_ml[wave][0][c], lo = lds_ml[wave][1][c];
-            const float mn = fmaxf(m_run, mo);
-            const float ms = mn == -INFINITY ? 0.f : mn;
-            const float sa = exp2f(m_run - ms), sb = exp2f(mo - ms);
-            m_run = mn;
-            l_run = l_run * sa + lo * sb;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * sa + lds_o[wave][dt * 64 + lane] * sb;
-        }
-        __syncthreads();
+    for (int dt = 0; dt < DT; ++dt) lds_o[wave][dt * 64 + lane] = o[dt];
+    if (g == 0) {
+        lds_ml[wave][0][c] = m_run;
+        lds_ml[wave][1][c] = l_run;
     }
-    if (wave != 0 || !ok) return;
+    __syncthreads();
+    if (wave >= DT || !ok) return;
+    float mall = lds_ml[0][0][c];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) mall = fmaxf(mall, lds_ml[w][0][c]);
+    float L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) {
+        const float mw = lds_ml[w][0][c];
+        const float sw = mw == -INFINITY ? 0.f : exp2f(mw - mall);
+        L += lds_ml[w][1][c] * sw;
+        acc += lds_o[w][wave * 64 + lane] * sw;
+    }
     const int col0 = (hk * a.group + gq) * D;
-    const float inv = 1.0f / l_run;
+    const float inv = 1.0f / L;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float v = o[dt][i] * inv;
-            const u16 hi = f32_to_bf16(v);
-            const int col = col0 + dt * 16 + g * 4 + i;
-            a.out[operand_offset(m, col, a.out_tiles)] = hi;
-            a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
-        }
+    for (int i = 0; i < 4; ++i) {
+        const float v = acc[i] * inv;
+        const u16 hi = f32_to_bf16(v);
+        const int col = col0 + wave * 16 + g * 4 + i;
+        a.out[operand_offset(m, col, a.out_tiles)] = hi;
+        a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+    }
 }
 
 // Many query rows per kv head (more than two 16-row query tiles: many draft rows and/or a large GQA
