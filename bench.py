@@ -43,6 +43,10 @@ def main() -> int:
     ap.add_argument("--draft-step-ms", type=float, default=0.0,
                     help="with --k-sweep: time of one draft-model step on the host; adds the cost coefficient c(k) and the "
                     "balanced draft budget gamma")
+    ap.add_argument("--prefill-tokens", type=int, default=0,
+                    help="also time the prefill of this many prompt tokens from an empty cache (time to first token of the "
+                    "target model, Sec. 4.1) and add \"prefill\" to the line")
+    ap.add_argument("--prefill-chunk", type=int, default=80, help="rows per prefill forward pass (at most 80)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -67,7 +71,7 @@ def main() -> int:
 
     wl = inputs.WORKLOADS[args.workload]
     shape, P, n, k = wl.shape, wl.prefix_len, wl.n_seq, wl.k_draft
-    max_seq = (P + n * k + 1 + 31) // 32 * 32 + 32
+    max_seq = (max(P + n * k + 1, args.prefill_tokens) + 31) // 32 * 32 + 32
     t0 = time.time()
     log(f"[bench] workload {wl.name}: generating weights ({shape.weight_bytes() / 1e9:.2f} GB) ...")
     w = inputs.make_weights(shape, seed=args.seed, threads=16)
@@ -198,6 +202,21 @@ def main() -> int:
             out["k_sweep"]["cost_coefficient_by_k"] = {str(kk): round(c, 2)
                                                        for kk, c in budget.cost_coefficient(curve, args.draft_step_ms).items()}
             out["k_sweep"]["draft_budget"] = budget.draft_budget(curve, args.draft_step_ms)
+
+    if args.prefill_tokens > 0:
+        prompt = np.random.default_rng(args.seed + 7).integers(0, shape.vocab, size=args.prefill_tokens).tolist()
+        with torch.cuda.stream(stream):
+            times = []
+            for _ in range(3):
+                eng.set_prefix_len(0)
+                stream.synchronize()
+                t6 = time.perf_counter()
+                eng.prefill(prompt, chunk=args.prefill_chunk)
+                stream.synchronize()
+                times.append(time.perf_counter() - t6)
+        best = min(times)
+        out["prefill"] = {"tokens": args.prefill_tokens, "chunk": args.prefill_chunk, "ms": round(best * 1e3, 3),
+                          "tok_per_s": round(args.prefill_tokens / best, 1), "launch": "eager"}
 
     if not args.no_cpu_baseline:
         from oracle import duo_oracle as O
