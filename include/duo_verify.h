@@ -39,7 +39,7 @@ extern "C" {
 #define DUO_ERR_WORKSPACE   -5  /* workspace smaller than duo_workspace_bytes() */
 #define DUO_ERR_TOKEN_RANGE -6  /* root_token >= vocab */
 #define DUO_ERR_HIP         -7  /* a HIP call failed; see duo_last_hip_error() */
-#define DUO_ERR_ARG         -8  /* temperature <= 0, unknown select_mode, ... */
+#define DUO_ERR_ARG         -8  /* temperature < 0 or NaN, unknown select_mode, ... */
 
 /* Most rows one call can score: n*k (+1 with a root token). */
 #define DUO_MAX_ROWS 80
@@ -122,7 +122,10 @@ typedef struct duo_kv_cache {
 
 typedef struct duo_call {
     int32_t n, k;            /* n sequences of k draft tokens, n*k + (root?1:0) <= DUO_MAX_ROWS */
-    float   temperature;     /* p = softmax(logits / temperature), > 0 */
+    float   temperature;     /* p = softmax(logits / temperature), > 0; exactly 0 = the greedy limit of Alg. 2: p is
+                                one-hot at the largest logit (lowest id among equal logits), so a draft token is
+                                accepted iff it is that id and every correction / bonus token is that id; the
+                                uniforms are still read but cannot change the outcome */
     int32_t select_mode;     /* DUO_SELECT_* */
     int32_t root_token;      /* >= 0: the token emitted by the previous step, scored as one shared
                                 row in front of every sequence (its logits judge the first draft

@@ -272,8 +272,20 @@ def full_forward_uncached(shape: OracleShape, weights: Dict[str, object], tokens
 
 # ----------------------------------------------------------------------------- sampling
 def target_probs(logits_f32: np.ndarray, temperature: float) -> np.ndarray:
-    """p = softmax(logits / T) in float64 from float32 logits."""
-    z = np.asarray(logits_f32, dtype=np.float32).astype(np.float64) / float(temperature)
+    """p = softmax(logits / T) in float64 from float32 logits.
+
+    T = 0 is the limit T -> 0+: all mass on the largest logit, on the lowest id among equal ones
+    (the greedy setting; Alg. 2 is then applied to this one-hot p without any other change).
+    """
+    l32 = np.asarray(logits_f32, dtype=np.float32)
+    if float(temperature) == 0.0:
+        p = np.zeros(l32.shape, dtype=np.float64)
+        if l32.ndim == 1:
+            p[int(np.argmax(l32))] = 1.0
+        else:
+            p[np.arange(l32.shape[0]), np.argmax(l32, axis=-1)] = 1.0
+        return p
+    z = l32.astype(np.float64) / float(temperature)
     return softmax(z)
 
 

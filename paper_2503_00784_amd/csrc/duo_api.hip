@@ -344,7 +344,7 @@ int check_call(const duo_call* call, int vocab) {
     if (call->n < 1 || call->k < 1) return DUO_ERR_SHAPE;
     const int R = call->root_token >= 0 ? 1 : 0;
     if ((long long)call->n * call->k + R > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
-    if (!(call->temperature > 0.f)) return DUO_ERR_ARG;
+    if (!(call->temperature >= 0.f)) return DUO_ERR_ARG;  // 0 is the greedy limit; NaN fails the comparison
     if (call->select_mode != DUO_SELECT_INDEPENDENT_LONGEST && call->select_mode != DUO_SELECT_PAPER_SEQUENTIAL)
         return DUO_ERR_ARG;
     if (call->root_token >= vocab) return DUO_ERR_TOKEN_RANGE;

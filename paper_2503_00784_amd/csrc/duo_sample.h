@@ -12,6 +12,12 @@
 //   sample_deferred_kernel  Alg. 2 as listed: verify the unverified suffix, then judge only the first
 //                         tokens of the new sequences
 //   commit_kernel         picks the sequence to keep, moves its accepted K/V next to the prefix
+//
+// T = 0 is the greedy limit of the same rule: softmax(logits / T) tends to the one-hot distribution at the
+// largest logit (lowest id among equals), so a draft token is accepted exactly when it is that id, and every
+// correction or bonus token is that id (p(t) in {0, 1} in u * q(t) < p(t); the residual of a one-hot p is the
+// same one-hot unless q already puts all its mass there).  The statistics then hold the arg max instead of the
+// normaliser; everything else runs unchanged on the one-hot p.
 #pragma once
 #include "duo_common.h"
 
@@ -20,11 +26,12 @@ struct SampleArgs {
     int ld;
     const float* root_logits;  // fp32 [V], judges first tokens when R == 0
     int V, n, k, R, P;
-    double T;
+    double T;               // temperature; 0 selects the greedy limit
     const int32_t* tokens;  // [n][k]
     const float* q;         // [n][k][V]
     const float* u;         // [n][k+1]
-    double* stats;          // [n][k+1][STATS_SPLIT][2]: per vocabulary slice, max of z = logit / T and sum exp(z - max)
+    double* stats;          // [n][k+1][STATS_SPLIT][2]: per vocabulary slice, max of z = logit / T and sum exp(z - max);
+                            // greedy: max logit and the lowest id that attains it
     int32_t* acc;           // [n][k] accept flags
     double* p_run;          // [V] running distribution of the sequential rule
     int32_t* accept_len;    // [n]
@@ -35,6 +42,7 @@ struct SampleArgs {
         if (j == 0) return R ? logits : root_logits;
         return logits + (size_t)(R + i * k + j - 1) * ld;
     }
+    __device__ __forceinline__ bool greedy() const { return T == 0.0; }
     __device__ __forceinline__ int token(int i, int j) const {
         int t = tokens[i * k + j];
         return t < 0 ? 0 : (t >= V ? V - 1 : t);
@@ -74,10 +82,19 @@ __global__ __launch_bounds__(256) void sample_stats_kernel(SampleArgs a) {
     const int v0 = sl * len, v1 = min(a.V, v0 + len);
     float lm = -INFINITY;
     for (int v = v0 + threadIdx.x; v < v1; v += 256) lm = fmaxf(lm, row[v]);
-    const double zmax = block_max_d((double)lm, sm) / a.T;
-    double s = 0.0;
-    for (int v = v0 + threadIdx.x; v < v1; v += 256) s += exp((double)row[v] / a.T - zmax);
-    const double Z = block_sum_d(s, sm);
+    double zmax, Z;
+    if (a.greedy()) {  // Z: the lowest id of the slice that holds the slice's largest logit
+        zmax = block_max_d((double)lm, sm);
+        int first = a.V;
+        for (int v = v0 + threadIdx.x; v < v1; v += 256)
+            if ((double)row[v] == zmax) first = min(first, v);
+        Z = -block_max_d(-(double)first, sm);
+    } else {
+        zmax = block_max_d((double)lm, sm) / a.T;
+        double s = 0.0;
+        for (int v = v0 + threadIdx.x; v < v1; v += 256) s += exp((double)row[v] / a.T - zmax);
+        Z = block_sum_d(s, sm);
+    }
     if (threadIdx.x == 0) {
         double* st = a.stats + (((size_t)i * (a.k + 1) + j) * STATS_SPLIT + sl) * 2;
         st[0] = zmax;
@@ -99,15 +116,47 @@ __device__ __forceinline__ void merged_stats(const SampleArgs& a, int i, int j, 
         if (st[2 * s + 1] > 0.0) Z += st[2 * s + 1] * exp(st[2 * s] - zmax);
 }
 
+// greedy: the arg max of judging distribution (i, j), lowest id among equal logits (slices are in id order)
+__device__ __forceinline__ int merged_argmax(const SampleArgs& a, int i, int j) {
+    const double* st = a.stats + ((size_t)i * (a.k + 1) + j) * STATS_SPLIT * 2;
+    double best = st[0];
+    int arg = (int)st[1];
+    for (int s = 1; s < STATS_SPLIT; ++s)
+        if (st[2 * s] > best) {
+            best = st[2 * s];
+            arg = (int)st[2 * s + 1];
+        }
+    return arg;
+}
+
+// p_run[v] = p(v) of judging distribution (i, j) for the whole vocabulary; ends with a barrier
+__device__ __forceinline__ void fill_running_distribution(const SampleArgs& a, int i, int j) {
+    const float* row = a.judge_row(i, j);
+    if (a.greedy()) {
+        const int amax = merged_argmax(a, i, j);
+        for (int v = threadIdx.x; v < a.V; v += blockDim.x) a.p_run[v] = v == amax ? 1.0 : 0.0;
+    } else {
+        double zmax, Z;
+        merged_stats(a, i, j, zmax, Z);
+        for (int v = threadIdx.x; v < a.V; v += blockDim.x) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
+    }
+    __syncthreads();
+}
+
 // accept flags of sequence i, positions from..k-1 (one thread each), into acc[]; ends with a barrier
 __device__ __forceinline__ void accept_flags(const SampleArgs& a, int i, int from) {
     const int j = from + threadIdx.x;
     if (j < a.k) {
-        double zmax, Z;
-        merged_stats(a, i, j, zmax, Z);
         const float* row = a.judge_row(i, j);
         const int t = a.token(i, j);
-        const double p_t = exp((double)row[t] / a.T - zmax) / Z;
+        double p_t;
+        if (a.greedy()) {
+            p_t = t == merged_argmax(a, i, j) ? 1.0 : 0.0;
+        } else {
+            double zmax, Z;
+            merged_stats(a, i, j, zmax, Z);
+            p_t = exp((double)row[t] / a.T - zmax) / Z;
+        }
         const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
         a.acc[i * a.k + j] = lhs < p_t ? 1 : 0;
     }
@@ -203,6 +252,18 @@ __device__ int block_inverse_cdf(F w, int V, double u, double* sm_d, int* sm_i) 
 // Correction / bonus token of sequence i after `a` accepted drafts.
 __device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_d, int* sm_i) {
     const float* row = a.judge_row(i, acc_len);
+    if (a.greedy()) {  // one-hot p: same two draws over the one-hot weights
+        const int amax = merged_argmax(a, i, acc_len);
+        const double ug = (double)a.u[i * (a.k + 1) + a.k];
+        auto pg = [=](int v) { return v == amax ? 1.0 : 0.0; };
+        if (acc_len < a.k) {
+            const float* qrow = a.q + ((size_t)i * a.k + acc_len) * a.V;
+            auto rg = [=](int v) { return fmax((v == amax ? 1.0 : 0.0) - (double)qrow[v], 0.0); };
+            const int tok = block_inverse_cdf(rg, a.V, ug, sm_d, sm_i);
+            if (tok >= 0) return tok;
+        }
+        return block_inverse_cdf(pg, a.V, ug, sm_d, sm_i);
+    }
     double zmax, Z;
     merged_stats(a, i, acc_len, zmax, Z);
     // reciprocals once per call instead of two divisions per vocabulary entry (the single workgroup is
@@ -276,13 +337,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
     const int tid = threadIdx.x;
-    {
-        const float* row = a.judge_row(0, 0);
-        double zmax, Z;
-        merged_stats(a, 0, 0, zmax, Z);
-        for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
-    }
-    __syncthreads();
+    fill_running_distribution(a, 0, 0);
     const int sel = sequential_first_tokens(a.p_run, a.V, a.n, a.tokens, a.k, a.q, (size_t)a.k * a.V, a.u, a.k + 1, sm_d);
     int acc_len = 0, tok;
     if (sel < 0) {
@@ -330,11 +385,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleA
     if (acc_len < a.k) {
         tok = finish_token(a, 0, acc_len, sm_d, sm_i);  // residual draw at the first rejection
     } else {
-        const float* row = a.judge_row(0, a.k);  // the distribution after the last scored token
-        double zmax, Z;
-        merged_stats(a, 0, a.k, zmax, Z);
-        for (int v = tid; v < a.V; v += SAMPLE_THREADS) a.p_run[v] = exp((double)row[v] / a.T - zmax) / Z;
-        __syncthreads();
+        fill_running_distribution(a, 0, a.k);  // the distribution after the last scored token
         sel = sequential_first_tokens(a.p_run, a.V, d.s, d.first_tokens, 1, d.first_probs, (size_t)a.V, d.uniforms_first, 1,
                                       sm_d);
         if (sel < 0) {

@@ -89,6 +89,36 @@ def test_deferred_sampler_bit_exact_on_identical_logits(B, V, l, s, scenario):
         assert branches == {"final"}
 
 
+@pytest.mark.parametrize("V,l,s", [(4099, 4, 3), (32000, 6, 2), (50, 2, 0)])
+@pytest.mark.parametrize("variant", ["suffix_breaks", "second_new", "none_new"])
+def test_deferred_sampler_greedy_limit(B, V, l, s, variant):
+    """Temperature 0 in the deferred form: one-hot target distributions on both sides."""
+    say(f"greedy deferred sampler V={V} l={l} s={s} variant={variant}")
+    root, logits, q, toks, u, fq, ftoks, fu = _case(V, l, s, 3, "argmax", True)
+    best_next = int(np.argmax(logits[l - 1]))
+    if variant == "suffix_breaks":
+        toks[l - 1] = (toks[l - 1] + 1) % V
+    for i in range(s):
+        ftoks[i] = (best_next + 1 + i) % V
+    if variant == "second_new" and s >= 2:
+        ftoks[1] = best_next
+    judge = [root] + [logits[m] for m in range(l - 1)]
+    x = [4, 5]
+    ref = _oracle_outcome(x, toks.tolist(), judge, logits[l - 1], q, u[:l], ftoks, fq, fu, u[l], 0.0)
+    got = B.deferred_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u),
+                            to_dev(ftoks) if s else None, to_dev(fq) if s else None, to_dev(fu) if s else None,
+                            temperature=0.0, has_root=False, prefix_len=2)
+    assert got["status"] == 0
+    out = _gpu_outcome(x, toks.tolist(), got, ftoks)
+    assert out[0] == ref[0], (out, ref, got)
+    if variant == "suffix_breaks":
+        assert got["accept_len"] == l - 1 and got["next_token"] == int(np.argmax(judge[l - 1]))
+    elif variant == "second_new" and s >= 2:
+        assert got["accept_len"] == l and got["selected"] == 1
+    else:
+        assert got["accept_len"] == l and got["selected"] == -1 and got["next_token"] == best_next
+
+
 def test_deferred_sampler_flags_out_of_range_first_token(B):
     root, logits, q, toks, u, fq, ftoks, fu = _case(50, 2, 2, 0, "accept_all", False)
     ftoks[1] = 50

@@ -77,6 +77,37 @@ def test_sampler_bit_exact_on_identical_logits(B, V, n, k, has_root, peaked, mod
     assert ties < total
 
 
+@pytest.mark.parametrize("V,n,k,has_root", [(32000, 1, 8, False), (32000, 4, 8, True), (4099, 3, 5, False),
+                                            (128256, 2, 16, False), (50, 2, 3, True)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_sampler_greedy_limit_bit_exact(B, V, n, k, has_root, mode):
+    """Temperature 0: one-hot target distributions (arg max, lowest id among equal logits) on both sides."""
+    for seed in range(3):
+        say(f"greedy sampler V={V} n={n} k={k} root={has_root} mode={mode} seed={seed}")
+        logits, root, q, toks, u = _sampling_case(V, n, k, seed, has_root, True)
+        if seed == 2:  # equal largest logits in every row, some of them across the sampler's vocabulary slices
+            for r in range(logits.shape[0]):
+                a = int(np.argmax(logits[r]))
+                logits[r, (a + V // 2) % V] = logits[r, a]
+                logits[r, (a + 1) % V] = logits[r, a]
+            root[(int(np.argmax(root)) + V // 3) % V] = root.max()
+        ref = O.speculative_verify(logits, root, toks, q, u, prefix_len=100, temperature=0.0, select_mode=mode,
+                                   has_root=has_root)
+        got = B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u), temperature=0.0,
+                            select_mode=mode, has_root=has_root, prefix_len=100)
+        assert got["status"] == 0
+        np.testing.assert_array_equal(got["accept_len"], ref.accept_len)
+        np.testing.assert_array_equal(got["next_token"], ref.next_token)
+        assert (got["selected"], got["commit_len"], got["commit_token"], got["new_prefix_len"]) == \
+               (ref.selected, ref.commit_len, ref.commit_token, ref.new_prefix_len)
+
+
+def test_negative_temperature_is_rejected(B):
+    logits, root, q, toks, u = _sampling_case(50, 1, 2, 0, False, False)
+    with pytest.raises(B.DuoError):
+        B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u), temperature=-1.0)
+
+
 def test_sampler_flags_out_of_range_token(B):
     logits, root, q, toks, u = _sampling_case(50, 1, 2, 0, False, False)
     toks[0, 1] = 50
@@ -174,6 +205,40 @@ def test_mid_config_gqa_ragged(B, n, k, mode, root):
     got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 31 + k, mode=mode, root_token=root)
     if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
         _check_cache(eng, cache, cache.prefix_len)
+
+
+@pytest.mark.parametrize("mode,root", [(0, -1), (1, 12)])
+def test_mid_config_greedy_step(B, mode, root):
+    """A whole step at temperature 0.  The logits are compared as always; the decisions are the arg-max rule applied to
+    the logits the GPU returned (an arg max taken on the oracle's own logits could differ at near-equal logits)."""
+    import torch
+    shape = inputs.MID
+    n, k = 3, 5
+    say(f"MID greedy mode={mode} root={root}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False)
+    q, toks, u = inputs.make_draft(shape.vocab, n, k, seed=5)
+    # make the drafts follow the oracle's arg max for a while, so that accepted lengths are not all zero
+    ol = O.verify_forward(oshape, w, cache, toks, root).astype(np.float32)  # the forward pass alone commits nothing
+    R = 1 if root >= 0 else 0
+    toks[1, 0] = int(np.argmax(ol[0] if R else cache.root_logits))
+    ol = O.verify_forward(oshape, w, cache, toks, root).astype(np.float32)
+    toks[1, 1] = int(np.argmax(ol[R + k]))
+    lg = torch.empty((R + n * k, shape.vocab), dtype=torch.float32, device="cuda")
+    eng.verify(to_dev(toks), to_dev(q), to_dev(u), temperature=0.0, select_mode=mode, root_token=root, logits_out=lg)
+    got = eng.results(n)
+    assert got["status"] == 0
+    gl = lg.cpu().numpy()
+    ol = O.verify_forward(oshape, w, cache, toks, root).astype(np.float32)
+    ok, max_abs, worst = logits_close(gl, ol)
+    assert ok, (max_abs, worst)
+    ref = O.speculative_verify(gl, eng.root_logits.cpu().numpy(), toks, q, u, prefix_len=77, temperature=0.0,
+                               select_mode=mode, has_root=bool(R))
+    say(f"  gpu accept {got['accept_len']} commit {got['selected']}/{got['commit_len']}/{got['commit_token']}")
+    np.testing.assert_array_equal(got["accept_len"], ref.accept_len)
+    np.testing.assert_array_equal(got["next_token"], ref.next_token)
+    assert (got["selected"], got["commit_len"], got["commit_token"], got["new_prefix_len"]) == \
+           (ref.selected, ref.commit_len, ref.commit_token, ref.new_prefix_len)
+    assert got["commit_len"] >= 1
 
 
 def test_cache_filled_to_the_last_slot(B):

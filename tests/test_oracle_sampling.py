@@ -334,3 +334,66 @@ def test_deferred_form_unverified_suffix_is_textbook_chain():
                 assert x[-1] == res.commit_token
         else:
             assert x[:1 + l] == [9] + xt
+
+
+# ------------------------------------------------------------------ the greedy limit (temperature 0)
+def _greedy_case(g, V, n, k, match):
+    """Random logits; sequence i copies the arg max of its judging rows for match[i] positions, then deviates."""
+    logits = g.normal(size=(n * k, V)).astype(np.float32)
+    root = g.normal(size=V).astype(np.float32)
+    toks = np.zeros((n, k), dtype=np.int64)
+    for i in range(n):
+        for j in range(k):
+            row = root if j == 0 else logits[i * k + j - 1]
+            best = int(np.argmax(row))
+            toks[i, j] = best if j < match[i] else (best + 1 + int(g.integers(V - 1))) % V
+    q = np.stack([[_dist(g, V) for _ in range(k)] for _ in range(n)])
+    return logits, root, toks, q
+
+
+def test_greedy_target_probs_is_one_hot_lowest_id_on_ties():
+    lg = np.array([0.5, 2.0, -1.0, 2.0], dtype=np.float32)
+    assert O.target_probs(lg, 0.0).tolist() == [0.0, 1.0, 0.0, 0.0]
+    two = O.target_probs(np.stack([lg, lg[::-1]]), 0.0)
+    assert two.tolist() == [[0.0, 1.0, 0.0, 0.0], [1.0, 0.0, 0.0, 0.0]]
+
+
+@pytest.mark.parametrize("mode", [O.MODE_INDEPENDENT_LONGEST, O.MODE_PAPER_SEQUENTIAL])
+def test_greedy_is_prefix_match_with_the_arg_max_chain(mode):
+    """Closed form of Alg. 2 at T = 0: the accepted length is the number of leading draft tokens equal to the target's
+    arg max, the emitted token is the arg max after them, and no uniform can change that."""
+    g = np.random.default_rng(11)
+    V, k = 17, 5
+    for n, match in ((1, [3]), (1, [5]), (1, [0]), (3, [0, 2, 4]), (3, [0, 0, 0]), (2, [5, 5])):
+        logits, root, toks, q = _greedy_case(g, V, n, k, match)
+        outs = []
+        for useed in range(3):
+            u = np.random.default_rng(useed).random((n, k + 1)).astype(np.float32)
+            outs.append(O.speculative_verify(logits, root, toks, q, u, prefix_len=7, temperature=0.0, select_mode=mode))
+        r = outs[0]
+        for o in outs[1:]:
+            assert (o.selected, o.commit_len, o.commit_token) == (r.selected, r.commit_len, r.commit_token)
+        if mode == O.MODE_INDEPENDENT_LONGEST:
+            assert r.accept_len.tolist() == match
+            sel = int(np.argmax(match))                      # longest, lowest index among equals
+        else:
+            firsts = [i for i in range(n) if match[i] > 0]   # the first sequence whose first token is the arg max
+            sel = firsts[0] if firsts else -1
+        assert r.selected == sel
+        length = match[sel] if sel >= 0 else 0
+        assert r.commit_len == length and r.new_prefix_len == 7 + length
+        row = root if length == 0 else logits[max(sel, 0) * k + length - 1]
+        assert r.commit_token == int(np.argmax(row))
+
+
+def test_greedy_equals_a_very_small_temperature():
+    g = np.random.default_rng(12)
+    V, n, k = 23, 2, 4
+    for trial in range(5):
+        logits, root, toks, q = _greedy_case(g, V, n, k, [int(g.integers(k + 1)) for _ in range(n)])
+        u = g.random((n, k + 1)).astype(np.float32)
+        for mode in (O.MODE_INDEPENDENT_LONGEST, O.MODE_PAPER_SEQUENTIAL):
+            a = O.speculative_verify(logits, root, toks, q, u, prefix_len=0, temperature=0.0, select_mode=mode)
+            b = O.speculative_verify(logits, root, toks, q, u, prefix_len=0, temperature=1e-4, select_mode=mode)
+            assert (a.selected, a.commit_len, a.commit_token) == (b.selected, b.commit_len, b.commit_token)
+            assert a.accept_len.tolist() == b.accept_len.tolist() and a.next_token.tolist() == b.next_token.tolist()
