@@ -86,7 +86,8 @@ def test_verify_rejects_bad_arguments_before_touching_the_gpu(lib):
     assert run(B.Call(1, 0, 1.0, 0, -1, 128)) == -2
     assert run(B.Call(10, 8, 1.0, 0, 5, 128)) == -2                            # 81 rows with the root
     assert run(B.Call(11, 8, 1.0, 0, -1, 128)) == -2
-    assert run(B.Call(1, 8, 0.0, 0, -1, 128)) == -8
+    assert run(B.Call(1, 8, -0.5, 0, -1, 128)) == -8                           # 0 is the greedy limit, below it nothing
+    assert run(B.Call(1, 8, float("nan"), 0, -1, 128)) == -8
     assert run(B.Call(1, 8, 1.0, 2, -1, 128)) == -8
     assert run(B.Call(1, 8, 1.0, 0, 32000, 128)) == -6
     assert run(B.Call(1, 8, 1.0, 0, -1, 249)) == -3                            # 249 + 8 > 256
