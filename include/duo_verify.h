@@ -43,6 +43,7 @@ extern "C" {
 
 /* Most rows one call can score: n*k (+1 with a root token). */
 #define DUO_MAX_ROWS 80
+#define DUO_MAX_PREFILL_ROWS 1024 /* rows of one duo_prefill_chunk call */
 
 /* Bits of the device-side status word (duo_result.status), set by kernels that cannot be
  * checked on the host without a synchronisation. */
@@ -247,6 +248,16 @@ int duo_deferred_sample(const float *logits, const float *root_logits, int vocab
  */
 int duo_skinny_gemm(const uint16_t *x_packed, const uint16_t *w_packed, float *y, int rows, int N, int K,
                     void *hip_stream);
+
+/*
+ * The projection kernel of the many-row (prefill) pass on its own, for tests and kernel benchmarks.  The
+ * activations are bf16 pairs a = hi + lo: x_packed comes from duo_pack_activations over 2*PR rows, PR = rows
+ * rounded up to a multiple of 16, rows [0, rows) holding the hi parts and rows [PR, PR + rows) the lo parts
+ * (all other rows zero).  y[m][n] = sum_k (hi + lo)[m][k] * w[n][k], fp32 [rows][N] row-major; w from
+ * duo_pack_matrix; rows <= DUO_MAX_PREFILL_ROWS, K % 32 == 0.  Device pointers.
+ */
+int duo_block_gemm(const uint16_t *x_packed, const uint16_t *w_packed, float *y, int rows, int N, int K,
+                   void *hip_stream);
 
 /*
  * Per-kernel timing for the roofline report (the per-iteration time breakdown of Sec. 4.4

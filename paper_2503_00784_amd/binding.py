@@ -22,7 +22,7 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_k_cache_offset",
+           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_block_gemm", "duo_k_cache_offset",
            "duo_v_cache_offset", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
            "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
@@ -91,6 +91,7 @@ def load() -> C.CDLL:
                                         C.c_void_p, C.c_void_p, C.c_int, C.POINTER(Call), C.POINTER(Result), C.c_void_p,
                                         C.c_size_t, C.c_void_p]
     lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+    lib.duo_block_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.duo_packed_elems.argtypes = [C.c_int, C.c_int]
     lib.duo_packed_elems.restype = C.c_size_t
     for name in ("duo_k_cache_offset", "duo_v_cache_offset"):
@@ -101,7 +102,7 @@ def load() -> C.CDLL:
     lib.duo_pack_gate_up.argtypes = [C.POINTER(ModelConfig), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.duo_pack_activations.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     for name in ("duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-                 "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_pack_matrix",
+                 "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_block_gemm", "duo_pack_matrix",
                  "duo_pack_qkv", "duo_pack_gate_up", "duo_pack_activations"):
         getattr(lib, name).restype = C.c_int
     lib.duo_profile_enable.argtypes = [C.c_int]
@@ -439,4 +440,20 @@ def skinny_gemm(x_bits, w_bits):
     xp, wp = pack_activations(x_bits), pack_matrix(w_bits)
     y = torch.empty((rows, N), dtype=torch.float32, device=x_bits.device)
     _check(load().duo_skinny_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_skinny_gemm")
+    return y
+
+
+def block_gemm(hi_bits, lo_bits, w_bits):
+    """y = (hi + lo) W^T through duo_pack_activations / duo_pack_matrix / duo_block_gemm.
+    hi_bits, lo_bits int16 [rows][K] (the two bf16 halves of the activations), w_bits int16 [N][K]."""
+    import torch
+    rows, K = hi_bits.shape
+    N = w_bits.shape[0]
+    pr = (rows + 15) // 16 * 16
+    both = torch.zeros((2 * pr, K), dtype=torch.int16, device=hi_bits.device)
+    both[:rows] = hi_bits
+    both[pr:pr + rows] = lo_bits
+    xp, wp = pack_activations(both), pack_matrix(w_bits)
+    y = torch.empty((rows, N), dtype=torch.float32, device=hi_bits.device)
+    _check(load().duo_block_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_block_gemm")
     return y

@@ -12,6 +12,7 @@
 #include "duo_attn.h"
 #include "duo_common.h"
 #include "duo_gemm.h"
+#include "duo_gemm_block.h"
 #include "duo_pack.h"
 #include "duo_rowops.h"
 #include "duo_sample.h"
@@ -546,6 +547,17 @@ int duo_skinny_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, in
     return hip_ok(hipGetLastError(), "duo_skinny_gemm launch");
 }
 
+int duo_block_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, int N, int K, void* hip_stream) {
+    if (!x || !w || !y) return DUO_ERR_NULL;
+    if (rows < 1 || rows > DUO_MAX_PREFILL_ROWS || N < 1 || K < 32 || K % 32) return DUO_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    EpiStoreF32 e{N, rows, 1, y, N, 0};
+    launch_block<4, 4, 1>(x, w, K, (N + 15) / 16, rows, 1, RowScale{nullptr, 0, 0.f, 0.f, nullptr}, e, s);
+    return hip_ok(hipGetLastError(), "duo_block_gemm launch");
+}
+
 size_t duo_k_cache_offset(int head_dim, int slot, int channel) { return k_cache_offset(head_dim, slot, channel); }
 size_t duo_v_cache_offset(int head_dim, int slot, int channel) { return v_cache_offset(head_dim, slot, channel); }
 
@@ -595,7 +607,7 @@ int duo_pack_gate_up(const duo_model_config* cfg, const uint16_t* w_gate, const 
 
 int duo_pack_activations(const uint16_t* src, int rows, int K, uint16_t* dst, void* hip_stream) {
     if (!src || !dst) return DUO_ERR_NULL;
-    if (rows < 1 || rows > DUO_MAX_ROWS || K < 32 || K % 32) return DUO_ERR_SHAPE;
+    if (rows < 1 || rows > 2 * DUO_MAX_PREFILL_ROWS || K < 32 || K % 32) return DUO_ERR_SHAPE;
     if (!aligned16(src) || !aligned16(dst)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();

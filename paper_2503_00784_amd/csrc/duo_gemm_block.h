@@ -1,0 +1,183 @@
+// Projections over many rows (prefill chunks of 81..1024 prompt tokens; the target model's share of the
+// time to first token, Sec. 4.1).  With that many rows the product is no longer a weight stream with a
+// few activation rows beside it: both operands are re-used and both are staged in LDS.
+//
+// A workgroup owns a block of 2*WM row tiles (16 rows each) x 2*WN weight bands (16 columns each); its four
+// consumer waves form a 2 x 2 grid, each with WM x WN accumulator tiles.  Both operands already lie in
+// MFMA-tile order in global memory (duo_gemm.h), so a stage is a list of 1 KiB tiles: per K step the block's
+// hi tiles, its lo tiles (the activations are bf16 pairs, hi and lo products add into the same accumulators)
+// and its weight tiles.  A fifth wave does nothing but move tiles: 16-byte global -> LDS loads into a
+// three-deep ring of stages, two stages ahead, handed over with one barrier per stage (bare s_barrier
+// behind a counted wait in the producer, exactly as in gemm_wide_kernel).  The consumers touch no global
+// memory inside the loop.
+//
+// Per K step a wave reads (2*WM + WN) KiB from LDS for 2*WM*WN MFMAs: 12 KiB per 32 MFMAs (512 cycles) at
+// WM = WN = 4, i.e. 96 B/clk per compute unit, inside what LDS delivers; the block pulls (4*WM + 2*WN) KiB
+// per K step through L2.
+//
+// Grid: x = blocks of bands, y = K splits (partial results, see EpiStoreF32), z = blocks of rows.
+// ENT = bands per epilogue tile (2 for the rotary and SwiGLU epilogues, 1 otherwise).
+#pragma once
+#include "duo_gemm.h"
+
+template <int WM, int WN, int KS, int ENT, class Epi>
+__global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__ X, const u16* __restrict__ W, int K,
+                                                         int split_steps, int nbands, int mh_total, int quads, RowScale rsc,
+                                                         Epi epi) {
+    constexpr int BMT = 2 * WM, BNT = 2 * WN;  // row tiles (hi) and bands per workgroup
+    constexpr int PER = 2 * BMT + BNT;         // tiles per K step
+    constexpr int ST = KS * PER;               // tiles per stage
+    constexpr int NBUF = 3;
+    static_assert(ST <= 63, "a stage's loads fit the memory counter");
+    static_assert(WN % ENT == 0, "whole epilogue tiles per wave");
+    __shared__ u32x4 lds[NBUF * ST * 64];
+    __shared__ float row_scale[BMT * 16];
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar: MFMA ignores EXEC
+    const int steps = K >> 5;
+    const int k0 = blockIdx.y * split_steps;
+    const int ns = min(steps - k0, split_steps);  // K steps of this split (the host makes it positive)
+    const int rounds = (ns + KS - 1) / KS;
+    const int row_tile0 = blockIdx.z * BMT, band0 = blockIdx.x * BNT;
+    const int row0 = row_tile0 * 16, nrows = quads * 4;
+
+    // RMSNorm factors of this block's rows (all five waves)
+    if (rsc.full) {
+        for (int i = threadIdx.x; i < BMT * 16; i += 320) {
+            const int m = row0 + i;
+            row_scale[i] = m < nrows ? 1.0f / sqrtf(rsc.full[m] * rsc.inv_d + rsc.eps) : 0.f;
+        }
+    } else if (rsc.part) {
+        f32x4 rsv[RowScale::MAXQ];
+        const int rend = min(row0 + BMT * 16, nrows);
+        for (int r0 = row0 + wave * 8; r0 < rend; r0 += 5 * 8) {
+            rsc.load(rsv, r0, nrows, lane);
+            rsc.reduce(rsv, row_scale - row0, r0, nrows, lane);
+        }
+    }
+
+    if (wave == 4) {
+        // ---- producer: stage r goes to ring buffer r % 3; steps past the end re-read the last step
+        const u32x4* xg = reinterpret_cast<const u32x4*>(X) + lane;
+        const u32x4* wg = reinterpret_cast<const u32x4*>(W) + lane;
+        const int mt_total = 2 * mh_total;
+        auto issue = [&](int r) {
+            const int b = r % NBUF;
+#pragma unroll
+            for (int i = 0; i < ST; ++i) {
+                const int ks = i / PER, t = i % PER;
+                int st = r * KS + ks;
+                st = k0 + (st < ns ? st : ns - 1);
+                const u32x4* src;
+                if (t < 2 * BMT) {  // hi tiles, then lo tiles; row tiles past the operand re-read its last one
+                    int rt = row_tile0 + t % BMT;
+                    rt = rt < mh_total ? rt : mh_total - 1;
+                    src = xg + ((size_t)st * mt_total + (t / BMT) * mh_total + rt) * 64;
+                } else {  // bands past the matrix re-read its last one
+                    int bd = band0 + (t - 2 * BMT);
+                    bd = bd < nbands ? bd : nbands - 1;
+                    src = wg + ((size_t)bd * steps + st) * 64;
+                }
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)(lds + (b * ST + i) * 64), 16, 0, 0);
+            }
+        };
+        // vmcnt(ST): everything but the youngest stage has landed (expcnt and lgkmcnt fields left at their maxima)
+        constexpr int WAIT_ALL_BUT_ONE_STAGE = (ST & 15) | ((ST >> 4) << 14) | (7 << 4) | (15 << 8);
+        issue(0);
+        issue(1);
+        __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_STAGE & ~(15 << 8));  // and lgkmcnt(0): this wave's row scales are written
+        __builtin_amdgcn_s_barrier();
+        for (int r = 0; r < rounds; ++r) {
+            issue(r + 2);  // its buffer was drained in round r - 1
+            __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_STAGE);  // stage r + 1 has landed
+            __builtin_amdgcn_s_barrier();
+        }
+        __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));  // vmcnt(0): nothing is in flight towards LDS when this wave ends
+        return;
+    }
+
+    // ---- consumers: wave (wm, wn) of the 2 x 2 grid
+    const int wm = wave >> 1, wn = wave & 1;
+    f32x4 acc[WM][WN];
+#pragma unroll
+    for (int m = 0; m < WM; ++m)
+#pragma unroll
+        for (int t = 0; t < WN; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    __syncthreads();  // stage 0 is in LDS, the row scales are written
+    for (int r = 0; r < rounds; ++r) {
+        const u32x4* stage = lds + (r % NBUF) * ST * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (r * KS + ks < ns) {  // wave-uniform
+                const u32x4* st = stage + ks * PER * 64;
+                bf16x8 ah[WM], al[WM], b[WN];
+#pragma unroll
+                for (int m = 0; m < WM; ++m) {
+                    Frag8 f, g;
+                    f.q = st[(wm * WM + m) * 64];
+                    g.q = st[(BMT + wm * WM + m) * 64];
+                    ah[m] = f.v;
+                    al[m] = g.v;
+                }
+#pragma unroll
+                for (int t = 0; t < WN; ++t) {
+                    Frag8 f;
+                    f.q = st[(2 * BMT + wn * WN + t) * 64];
+                    b[t] = f.v;
+                }
+#pragma unroll
+                for (int m = 0; m < WM; ++m)
+#pragma unroll
+                    for (int t = 0; t < WN; ++t) acc[m][t] = mfma16(ah[m], b[t], acc[m][t]);
+#pragma unroll
+                for (int m = 0; m < WM; ++m)
+#pragma unroll
+                    for (int t = 0; t < WN; ++t) acc[m][t] = mfma16(al[m], b[t], acc[m][t]);
+            }
+        }
+        __syncthreads();  // stage r + 1 is in LDS; stage r's buffer may be refilled
+    }
+
+    // A lane's accumulator quad is rows 4*(lane/16) .. +3 of its row tile, column lane%16 of its band.
+    typename Epi::Pre pre;
+#pragma unroll
+    for (int m = 0; m < WM; ++m) {
+        const int qi = (row_tile0 + wm * WM + m) * 4 + (lane >> 4);
+        if (qi >= quads) continue;
+        float rs[4] = {1.f, 1.f, 1.f, 1.f};
+        if (rsc.part) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rs[i] = row_scale[qi * 4 + i - row0];
+        }
+#pragma unroll
+        for (int t = 0; t < WN; t += ENT) {
+            const int band = band0 + wn * WN + t;
+            if (band >= nbands) continue;  // wave-uniform
+            f32x4 v[ENT];
+#pragma unroll
+            for (int e = 0; e < ENT; ++e)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[e][i] = acc[m][t + e][i] * rs[i];
+            epi.store(band / ENT, qi, lane & 15, v, pre, false);
+        }
+    }
+}
+
+// Launch for M rows (operand of 2 * mh_total row tiles: hi tiles, then lo tiles), `nbands` bands of 16 columns,
+// K split `splits` ways over the grid's y dimension (returns the number of splits actually used).
+template <int WM, int WN, int ENT, class Epi>
+static inline int launch_block(const u16* X, const u16* W, int K, int nbands, int M, int splits, const RowScale& rsc,
+                               const Epi& epi, hipStream_t s) {
+    constexpr int KS = (2 * (4 * WM + 2 * WN) <= 48) ? 2 : 1;  // stage of at most 48 KiB
+    const int mh_total = pair_rows_for(M) / 16, quads = pair_rows_for(M) / 4;
+    const int steps = K >> 5;
+    int split_steps = (steps + splits - 1) / splits;
+    split_steps = (split_steps + KS - 1) / KS * KS;
+    const int S = (steps + split_steps - 1) / split_steps;
+    const dim3 grid((nbands + 2 * WN - 1) / (2 * WN), S, (mh_total + 2 * WM - 1) / (2 * WM));
+    DUO_LAUNCH((gemm_block_kernel<WM, WN, KS, ENT, Epi>), grid, dim3(320), s, X, W, K, split_steps, nbands, mh_total, quads, rsc,
+               epi);
+    return S;
+}

@@ -34,6 +34,26 @@ def test_skinny_gemm_matches_oracle_matmul(B, rows, N, K):
     assert err <= 2e-6 * np.sqrt(K) * max(1.0, np.abs(ref).max())
 
 
+@pytest.mark.parametrize("rows,N,K", [(81, 128, 64), (128, 4096, 4096), (256, 1000, 512), (300, 4099, 1408), (1024, 520, 2048),
+                                      (130, 96, 96), (512, 11008, 4096), (255, 4096, 11008)])
+def test_block_gemm_matches_oracle_matmul(B, rows, N, K):
+    """The many-row projection kernel: activations as bf16 pairs (hi + lo), several row blocks, ragged rows, bands
+    and K steps."""
+    import torch
+    say(f"block gemm rows={rows} N={N} K={K}")
+    g = np.random.default_rng(rows * 1000 + N)
+    a = g.normal(0, 1, (rows, K)).astype(np.float32)
+    hi = inputs.f32_to_bf16_bits(a)
+    lo = inputs.f32_to_bf16_bits((a.astype(np.float64) - O.bf16_bits_to_f64(hi)).astype(np.float32))
+    w = inputs.f32_to_bf16_bits(g.normal(0, 0.02, (N, K)).astype(np.float32))
+    y = B.block_gemm(to_dev(hi.view(np.int16)), to_dev(lo.view(np.int16)), to_dev(w.view(np.int16)))
+    torch.cuda.synchronize()
+    ref = (O.bf16_bits_to_f64(hi) + O.bf16_bits_to_f64(lo)) @ O.bf16_bits_to_f64(w).T
+    err = np.abs(y.cpu().numpy() - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= 2e-6 * np.sqrt(K) * max(1.0, np.abs(ref).max())
+
+
 # ------------------------------------------------------------------ sampler on identical logits
 def _sampling_case(V, n, k, seed, has_root, peaked):
     g = np.random.default_rng(seed)
