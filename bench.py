@@ -46,7 +46,7 @@ def main() -> int:
     ap.add_argument("--prefill-tokens", type=int, default=0,
                     help="also time the prefill of this many prompt tokens from an empty cache (time to first token of the "
                     "target model, Sec. 4.1) and add \"prefill\" to the line")
-    ap.add_argument("--prefill-chunk", type=int, default=80, help="rows per prefill forward pass (at most 80)")
+    ap.add_argument("--prefill-chunk", type=int, default=512, help="rows per prefill forward pass (at most 1024)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -77,7 +77,7 @@ def main() -> int:
     w = inputs.make_weights(shape, seed=args.seed, threads=16)
     kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=args.seed)
     q, toks, u = inputs.make_draft(shape.vocab, n, k, seed=args.seed + 1, easy_rows=inputs.easy_rows_for(n, k))
-    eng = B.VerifyEngine(shape, w, max_seq)
+    eng = B.VerifyEngine(shape, w, max_seq, max_prefill_rows=args.prefill_chunk if args.prefill_tokens > 0 else B.DUO_MAX_ROWS)
     eng.load_cache(kb, vb, P, root)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     d_toks, d_q, d_u = dev(toks), dev(q), dev(u)

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libduo_verify.so")
 
 DUO_MAX_ROWS = 80
+DUO_MAX_PREFILL_ROWS = 1024
 SELECT_INDEPENDENT_LONGEST = 0
 SELECT_PAPER_SEQUENTIAL = 1
 STATUS_TOKEN_CLAMPED = 1
@@ -268,7 +269,8 @@ class VerifyEngine:
     """Owns the device buffers of one model instance (cache, workspace, results) and calls the C ABI."""
 
     def __init__(self, shape, host_weights: Dict[str, object], max_seq: int, device: str = "cuda:0",
-                 max_rows: int = DUO_MAX_ROWS, weights: Optional[DeviceWeights] = None):
+                 max_rows: int = DUO_MAX_ROWS, weights: Optional[DeviceWeights] = None,
+                 max_prefill_rows: int = DUO_MAX_ROWS):
         import torch
         self.torch = torch
         self.lib = load()
@@ -283,7 +285,9 @@ class VerifyEngine:
         self.vT = torch.zeros((L, H, max_seq * D), dtype=torch.int16, device=device)
         self.prefix_len = torch.zeros(1, dtype=torch.int32, device=device)
         self.root_logits = torch.zeros(shape.vocab, dtype=torch.float32, device=device)
-        self.ws_bytes = workspace_bytes(self.cfg, max_rows)
+        # verify calls take up to DUO_MAX_ROWS rows, prefill chunks up to DUO_MAX_PREFILL_ROWS (a larger workspace)
+        self.max_prefill_rows = max(int(max_prefill_rows), min(int(max_rows), DUO_MAX_ROWS))
+        self.ws_bytes = max(workspace_bytes(self.cfg, min(max_rows, DUO_MAX_ROWS)), workspace_bytes(self.cfg, self.max_prefill_rows))
         self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
         self.accept_len = torch.zeros(DUO_MAX_ROWS, dtype=torch.int32, device=device)
         self.next_token = torch.zeros(DUO_MAX_ROWS, dtype=torch.int32, device=device)
@@ -323,6 +327,8 @@ class VerifyEngine:
     def prefill(self, tokens: Sequence[int], chunk: int = 64) -> None:
         torch = self.torch
         toks = torch.tensor(list(tokens), dtype=torch.int32, device=self.device)
+        if chunk > self.max_prefill_rows:
+            raise ValueError(f"prefill chunk {chunk} exceeds the engine's max_prefill_rows {self.max_prefill_rows}")
         for s in range(0, len(tokens), chunk):
             m = min(chunk, len(tokens) - s)
             rc = self.lib.duo_prefill_chunk(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),

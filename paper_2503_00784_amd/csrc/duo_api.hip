@@ -25,6 +25,16 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 constexpr int MAX_CHUNKS = 64;
+constexpr int MAX_CHUNKS_MANY_ROWS = 8;  // key chunks of the attention kernels in passes of more than DUO_MAX_ROWS rows
+
+// K splits of a residual projection (N = d_model columns) in the many-row pass: enough workgroups of 128 x 128 for
+// the chip, at most eight partial results.
+int block_splits(int M, int N) {
+    const int mh = pair_rows_for(M) / 16;
+    const int wgs = ((N / 16 + 7) / 8) * ((mh + 7) / 8);
+    const int S = 256 / wgs;
+    return S < 1 ? 1 : (S > WIDE_MAX_SPLIT ? WIDE_MAX_SPLIT : S);
+}
 
 // GEMM operand buffers (h, attn, act) hold activations as bf16 pairs: row m = hi, row pair_rows + m = lo,
 // padded to whole 16-row MFMA tiles; rows that carry no activation are never stored from.
@@ -43,7 +53,8 @@ struct Workspace {
     int32_t* acc;
     float* ssq;      // [Mp][d/16] partial sums of squares of the residual stream (for the next RMSNorm)
     float* ssq_full; // [Mp] complete sums of squares (written by the one-workgroup-per-row producers)
-    float* split;    // [WIDE_MAX_SPLIT][Mp][d] partial results of the K-split residual projections
+    float* split;    // [splits][Mp][d] partial results of the K-split residual projections
+    u16* h_last;     // many-row pass: the last row of h as an operand of its own (one tile per K step)
     size_t q_plane;  // elements between the two query planes
     size_t total;
 };
@@ -81,13 +92,16 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.q = reinterpret_cast<u16*>(take(2 * Mp * qd * 2));
     ws.attn = reinterpret_cast<u16*>(take(Ar * qd * 2));
     ws.act = reinterpret_cast<u16*>(take(Ar * F * 2));
-    ws.part = reinterpret_cast<float*>(take((size_t)c.n_kv_heads * (Mp * group) * MAX_CHUNKS * (c.head_dim + 4) * 4));
+    const bool many = max_rows > DUO_MAX_ROWS;  // prefill pass: few key chunks, logits of the last row only
+    ws.part = reinterpret_cast<float*>(
+        take((size_t)c.n_kv_heads * (Mp * group) * (many ? MAX_CHUNKS_MANY_ROWS : MAX_CHUNKS) * (c.head_dim + 4) * 4));
     ws.rope_c = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
     ws.rope_s = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
-    ws.logits = reinterpret_cast<float*>(take(Mp * V * 4));
+    ws.logits = reinterpret_cast<float*>(take((many ? 16 : Mp) * V * 4));
     ws.ssq = reinterpret_cast<float*>(take(Mp * (d / 16) * 4));
     ws.ssq_full = reinterpret_cast<float*>(take(Mp * 4));
-    ws.split = reinterpret_cast<float*>(take((size_t)WIDE_MAX_SPLIT * Mp * d * 4));
+    ws.split = reinterpret_cast<float*>(take((size_t)(many ? block_splits(max_rows, c.d_model) : WIDE_MAX_SPLIT) * Mp * d * 4));
+    ws.h_last = reinterpret_cast<u16*>(take(16 * d * 2));
     carve_sampler(base, off, c.vocab, ws);
     ws.total = off;
     return ws;
@@ -161,6 +175,12 @@ void launch_attention(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_
 template <int NT, class Epi>
 void launch_projection(int M, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
                        hipStream_t s) {
+    if (M > DUO_MAX_ROWS) {  // prefill pass: both operands staged in LDS; wider blocks once they still fill the chip
+        const int bands = tiles * NT, mh = pair_rows_for(M) / 16;
+        if (((bands + 15) / 16) * ((mh + 7) / 8) >= 160) launch_block<4, 8, NT>(X, W, K, bands, M, 1, rsc, epi, s);
+        else launch_block<4, 4, NT>(X, W, K, bands, M, 1, rsc, epi, s);
+        return;
+    }
     if (M <= 8) {
         if (!launch_wide_half<NT>(X, W, K, tiles, rsc, epi, s)) launch_gemm_rows<NT>(M, true, X, W, K, tiles, rsc, epi, s);
         return;
@@ -181,20 +201,27 @@ void launch_projection(int M, const u16* X, const u16* W, int K, int tiles, cons
 static_assert(WIDE_MAX_SPLIT <= 8, "residual_reduce_kernel holds at most eight splits in registers");
 
 // Whether the residual projection over K input channels runs as K-split partial products + reduce kernel.
-bool residual_is_split(int M, int K) { return !(M <= 16 || (M <= 32 && K <= 6144)); }
+bool residual_is_split(int M, int K, int N) {
+    if (M > DUO_MAX_ROWS) return block_splits(M, N) > 1;
+    return !(M <= 16 || (M <= 32 && K <= 6144));
+}
 
 void launch_residual_projection(int M, const u16* X, const u16* W, int K, const EpiResidual& er, float* split,
                                 float* ssq_full, int cls, hipStream_t s) {
     const RowScale none{nullptr, 0, 0.f, 0.f, nullptr};
     const int MH = (M + 15) / 16, d = er.N;
-    if (!residual_is_split(M, K)) {
+    if (!residual_is_split(M, K, d)) {
         prof(cls, s);
-        launch_gemm_rows<1>(M, true, X, W, K, d / 16, none, er, s);
+        if (M > DUO_MAX_ROWS) launch_block<4, 4, 1>(X, W, K, d / 16, M, 1, none, er, s);
+        else launch_gemm_rows<1>(M, true, X, W, K, d / 16, none, er, s);
         return;
     }
     int S = 1;
     prof(cls, s);
-    switch (MH) {
+    if (M > DUO_MAX_ROWS) {
+        EpiStoreF32 e{d, M, 1, split, d, (size_t)M * d};
+        S = launch_block<4, 4, 1>(X, W, K, d / 16, M, block_splits(M, d), none, e, s);
+    } else switch (MH) {
         case 2: S = launch_wide_split<2>(X, W, K, d, M, split, none, s); break;
         case 3: S = launch_wide_split<3>(X, W, K, d, M, split, none, s); break;
         case 4: S = launch_wide_split<4>(X, W, K, d, M, split, none, s); break;
@@ -227,7 +254,9 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     // (embedding gather, K-split reduce) and the consumer is the LDS-shared kernel, which reads them directly.
     const RowScale norm_part{ws.ssq, NP, 1.0f / (float)d, c.rms_eps, nullptr};
     const RowScale norm_full{ws.ssq, NP, 1.0f / (float)d, c.rms_eps, ws.ssq_full};
-    const bool o_split = residual_is_split(M, qd), down_split = residual_is_split(M, F);
+    const bool o_split = residual_is_split(M, qd, d), down_split = residual_is_split(M, F, d);
+    const bool many = M > DUO_MAX_ROWS;  // prefill pass: logits of the last row only (to logits[0 .. V))
+    const int max_chunks = many ? MAX_CHUNKS_MANY_ROWS : MAX_CHUNKS;
     prof(DUO_PROF_SETUP, s);
     DUO_LAUNCH(rope_table_kernel, dim3(M), dim3(64), s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s, status);
     prof(DUO_PROF_SETUP, s);
@@ -254,7 +283,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         sh_nwv = MqT > 16 ? 7 : (MqT > 4 ? 8 : (MqT > 2 ? 4 : 2));
         sh_zg = (MqT + sh_nwv * sh_mtw - 1) / (sh_nwv * sh_mtw);
         int target = (256 + Hkv * sh_zg - 1) / (Hkv * sh_zg);
-        target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
+        target = target < 1 ? 1 : (target > max_chunks ? max_chunks : target);
         bpw = (NB + target - 1) / target;  // blocks per chunk
         bpw = bpw < 2 ? 2 : bpw;
         nchunks = (NB + bpw - 1) / bpw;
@@ -268,7 +297,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         // of 3 blocks per wave take 14 us, 544 of one block 24 us)
         nwv = 4;
         int target = (224 + Hkv * MG - 1) / (Hkv * MG);
-        target = target < 1 ? 1 : (target > MAX_CHUNKS ? MAX_CHUNKS : target);
+        target = target < 1 ? 1 : (target > max_chunks ? max_chunks : target);
         bpw = (NB + 4 * target - 1) / (4 * target);
         bpw = bpw < 2 ? 2 : bpw;
         nchunks = (NB + 4 * bpw - 1) / (4 * bpw);
@@ -315,8 +344,15 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         EpiResidual ed{d, M, ws.x, d, gnext, ws.h, PR, AT, ws.ssq};
         launch_residual_projection(M, ws.act, w.w_down[l], F, ed, ws.split, ws.ssq_full, DUO_PROF_DOWN, s);
     }
-    EpiStoreF32 el{V, M, 2, logits, V};
     prof(DUO_PROF_LMHEAD, s);
+    if (many) {
+        DUO_LAUNCH(last_row_operand_kernel, dim3(d / 32), dim3(64), s, ws.h, M - 1, PR, AT, ws.h_last);
+        const RowScale last{ws.ssq + (size_t)(M - 1) * NP, NP, 1.0f / (float)d, c.rms_eps, down_split ? ws.ssq_full + (M - 1) : nullptr};
+        EpiStoreF32 el{V, 1, 2, logits, V};
+        launch_projection<2>(1, ws.h_last, w.lm_head, d, (V + 31) / 32, last, el, s);
+        return;
+    }
+    EpiStoreF32 el{V, M, 2, logits, V};
     launch_projection<2>(M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
 }
 
@@ -366,7 +402,7 @@ int duo_workspace_bytes(const duo_model_config* cfg, int max_rows, size_t* bytes
     if (!bytes) return DUO_ERR_NULL;
     int rc = check_config(cfg);
     if (rc) return rc;
-    if (max_rows < 1 || max_rows > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
+    if (max_rows < 1 || max_rows > DUO_MAX_PREFILL_ROWS) return DUO_ERR_SHAPE;
     *bytes = carve(*cfg, max_rows, nullptr).total;
     return DUO_OK;
 }
@@ -410,7 +446,7 @@ int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_
     if ((rc = check_weights(cfg, w))) return rc;
     if (!cache || !cache->k || !cache->v || !cache->prefix_len || !cache->root_logits || !tokens || !status || !workspace)
         return DUO_ERR_NULL;
-    if (m < 1 || m > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
+    if (m < 1 || m > DUO_MAX_PREFILL_ROWS) return DUO_ERR_SHAPE;
     if (host_prefix_len < 0) return DUO_ERR_ARG;
     if ((long long)host_prefix_len + m > cfg->max_seq) return DUO_ERR_CAPACITY;
     if (!aligned16(cache->k) || !aligned16(cache->v) || !aligned16(workspace)) return DUO_ERR_ALIGN;
@@ -422,7 +458,7 @@ int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_
     const RowPlan plan{host_prefix_len, 0, 1, m, m};  // the pass's first kernel clears *status
     enqueue_forward(*cfg, *w, *cache, tokens, -1, plan, ws, ws.logits, status, s);
     DUO_LAUNCH(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), s,
-                       ws.logits + (size_t)(m - 1) * cfg->vocab, cache->root_logits, cfg->vocab, cache->prefix_len,
+                       ws.logits + (m > DUO_MAX_ROWS ? 0 : (size_t)(m - 1) * cfg->vocab), cache->root_logits, cfg->vocab, cache->prefix_len,
                        host_prefix_len + m);
     return hip_ok(hipGetLastError(), "duo_prefill_chunk launch");
 }

@@ -134,3 +134,17 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
 }
+
+// Row m of a paired operand buffer (hi at row m, lo at row pair_rows + m; `tiles` row tiles per K step) as an operand
+// of its own for a one-row product: one tile per K step, hi in row 0, lo in row 8, all other rows zero.
+// grid = K/32 workgroups of one wave.
+__global__ __launch_bounds__(64) void last_row_operand_kernel(const u16* __restrict__ src, int m, int pair_rows, int tiles,
+                                                              u16* __restrict__ dst) {
+    const int ks = blockIdx.x, lane = threadIdx.x, r = lane & 15, g = lane >> 4;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (r == 0 || r == 8) {
+        const int row = r == 0 ? m : pair_rows + m;
+        v = *reinterpret_cast<const u32x4*>(src + (((size_t)ks * tiles + (row >> 4)) * 64 + g * 16 + (row & 15)) * 8);
+    }
+    *reinterpret_cast<u32x4*>(dst + ((size_t)ks * 64 + lane) * 8) = v;
+}

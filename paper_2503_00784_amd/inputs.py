@@ -71,6 +71,8 @@ LLAMA2_7B = ModelShape(32, 4096, 32, 32, 128, 11008, 32000)
 LLAMA3_8B = ModelShape(32, 4096, 32, 8, 128, 14336, 128256, rope_theta=500000.0)
 # a mid-sized shape for parity tests that must span several tiles yet finish in seconds
 MID = ModelShape(3, 512, 8, 2, 64, 1408, 4099)
+# one 7B-wide layer (GQA, heads of 128): the launch shapes a prompt chunk of ~1000 rows takes at full width
+WIDE1 = ModelShape(1, 4096, 32, 8, 128, 4096, 1000)
 
 WORKLOADS: Dict[str, Workload] = {
     "C0": Workload("C0-tiny-P128-n1-k8", TINY, 128, 1, 8),

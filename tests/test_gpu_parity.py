@@ -261,6 +261,50 @@ def test_mid_config_greedy_step(B, mode, root):
     assert got["commit_len"] >= 1
 
 
+@pytest.mark.parametrize("chunks", [(300,), (200, 130), (81, 512), (1024,), (40, 95)])
+def test_many_row_prefill_matches_oracle(B, chunks):
+    """Prompt chunks of more than 80 rows run through the block projection kernel (K-split residual projections at
+    this width): root logits and cache against the oracle's prefill, then one verify step on top."""
+    shape = inputs.MID
+    total = sum(chunks)
+    max_seq = (total + 40 + 31) // 32 * 32
+    say(f"MID many-row prefill chunks={chunks}")
+    w = inputs.make_weights(shape, seed=4, threads=16)
+    oshape = O.shape_from(shape)
+    eng = B.VerifyEngine(shape, w, max_seq, max_prefill_rows=max(chunks))
+    prefix = inputs.make_prefix_ids(shape, total, seed=4)
+    at = 0
+    for c in chunks:
+        eng.prefill(prefix[at:at + c].tolist(), chunk=c)
+        at += c
+    cache = O.prefill(oshape, w, prefix.tolist(), max_seq)
+    ok, max_abs, worst = logits_close(eng.root_logits.cpu().numpy(), cache.root_logits)
+    say(f"  root logits max abs err {max_abs:.3e} (worst err/bound {worst:.3f})")
+    assert ok
+    _check_cache(eng, cache, total)
+    assert int(eng.prefix_len.item()) == total
+    _check_step(B, shape, w, oshape, eng, cache, 2, 4, seed=9, mode=0, root_token=-1)
+
+
+def test_many_row_prefill_full_width_layer(B):
+    """One layer of 7B width, 1007 prompt rows: the launch shapes of a full-size chunk (unsplit residual projections
+    with the residual epilogue in the block kernel, the wider blocks for QKV and gate/up, heads of 128, GQA)."""
+    shape = inputs.WIDE1
+    total = 1007
+    max_seq = 1056
+    say("WIDE1 many-row prefill 1007 rows")
+    w = inputs.make_weights(shape, seed=6, threads=16)
+    oshape = O.shape_from(shape)
+    eng = B.VerifyEngine(shape, w, max_seq, max_prefill_rows=total)
+    prefix = inputs.make_prefix_ids(shape, total, seed=6)
+    eng.prefill(prefix.tolist(), chunk=total)
+    cache = O.prefill(oshape, w, prefix.tolist(), max_seq)
+    ok, max_abs, worst = logits_close(eng.root_logits.cpu().numpy(), cache.root_logits)
+    say(f"  root logits max abs err {max_abs:.3e} (worst err/bound {worst:.3f})")
+    assert ok
+    _check_cache(eng, cache, total)
+
+
 def test_cache_filled_to_the_last_slot(B):
     """prefix + rows == max_seq exactly: the last cache slot is written and read; one more row is refused."""
     shape = inputs.MID
