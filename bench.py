@@ -214,9 +214,16 @@ def main() -> int:
                 eng.prefill(prompt, chunk=args.prefill_chunk)
                 stream.synchronize()
                 times.append(time.perf_counter() - t6)
+            B.profile_enable(True)  # one more pass with per-kernel events
+            eng.set_prefix_len(0)
+            eng.prefill(prompt, chunk=args.prefill_chunk)
+            pprof = B.profile_read()
+            B.profile_enable(False)
+            stream.synchronize()
         best = min(times)
         out["prefill"] = {"tokens": args.prefill_tokens, "chunk": args.prefill_chunk, "ms": round(best * 1e3, 3),
-                          "tok_per_s": round(args.prefill_tokens / best, 1), "launch": "eager"}
+                          "tok_per_s": round(args.prefill_tokens / best, 1), "launch": "eager",
+                          "kernel_ms": {nm: round(v["ms"], 3) for nm, v in pprof.items() if v["launches"]}}
 
     if not args.no_cpu_baseline:
         from oracle import duo_oracle as O
