@@ -514,6 +514,13 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     const int b0 = cb * a.blocks_per_wave;  // here: blocks per chunk
     int nb = NB - b0;
     nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
+    {
+        // No row sees a key behind its own slot: the blocks behind the slot of this workgroup's last query row
+        // are masked for all of its rows and are left out (a prompt chunk's early rows skip the chunk's late keys).
+        const int r_last = min(a.plan.M * a.group, (int)(blockIdx.z + 1) * NWV * MTW * 16) - 1;
+        const int nb_vis = (a.plan.P + r_last / a.group) / 32 + 1 - b0;
+        nb = nb_vis < nb ? (nb_vis < 0 ? 0 : nb_vis) : nb;
+    }
 
     if (wave == NWV) {
         // ---- producer.  The cache stores the tiles as they are needed (see k_cache_offset / v_cache_offset):
