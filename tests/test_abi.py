@@ -45,7 +45,9 @@ def test_workspace_bytes_validation(lib):
     assert lib.duo_workspace_bytes(None, 8, C.byref(out)) == -1
     assert lib.duo_workspace_bytes(C.byref(cfg), 8, None) == -1
     assert lib.duo_workspace_bytes(C.byref(cfg), 0, C.byref(out)) == -2
-    assert lib.duo_workspace_bytes(C.byref(cfg), 81, C.byref(out)) == -2
+    assert lib.duo_workspace_bytes(C.byref(cfg), 81, C.byref(out)) == 0      # prompt chunks take up to 1024 rows
+    assert lib.duo_workspace_bytes(C.byref(cfg), 1024, C.byref(out)) == 0 and out.value > n
+    assert lib.duo_workspace_bytes(C.byref(cfg), 1025, C.byref(out)) == -2
     for field, bad in [("head_dim", 96), ("d_model", 770), ("max_seq", 250), ("n_kv_heads", 5), ("d_ff", 100)]:
         c2 = B.make_config(inputs.TINY, 256)
         setattr(c2, field, bad)
@@ -108,7 +110,7 @@ def test_other_entry_points_validate(lib):
     nbytes = B.workspace_bytes(cfg, 80)
     pf = lambda m, P, toks=0x1000: lib.duo_prefill_chunk(C.byref(cfg), C.byref(w), C.byref(cache), toks, m, P, 0x1000,
                                                          0x1000, nbytes, None)
-    assert pf(0, 0) == -2 and pf(81, 0) == -2 and pf(8, 250) == -3 and pf(8, -1) == -8 and pf(8, 0, None) == -1
+    assert pf(0, 0) == -2 and pf(1025, 0) == -2 and pf(8, 250) == -3 and pf(8, -1) == -8 and pf(8, 0, None) == -1
     out = C.c_size_t()
     assert lib.duo_sample_workspace_bytes(32000, 1, 8, C.byref(out)) == 0 and out.value >= 32000 * 8
     assert lib.duo_sample_workspace_bytes(1, 1, 8, C.byref(out)) == -2
@@ -127,7 +129,9 @@ def test_other_entry_points_validate(lib):
     assert lib.duo_pack_qkv(C.byref(cfg), None, 0x1000, 0x1000, 0x1000, None) == -1
     assert lib.duo_pack_qkv(C.byref(cfg), 0x1000, 0x1000, 0x1008, 0x1000, None) == -4
     assert lib.duo_pack_gate_up(C.byref(cfg), 0x1000, None, 0x1000, None) == -1
-    assert lib.duo_pack_activations(0x1000, 81, 64, 0x1000, None) == -2 and lib.duo_pack_activations(None, 8, 64, 0x1000, None) == -1
+    bg = lambda **kw: lib.duo_block_gemm(kw.get("x", 0x1000), 0x1000, 0x1000, kw.get("rows", 256), 64, kw.get("K", 64), None)
+    assert bg(x=None) == -1 and bg(rows=0) == -2 and bg(rows=1025) == -2 and bg(K=48) == -2 and bg(x=0x1002) == -4
+    assert lib.duo_pack_activations(0x1000, 2049, 64, 0x1000, None) == -2 and lib.duo_pack_activations(None, 8, 64, 0x1000, None) == -1
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
