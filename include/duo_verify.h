@@ -146,7 +146,10 @@ typedef struct duo_result {
     float   *logits_out; /* optional fp32 [rows][vocab] (rows = (root?1:0) + n*k), may be NULL */
 } duo_result;
 
-/* Bytes of device scratch duo_verify / duo_prefill_chunk need for calls of up to `max_rows` rows. */
+/* Bytes of device scratch a call of up to `max_rows` rows needs: duo_verify takes at most DUO_MAX_ROWS rows,
+ * duo_prefill_chunk at most DUO_MAX_PREFILL_ROWS.  Not monotonic across DUO_MAX_ROWS (a pass of more rows keeps the
+ * logits of its last row only): a caller that makes both kinds of call allocates the larger of
+ * duo_workspace_bytes(DUO_MAX_ROWS) and duo_workspace_bytes(its largest prefill chunk). */
 int duo_workspace_bytes(const duo_model_config *cfg, int max_rows, size_t *bytes);
 
 /*
@@ -180,9 +183,12 @@ int duo_verify(const duo_model_config *cfg, const duo_weights *w, duo_kv_cache *
                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Scores m <= DUO_MAX_ROWS tokens (device int32) as a continuation of the cached prefix with a
+ * Scores m <= DUO_MAX_PREFILL_ROWS tokens (device int32) as a continuation of the cached prefix with a
  * plain causal mask, appends their keys/values, advances *prefix_len by m and stores the last
- * row's logits in cache->root_logits: the target pass of Alg. 1 applied to prompt tokens.
+ * row's logits in cache->root_logits: the target pass of Alg. 1 applied to prompt tokens (the target model's
+ * share of the time to first token, Sec. 4.1).  Up to DUO_MAX_ROWS rows run through the verify pass's
+ * weight-streaming kernels; more rows through projection kernels that stage both operands in LDS, and only
+ * the last row's logits are computed.  `workspace` needs duo_workspace_bytes(cfg, m) bytes.
  */
 int duo_prefill_chunk(const duo_model_config *cfg, const duo_weights *w, duo_kv_cache *cache,
                       const int32_t *tokens, int m, int host_prefix_len, int32_t *status,

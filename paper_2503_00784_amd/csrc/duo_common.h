@@ -9,8 +9,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-#define DUO_WAVE 64
-
 // Every kernel launch of the library goes through DUO_LAUNCH.  When the per-kernel profiler is armed
 // (see duo_profile_enable) the launch carries a start and a stop event that take the dispatch's own
 // begin and end timestamps, the same clock a kernel trace reads; otherwise it is a plain launch.
@@ -65,14 +63,6 @@ __device__ __forceinline__ bf16x8 load_frag(const u16* p) {
     f.q = *reinterpret_cast<const u32x4*>(p);
     return f.v;
 }
-// weights and prefix KV are read once per step: mark the loads non-temporal so they do not
-// displace the activations that every workgroup re-reads from L2
-__device__ __forceinline__ bf16x8 load_frag_stream(const u16* p) {
-    Frag8 f;
-    f.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return f.v;
-}
-
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     // D[16x16] += A[16x32] * B[32x16]; lane l supplies A[l%16][8*(l/16) .. +8] and
     // B[8*(l/16) .. +8][l%16]; it receives D[4*(l/16) .. +4][l%16].
