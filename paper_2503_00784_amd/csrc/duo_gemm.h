@@ -423,6 +423,23 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
 
 // ---- epilogues -------------------------------------------------------------------------------
 // store(tile, qi, c, v): v[t][i] is the sum for row m = 4*qi + i, column c of tile slot t.
+// store4(tile, m, c4, v): v[t][i] is the sum for row m, column c4 + i of tile slot t (c4 = 0, 4, 8, 12): what a
+// lane holds when the weights are the first MFMA operand.  Four consecutive columns are 16 bytes of an fp32
+// row and 8 bytes (half a 16-byte chunk) of a bf16 operand buffer, so the stores are vectors.
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// four floats -> hi = bf16(x) and lo = bf16(x - hi), four bf16 values (8 bytes) each
+__device__ __forceinline__ void split_bf16x4(const f32x4& x, u32x2& hi, u32x2& lo) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint32_t h = pack_bf16x2(x[2 * j], x[2 * j + 1]);
+        hi[j] = h;
+        lo[j] = pack_bf16x2(x[2 * j] - __uint_as_float(h << 16), x[2 * j + 1] - __uint_as_float(h & 0xffff0000u));
+    }
+}
+__device__ __forceinline__ u32x2 pack_bf16x4(const f32x4& x) {
+    return u32x2{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+}
 
 struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile*NT + t)*16 .. +16 of W
     int N, M, NT;
@@ -442,6 +459,22 @@ struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile
             for (int i = 0; i < 4; ++i) {
                 const int m = qi * 4 + i;
                 if (m < M) y[(size_t)m * ldy + n] = v[t][i];
+            }
+        }
+    }
+    template <int NTT>
+    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[NTT]) const {
+        if (m >= M) return;
+        float* y = Y + blockIdx.y * split_stride + (size_t)m * ldy;
+#pragma unroll
+        for (int t = 0; t < NTT; ++t) {
+            const int n = (tile * NT + t) * 16 + c4;
+            if (n + 3 < N && (ldy & 3) == 0) {
+                *reinterpret_cast<f32x4*>(y + n) = v[t];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n + i < N) y[n + i] = v[t][i];
             }
         }
     }
@@ -496,6 +529,27 @@ struct EpiResidual {
             if (c == 0 && m < M) ssq_part[(size_t)m * (N >> 4) + tile] = sq[i];
         }
     }
+    // All 64 lanes call this together; the lanes c4 = 0, 4, 8, 12 of one row are 16 lanes apart.
+    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[1]) const {
+        const int n = tile * 16 + c4;
+        float sq = 0.f;
+        if (m < M) {
+            float* xp = X + (size_t)m * ldx + n;
+            const f32x4 xn = *reinterpret_cast<const f32x4*>(xp) + v[0];
+            *reinterpret_cast<f32x4*>(xp) = xn;
+            sq = (xn[0] * xn[0] + xn[1] * xn[1]) + (xn[2] * xn[2] + xn[3] * xn[3]);
+            const u32x2 gb = *reinterpret_cast<const u32x2*>(gain + n);
+            const f32x4 u = {xn[0] * __uint_as_float(gb[0] << 16), xn[1] * __uint_as_float(gb[0] & 0xffff0000u),
+                             xn[2] * __uint_as_float(gb[1] << 16), xn[3] * __uint_as_float(gb[1] & 0xffff0000u)};
+            u32x2 hi, lo;
+            split_bf16x4(u, hi, lo);
+            *reinterpret_cast<u32x2*>(h + operand_offset(m, n, h_tiles)) = hi;
+            *reinterpret_cast<u32x2*>(h + operand_offset(pair_rows + m, n, h_tiles)) = lo;
+        }
+        sq += __shfl_xor(sq, 16, 64);  // the tile's sixteen columns: four lanes, 16 apart
+        sq += __shfl_xor(sq, 32, 64);
+        if (c4 == 0 && m < M) ssq_part[(size_t)m * (N >> 4) + tile] = sq;
+    }
 };
 
 // band 0 = gate rows tile*16.., band 1 = up rows tile*16..; act[m][n] = silu(gate) * up, written as a
@@ -520,6 +574,17 @@ struct EpiSwiGLU {
                 act[operand_offset(pair_rows + m, n, act_tiles)] = f32_to_bf16(a - bf16_to_f32(hi));
             }
         }
+    }
+    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[2]) const {
+        const int n = tile * 16 + c4;
+        if (n >= F || m >= M) return;
+        f32x4 a;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = v[0][i] / (1.f + expf(-v[0][i])) * v[1][i];
+        u32x2 hi, lo;
+        split_bf16x4(a, hi, lo);
+        *reinterpret_cast<u32x2*>(act + operand_offset(m, n, act_tiles)) = hi;
+        *reinterpret_cast<u32x2*>(act + operand_offset(pair_rows + m, n, act_tiles)) = lo;
     }
 };
 
@@ -580,6 +645,38 @@ struct EpiQKV {
                 u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
                 vp[v_cache_offset(D, plan.slot(m), d)] = f32_to_bf16(lo);
                 vp[v_cache_offset(D, plan.slot(m), d + half)] = f32_to_bf16(hi);
+            }
+        }
+    }
+    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[2]) const {
+        if (m >= plan.M) return;
+        const int head = tile / bph;
+        const int d = (tile - head * bph) * 16 + c4;
+        const f32x4 lo = v[0], hi = v[1];
+        if (head < Hq + Hkv) {
+            const f32x4 cs = *reinterpret_cast<const f32x4*>(rope_cos + m * half + d);
+            const f32x4 sn = *reinterpret_cast<const f32x4*>(rope_sin + m * half + d);
+            const f32x4 rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
+            if (head < Hq) {
+                u16* q = q_out + (size_t)m * ldq + head * D + d;
+                u32x2 l1, l2, h1, h2;
+                split_bf16x4(rl, l1, l2);
+                split_bf16x4(rh, h1, h2);
+                *reinterpret_cast<u32x2*>(q) = l1;
+                *reinterpret_cast<u32x2*>(q + half) = h1;
+                *reinterpret_cast<u32x2*>(q + q_plane) = l2;
+                *reinterpret_cast<u32x2*>(q + q_plane + half) = h2;
+            } else {  // four consecutive channels are contiguous in a key tile
+                u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
+                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d)) = pack_bf16x4(rl);
+                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d + half)) = pack_bf16x4(rh);
+            }
+        } else {  // the value tiles keep eight SLOTS of one channel together: element stores
+            u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                vp[v_cache_offset(D, plan.slot(m), d + i)] = f32_to_bf16(lo[i]);
+                vp[v_cache_offset(D, plan.slot(m), d + half + i)] = f32_to_bf16(hi[i]);
             }
         }
     }

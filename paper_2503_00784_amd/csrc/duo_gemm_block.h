@@ -130,37 +130,30 @@ __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__
 #pragma unroll
                 for (int m = 0; m < WM; ++m)
 #pragma unroll
-                    for (int t = 0; t < WN; ++t) acc[m][t] = mfma16(ah[m], b[t], acc[m][t]);
+                    for (int t = 0; t < WN; ++t) acc[m][t] = mfma16(b[t], ah[m], acc[m][t]);
 #pragma unroll
                 for (int m = 0; m < WM; ++m)
 #pragma unroll
-                    for (int t = 0; t < WN; ++t) acc[m][t] = mfma16(al[m], b[t], acc[m][t]);
+                    for (int t = 0; t < WN; ++t) acc[m][t] = mfma16(b[t], al[m], acc[m][t]);
             }
         }
         __syncthreads();  // stage r + 1 is in LDS; stage r's buffer may be refilled
     }
 
-    // A lane's accumulator quad is rows 4*(lane/16) .. +3 of its row tile, column lane%16 of its band.
-    typename Epi::Pre pre;
+    // The weights are the FIRST operand of the products above, so a lane's accumulator quad is one output row
+    // (lane % 16 of the row tile) and four consecutive columns (4 * (lane / 16) .. +3 of the band): vector stores.
 #pragma unroll
     for (int m = 0; m < WM; ++m) {
-        const int qi = (row_tile0 + wm * WM + m) * 4 + (lane >> 4);
-        if (qi >= quads) continue;
-        float rs[4] = {1.f, 1.f, 1.f, 1.f};
-        if (rsc.part) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) rs[i] = row_scale[qi * 4 + i - row0];
-        }
+        const int row = (row_tile0 + wm * WM + m) * 16 + (lane & 15);
+        const float rs = (rsc.part && row < nrows) ? row_scale[row - row0] : 1.f;
 #pragma unroll
         for (int t = 0; t < WN; t += ENT) {
             const int band = band0 + wn * WN + t;
             if (band >= nbands) continue;  // wave-uniform
             f32x4 v[ENT];
 #pragma unroll
-            for (int e = 0; e < ENT; ++e)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[e][i] = acc[m][t + e][i] * rs[i];
-            epi.store(band / ENT, qi, lane & 15, v, pre, false);
+            for (int e = 0; e < ENT; ++e) v[e] = acc[m][t + e] * rs;
+            epi.store4(band / ENT, row, 4 * (lane >> 4), v);
         }
     }
 }
