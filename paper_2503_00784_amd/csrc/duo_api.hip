@@ -284,6 +284,19 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         sh_zg = (MqT + sh_nwv * sh_mtw - 1) / (sh_nwv * sh_mtw);
         int target = (256 + Hkv * sh_zg - 1) / (Hkv * sh_zg);
         target = target < 1 ? 1 : (target > max_chunks ? max_chunks : target);
+        if (many) {
+            // many row groups: the chunk count that leaves the fewest compute units idle in the last round of
+            // workgroups (160 (head, row group) pairs: 3 chunks = 480 workgroups, not 2 = 320), few chunks preferred
+            float best = -1.f;
+            for (int t = 1; t <= max_chunks; ++t) {
+                const int wgs = Hkv * sh_zg * t;
+                const float eff = (float)wgs / (float)((wgs + 255) / 256 * 256) - 0.04f * (float)t;
+                if (eff > best) {
+                    best = eff;
+                    target = t;
+                }
+            }
+        }
         bpw = (NB + target - 1) / target;  // blocks per chunk
         bpw = bpw < 2 ? 2 : bpw;
         nchunks = (NB + bpw - 1) / bpw;
