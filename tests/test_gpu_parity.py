@@ -305,6 +305,19 @@ def test_many_row_prefill_full_width_layer(B):
     _check_cache(eng, cache, total)
 
 
+@pytest.mark.parametrize("n,k,mode", [(2, 4, 0), (1, 1, 0), (3, 5, 1)])
+def test_empty_prefix_with_root_token(B, n, k, mode):
+    """Nothing cached yet: the root token is the first token of the text (position 0) and the only shared context."""
+    shape = inputs.MID
+    say(f"MID empty prefix n={n} k={k} mode={mode}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 0, 64, seed=11, synthetic_cache=True)
+    assert cache.prefix_len == 0
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=4, mode=mode, root_token=9)
+    assert got["new_prefix_len"] == 1 + got["commit_len"]
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len)
+
+
 def test_cache_filled_to_the_last_slot(B):
     """prefix + rows == max_seq exactly: the last cache slot is written and read; one more row is refused."""
     shape = inputs.MID
