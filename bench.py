@@ -128,6 +128,31 @@ def main() -> int:
         res = eng.results(n)
         assert res["status"] == 0, res
 
+        # distribution of the step latency: one event pair per replay, outside the timed region
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(args.steps, 100))]
+        for a, b in ev:
+            a.record()
+            run()
+            b.record()
+        stream.synchronize()
+        lat = sorted(a.elapsed_time(b) for a, b in ev)
+        pct = lambda f: lat[min(len(lat) - 1, int(f * len(lat)))]
+
+        # what a plain streaming read reaches on this device: one 4 GiB buffer (far beyond the caches), five launches
+        probe_buf = torch.empty(1 << 30, dtype=torch.int32, device="cuda")
+        probe_buf.fill_(1)
+        probe_bytes = probe_buf.numel() * 4
+        sink = torch.zeros(2048, dtype=torch.int32, device="cuda")
+        B.stream_read_probe(probe_buf, sink)
+        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for a, b in pe:
+            a.record()
+            B.stream_read_probe(probe_buf, sink)
+            b.record()
+        stream.synchronize()
+        probe_gbps = probe_bytes / (min(a.elapsed_time(b) for a, b in pe) * 1e-3) / 1e9
+        del probe_buf
+
         # per-kernel timing pass (eager launches with HIP events between kernels on the same stream)
         B.profile_enable(True)
         prof_steps = min(args.steps, 20)
@@ -168,6 +193,10 @@ def main() -> int:
                       "launch": "hip_graph_replay" if graph is not None else "eager"},
            "verify_latency_ms": round(ms_per_step, 4), "algorithmic_bytes": algo_bytes,
            "achieved_hbm_GBps": round(achieved, 1), "frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
+           "latency_ms_p10_p50_p90": [round(pct(0.1), 4), round(pct(0.5), 4), round(pct(0.9), 4)],
+           "committed_tokens_per_s": round((int(res["commit_len"]) + 1) / (ms_per_step * 1e-3), 1),
+           "stream_read_probe": {"GBps": round(probe_gbps, 1), "bytes": probe_bytes,
+                                 "what": "one kernel of plain 16-byte loads over a 4 GiB buffer, best of five"},
            "roofline": roofline, "kernels": kernels}
 
     if args.k_sweep:

@@ -23,7 +23,7 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_block_gemm", "duo_k_cache_offset",
+           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_block_gemm", "duo_stream_read_probe", "duo_k_cache_offset",
            "duo_v_cache_offset", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
            "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
@@ -93,6 +93,8 @@ def load() -> C.CDLL:
                                         C.c_size_t, C.c_void_p]
     lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.duo_block_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+    lib.duo_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
+    lib.duo_stream_read_probe.restype = C.c_int
     lib.duo_packed_elems.argtypes = [C.c_int, C.c_int]
     lib.duo_packed_elems.restype = C.c_size_t
     for name in ("duo_k_cache_offset", "duo_v_cache_offset"):
@@ -263,6 +265,13 @@ class DeviceWeights:
             tab = (C.c_void_p * L)(*[t.data_ptr() for t in self.tensors[key]])
             self._tables[key] = tab
             setattr(self.c, key, C.cast(tab, C.POINTER(C.c_void_p)))
+
+    def all_tensors(self):
+        """Every device tensor of the model (packed matrices, embedding, gains), in no particular order."""
+        out = []
+        for v in self.tensors.values():
+            out.extend(v if isinstance(v, list) else [v])
+        return out
 
 
 class VerifyEngine:
@@ -463,3 +472,9 @@ def block_gemm(hi_bits, lo_bits, w_bits):
     y = torch.empty((rows, N), dtype=torch.float32, device=hi_bits.device)
     _check(load().duo_block_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_block_gemm")
     return y
+
+
+def stream_read_probe(buf, sink) -> None:
+    """Enqueue one plain streaming read of the device tensor `buf` (duo_stream_read_probe); `sink` is an int32 tensor."""
+    _check(load().duo_stream_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), sink.numel(),
+                                        _stream_ptr()), "duo_stream_read_probe")

@@ -607,6 +607,17 @@ int duo_block_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, int
     return hip_ok(hipGetLastError(), "duo_block_gemm launch");
 }
 
+int duo_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int sink_len, void* hip_stream) {
+    if (!src || !sink) return DUO_ERR_NULL;
+    if (bytes < 16 || sink_len < 1) return DUO_ERR_SHAPE;
+    if (!aligned16(src)) return DUO_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    const int grid = sink_len < 2048 ? sink_len : 2048;
+    DUO_LAUNCH(stream_read_kernel, dim3(grid), dim3(256), s, static_cast<const u32x4*>(src), bytes / 16, sink);
+    return hip_ok(hipGetLastError(), "duo_stream_read_probe launch");
+}
+
 size_t duo_k_cache_offset(int head_dim, int slot, int channel) { return k_cache_offset(head_dim, slot, channel); }
 size_t duo_v_cache_offset(int head_dim, int slot, int channel) { return v_cache_offset(head_dim, slot, channel); }
 

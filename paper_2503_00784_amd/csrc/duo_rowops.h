@@ -148,3 +148,24 @@ __global__ __launch_bounds__(64) void last_row_operand_kernel(const u16* __restr
     }
     *reinterpret_cast<u32x4*>(dst + ((size_t)ks * 64 + lane) * 8) = v;
 }
+
+// Plain streaming read of `chunks` 16-byte chunks (the ceiling a weight stream can reach on the device): every lane
+// keeps eight independent 16-byte loads in flight, 1 KiB per wave and load instruction as in the projection kernels;
+// the xor of everything read goes to sink[workgroup] so that the loads cannot be dropped.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t chunks, uint32_t* __restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < chunks; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j];
+    }
+    for (; i < chunks; i += stride) acc ^= src[i];
+    uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o, 64);
+    if ((threadIdx.x & 63) == 0) atomicXor(sink + blockIdx.x, x);
+}
