@@ -73,6 +73,8 @@ LLAMA3_8B = ModelShape(32, 4096, 32, 8, 128, 14336, 128256, rope_theta=500000.0)
 MID = ModelShape(3, 512, 8, 2, 64, 1408, 4099)
 # one 7B-wide layer (GQA, heads of 128): the launch shapes a prompt chunk of ~1000 rows takes at full width
 WIDE1 = ModelShape(1, 4096, 32, 8, 128, 4096, 1000)
+# one layer of 13B width (d_model 5120, 40 heads, d_ff 13824): band counts and K ranges other than the 7B/8B ones
+WIDE13 = ModelShape(1, 5120, 40, 40, 128, 13824, 1000)
 
 WORKLOADS: Dict[str, Workload] = {
     "C0": Workload("C0-tiny-P128-n1-k8", TINY, 128, 1, 8),

@@ -318,6 +318,18 @@ def test_empty_prefix_with_root_token(B, n, k, mode):
         _check_cache(eng, cache, cache.prefix_len)
 
 
+@pytest.mark.parametrize("n,k,root", [(1, 8, -1), (4, 16, 3), (2, 12, -1)])
+def test_other_width_single_layer(B, n, k, root):
+    """One layer of 13B width: the launch rules (waves per band group, K splits, attention shapes) at band counts
+    and K ranges other than those of the benchmark shapes."""
+    shape = inputs.WIDE13
+    say(f"WIDE13 n={n} k={k} root={root}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 300, 448, seed=13, synthetic_cache=True)
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n + k, mode=0, root_token=root)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len)
+
+
 def test_cache_filled_to_the_last_slot(B):
     """prefix + rows == max_seq exactly: the last cache slot is written and read; one more row is refused."""
     shape = inputs.MID
