@@ -271,12 +271,39 @@ def full_forward_uncached(shape: OracleShape, weights: Dict[str, object], tokens
 
 
 # ----------------------------------------------------------------------------- sampling
-def target_probs(logits_f32: np.ndarray, temperature: float) -> np.ndarray:
+def nucleus(p: np.ndarray, top_p: float) -> Tuple[np.ndarray, float]:
+    """Nucleus (top-p) restriction of one distribution: the most probable tokens, taken in order of
+    decreasing probability (equal probabilities by ascending id), up to and including the one with
+    which their mass reaches top_p; everything else set to zero and the rest renormalised.
+
+    Returns (p', margin): margin is the distance of the running mass from the cut at the two positions
+    that decide where the nucleus ends (a different summation order can only move the end when it is tiny).
+    """
+    p = np.asarray(p, dtype=np.float64)
+    order = np.argsort(-p, kind="stable")
+    c = np.cumsum(p[order])
+    target = float(top_p) * c[-1]
+    m = int(np.searchsorted(c, target, side="left"))  # first position whose running mass is >= target
+    m = min(m, len(p) - 1)
+    keep = order[:m + 1]
+    out = np.zeros_like(p)
+    out[keep] = p[keep] / p[keep].sum()
+    before = c[m - 1] if m > 0 else 0.0
+    return out, float(min(c[m] - target, target - before) / c[-1])
+
+
+def target_probs(logits_f32: np.ndarray, temperature: float, top_p: float = 0.0) -> np.ndarray:
     """p = softmax(logits / T) in float64 from float32 logits.
 
     T = 0 is the limit T -> 0+: all mass on the largest logit, on the lowest id among equal ones
     (the greedy setting; Alg. 2 is then applied to this one-hot p without any other change).
+    0 < top_p < 1 restricts every row to its nucleus (see `nucleus`); other values leave p as it is.
     """
+    if 0.0 < float(top_p) < 1.0 and float(temperature) != 0.0:
+        full = target_probs(logits_f32, temperature)
+        if full.ndim == 1:
+            return nucleus(full, top_p)[0]
+        return np.stack([nucleus(r, top_p)[0] for r in full])
     l32 = np.asarray(logits_f32, dtype=np.float32)
     if float(temperature) == 0.0:
         p = np.zeros(l32.shape, dtype=np.float64)
@@ -352,7 +379,7 @@ def _chain(i: int, start: int, judge, q, tokens, u, k_draft: int) -> Tuple[int, 
 def speculative_verify(logits_f32: np.ndarray, root_logits_f32: np.ndarray, draft_tokens: np.ndarray,
                        draft_probs: np.ndarray, uniforms: np.ndarray, prefix_len: int,
                        temperature: float = 1.0, select_mode: int = MODE_INDEPENDENT_LONGEST,
-                       has_root: bool = False) -> VerifyResult:
+                       has_root: bool = False, top_p: float = 0.0) -> VerifyResult:
     """Speculative sampling over n sequences of k draft tokens (Alg. 2 recast; Sec. 3.3).
 
     logits_f32[(R +) i*k + j] scores the token after draft (i, j); the distribution judging
@@ -365,7 +392,7 @@ def speculative_verify(logits_f32: np.ndarray, root_logits_f32: np.ndarray, draf
     R = 1 if has_root else 0
     q = draft_probs
     u = np.asarray(uniforms, dtype=np.float32).astype(np.float64)
-    p_root = target_probs(logits_f32[0] if has_root else root_logits_f32, temperature)
+    p_root = target_probs(logits_f32[0] if has_root else root_logits_f32, temperature, top_p)
     cache_p: Dict[Tuple[int, int], np.ndarray] = {}
 
     def judge(i: int, j: int) -> np.ndarray:
@@ -373,7 +400,7 @@ def speculative_verify(logits_f32: np.ndarray, root_logits_f32: np.ndarray, draf
         if j == 0:
             return p_root
         if (i, j) not in cache_p:
-            cache_p[(i, j)] = target_probs(logits_f32[R + i * k + j - 1], temperature)
+            cache_p[(i, j)] = target_probs(logits_f32[R + i * k + j - 1], temperature, top_p)
         return cache_p[(i, j)]
 
     def finish(i: int, a: int) -> Tuple[int, float]:
@@ -452,13 +479,13 @@ def commit_kv(cache: OracleCache, res: VerifyResult, k_draft: int, has_root: boo
 def oracle_verify(shape: OracleShape, weights: Dict[str, object], cache: OracleCache,
                   draft_tokens: np.ndarray, draft_probs: np.ndarray, uniforms: np.ndarray,
                   temperature: float = 1.0, select_mode: int = MODE_INDEPENDENT_LONGEST,
-                  root_token: int = -1, rounding: str = "contract"
+                  root_token: int = -1, rounding: str = "contract", top_p: float = 0.0
                   ) -> Tuple[VerifyResult, np.ndarray]:
     """The whole step: target pass, speculative sampling, KV commit.  Returns (result, fp32 logits)."""
     P = cache.prefix_len
     logits = verify_forward(shape, weights, cache, draft_tokens, root_token, rounding).astype(np.float32)
     res = speculative_verify(logits, cache.root_logits, draft_tokens, draft_probs, uniforms, P,
-                             temperature, select_mode, has_root=root_token >= 0)
+                             temperature, select_mode, has_root=root_token >= 0, top_p=top_p)
     k_draft = np.asarray(draft_tokens).shape[1]
     commit_kv(cache, res, k_draft, root_token >= 0)
     return res, logits

@@ -397,3 +397,92 @@ def test_greedy_equals_a_very_small_temperature():
             b = O.speculative_verify(logits, root, toks, q, u, prefix_len=0, temperature=1e-4, select_mode=mode)
             assert (a.selected, a.commit_len, a.commit_token) == (b.selected, b.commit_len, b.commit_token)
             assert a.accept_len.tolist() == b.accept_len.tolist() and a.next_token.tolist() == b.next_token.tolist()
+
+
+# ------------------------------------------------------------------ nucleus (top-p) restriction of the target
+def _nucleus_by_hand(p, top_p):
+    """The definition spelled out with a Python sort and a running sum."""
+    order = sorted(range(len(p)), key=lambda v: (-p[v], v))
+    total, run, keep = float(np.sum(p)), 0.0, []
+    for v in order:
+        keep.append(v)
+        run += p[v]
+        if run >= top_p * total:
+            break
+    out = np.zeros(len(p))
+    out[keep] = p[keep] / np.sum(p[keep])
+    return out
+
+
+def test_nucleus_hand_values_and_ties_by_ascending_id():
+    p = np.array([0.5, 0.2, 0.2, 0.1])
+    out, _ = O.nucleus(p, 0.6)
+    np.testing.assert_allclose(out, [5 / 7, 2 / 7, 0, 0], rtol=1e-15)     # of the two 0.2s the lower id is taken
+    out, _ = O.nucleus(p, 0.45)
+    assert out.tolist() == [1.0, 0.0, 0.0, 0.0]
+    out, _ = O.nucleus(p, 0.95)
+    np.testing.assert_allclose(out, p, rtol=1e-15)                          # everything is needed
+    out, _ = O.nucleus(np.array([0.1, 0.4, 0.1, 0.4]), 0.5)
+    np.testing.assert_allclose(out, [0, 0.5, 0, 0.5], rtol=1e-15)           # .4 (id 1) < .5, so id 3 joins
+
+
+def test_nucleus_properties_and_brute_force():
+    g = np.random.default_rng(31)
+    for trial in range(200):
+        V = int(g.integers(2, 40))
+        p = _dist(g, V, sharp=float(g.uniform(0.3, 3.0)))
+        if trial % 5 == 0:                       # some exact ties
+            p[int(g.integers(V))] = p[int(g.integers(V))]
+            p /= p.sum()
+        top_p = float(g.uniform(0.05, 0.99))
+        out, margin = O.nucleus(p, top_p)
+        if margin < 1e-12:
+            continue
+        np.testing.assert_allclose(out, _nucleus_by_hand(p, top_p), rtol=1e-13, atol=0)
+        kept = out > 0
+        assert abs(out.sum() - 1.0) < 1e-12
+        assert p[kept].sum() >= top_p * p.sum() - 1e-15                       # enough mass
+        assert p[kept].sum() - p[kept].min() < top_p * p.sum() + 1e-15        # and no token too many
+        if (~kept).any():
+            assert p[kept].min() >= p[~kept].max()                            # the most probable ones
+        np.testing.assert_allclose(out[kept] / out[kept].sum(), p[kept] / p[kept].sum(), rtol=1e-13)
+
+
+def test_top_p_switched_off_and_its_greedy_limit():
+    g = np.random.default_rng(32)
+    V, n, k = 19, 2, 3
+    logits = g.normal(size=(n * k, V)).astype(np.float32)
+    root = g.normal(size=V).astype(np.float32)
+    q = np.stack([[_dist(g, V) for _ in range(k)] for _ in range(n)])
+    toks = g.integers(0, V, size=(n, k))
+    toks[0, 0] = int(np.argmax(root))
+    u = g.random((n, k + 1)).astype(np.float32)
+    key = lambda r: (r.selected, r.commit_len, r.commit_token, r.accept_len.tolist(), r.next_token.tolist())
+    for mode in (O.MODE_INDEPENDENT_LONGEST, O.MODE_PAPER_SEQUENTIAL):
+        base = O.speculative_verify(logits, root, toks, q, u, 0, select_mode=mode)
+        for off in (0.0, 1.0, 1.5, -0.3):
+            assert key(O.speculative_verify(logits, root, toks, q, u, 0, select_mode=mode, top_p=off)) == key(base)
+        greedy = O.speculative_verify(logits, root, toks, q, u, 0, temperature=0.0, select_mode=mode)
+        tiny = O.speculative_verify(logits, root, toks, q, u, 0, select_mode=mode, top_p=1e-9)
+        assert key(tiny) == key(greedy)         # a nucleus of one token is the arg max
+
+
+def test_first_emitted_token_follows_the_nucleus_of_the_target():
+    """With top-p the method must reproduce the RESTRICTED target distribution, and only that one."""
+    g = np.random.default_rng(33)
+    V, N, top_p = 12, 30000, 0.7
+    p, q1 = _dist(g, V, 1.5), _dist(g, V, 1.5)
+    rows = _logits(_dist(g, V))[None]
+    want = O.nucleus(_f32_probs(p), top_p)[0]
+    assert 2 <= (want > 0).sum() < V
+    counts = np.zeros(V)
+    for _ in range(N):
+        t = _draw(g, q1)
+        u = g.random((1, 2)).astype(np.float32)
+        res = O.speculative_verify(rows, _logits(p), np.array([[t]]), q1[None, None], u, 0, top_p=top_p)
+        counts[t if res.commit_len >= 1 else res.commit_token] += 1
+    assert counts[want == 0].sum() == 0
+    assert stats.chisquare(counts[want > 0], want[want > 0] * N).pvalue > 1e-3
+    full = _f32_probs(p)
+    assert stats.chisquare(counts[want > 0], full[want > 0] / full[want > 0].sum() * N).pvalue > 1e-3  # same shape inside
+    assert abs(counts[int(np.argmax(full))] / N - full.max()) > 0.02           # but not the unrestricted probabilities
