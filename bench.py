@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--draft-step-ms", type=float, default=0.0,
                     help="with --k-sweep: time of one draft-model step on the host; adds the cost coefficient c(k) and the "
                     "balanced draft budget gamma")
+    ap.add_argument("--top-p", type=float, default=0.0, help="nucleus restriction of the target distributions in the timed step "
+                    "(a variant; the headline number is quoted without it)")
     ap.add_argument("--prefill-tokens", type=int, default=0,
                     help="also time the prefill of this many prompt tokens from an empty cache (time to first token of the "
                     "target model, Sec. 4.1) and add \"prefill\" to the line")
@@ -87,7 +89,7 @@ def main() -> int:
     def step():
         # restore the cache state (the previous step's commit advanced the prefix length), then verify
         eng.set_prefix_len(P)
-        eng.verify(d_toks, d_q, d_u, logits_out=logits)
+        eng.verify(d_toks, d_q, d_u, logits_out=logits, top_p=args.top_p)
 
     if args.calibration_copy:
         # A kernel of known traffic for the hardware counters: reads 256 MiB, writes 256 MiB, outside the timed region.
@@ -190,7 +192,8 @@ def main() -> int:
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": wl.name, "prefix_len": P, "n_seq": n, "k_draft": k, "rows": n * k,
-                      "launch": "hip_graph_replay" if graph is not None else "eager"},
+                      "launch": "hip_graph_replay" if graph is not None else "eager",
+                      **({"top_p": args.top_p} if 0.0 < args.top_p < 1.0 else {})},
            "verify_latency_ms": round(ms_per_step, 4), "algorithmic_bytes": algo_bytes,
            "achieved_hbm_GBps": round(achieved, 1), "frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
            "latency_ms_p10_p50_p90": [round(pct(0.1), 4), round(pct(0.5), 4), round(pct(0.9), 4)],
@@ -265,7 +268,7 @@ def main() -> int:
         oshape = O.shape_from(shape)
         cache = O.OracleCache.from_bits(oshape, kb, vb, P, root)
         t3 = time.perf_counter()
-        ores, ol = O.oracle_verify(oshape, w, cache, toks, q, u)
+        ores, ol = O.oracle_verify(oshape, w, cache, toks, q, u, top_p=args.top_p)
         t4 = time.perf_counter()
         gl = logits.cpu().numpy()
         err = float(np.abs(gl - ol).max())

@@ -132,6 +132,11 @@ typedef struct duo_call {
                                 row in front of every sequence (its logits judge the first draft
                                 tokens); < 0: cache.root_logits judges them */
     int32_t host_prefix_len; /* P as the host knows it; sizes the launch and is checked on device */
+    float   top_p;           /* 0 < top_p < 1 (and temperature > 0): every target distribution is first restricted to its
+                                nucleus, the most probable tokens in order of decreasing probability (equal ones by
+                                ascending id) up to and including the one with which their mass reaches top_p, and
+                                renormalised; Alg. 2 then runs on the restricted distributions.  Any other value
+                                (0 included): no restriction.  The draft distributions are taken as given. */
 } duo_call;
 
 /* Outputs (device).  Alg. 2 returns the new prefix length, the new prefix and the unverified

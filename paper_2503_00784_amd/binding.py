@@ -51,7 +51,7 @@ class KVCache(C.Structure):
 
 class Call(C.Structure):
     _fields_ = [("n", C.c_int32), ("k", C.c_int32), ("temperature", C.c_float), ("select_mode", C.c_int32),
-                ("root_token", C.c_int32), ("host_prefix_len", C.c_int32)]
+                ("root_token", C.c_int32), ("host_prefix_len", C.c_int32), ("top_p", C.c_float)]
 
 
 class Result(C.Structure):
@@ -347,11 +347,12 @@ class VerifyEngine:
             self.host_prefix_len += m
 
     def verify(self, draft_tokens, draft_probs, uniforms, temperature: float = 1.0,
-               select_mode: int = SELECT_INDEPENDENT_LONGEST, root_token: int = -1, logits_out=None) -> None:
+               select_mode: int = SELECT_INDEPENDENT_LONGEST, root_token: int = -1, logits_out=None,
+               top_p: float = 0.0) -> None:
         """Enqueue one verify step on torch's current stream.  Inputs are device tensors:
         draft_tokens int32 [n][k], draft_probs fp32 [n][k][V], uniforms fp32 [n][k+1]."""
         n, k = draft_tokens.shape
-        call = Call(n, k, float(temperature), int(select_mode), int(root_token), self.host_prefix_len)
+        call = Call(n, k, float(temperature), int(select_mode), int(root_token), self.host_prefix_len, float(top_p))
         res = Result(self.accept_len.data_ptr(), self.next_token.data_ptr(), self.commit.data_ptr(),
                      self.status.data_ptr(), _ptr(logits_out))
         rc = self.lib.duo_verify(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),
@@ -360,13 +361,14 @@ class VerifyEngine:
         _check(rc, "duo_verify")
 
     def verify_deferred(self, unverified_tokens, unverified_probs, uniforms, first_tokens=None, first_probs=None,
-                        uniforms_first=None, temperature: float = 1.0, root_token: int = -1, logits_out=None) -> None:
+                        uniforms_first=None, temperature: float = 1.0, root_token: int = -1, logits_out=None,
+                        top_p: float = 0.0) -> None:
         """Enqueue one round of Alg. 2 as listed (duo_verify_deferred) on torch's current stream.
         unverified_tokens int32 [l], unverified_probs fp32 [l][V], uniforms fp32 [l+1]; first_tokens int32 [s],
         first_probs fp32 [s][V], uniforms_first fp32 [s] (all three None for s = 0)."""
         l = int(unverified_tokens.shape[0])
         s_new = 0 if first_tokens is None else int(first_tokens.shape[0])
-        call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, int(root_token), self.host_prefix_len)
+        call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, int(root_token), self.host_prefix_len, float(top_p))
         res = Result(self.accept_len.data_ptr(), self.next_token.data_ptr(), self.commit.data_ptr(),
                      self.status.data_ptr(), _ptr(logits_out))
         rc = self.lib.duo_verify_deferred(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),
@@ -388,8 +390,8 @@ class VerifyEngine:
 
 
 def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temperature: float = 1.0,
-                select_mode: int = SELECT_INDEPENDENT_LONGEST, has_root: bool = False, prefix_len: int = 0
-                ) -> Dict[str, object]:
+                select_mode: int = SELECT_INDEPENDENT_LONGEST, has_root: bool = False, prefix_len: int = 0,
+                top_p: float = 0.0) -> Dict[str, object]:
     """duo_spec_sample on device tensors; returns host results."""
     import torch
     lib = load()
@@ -403,7 +405,7 @@ def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temper
     next_token = torch.zeros(n, dtype=torch.int32, device=dev)
     commit = torch.zeros(4, dtype=torch.int32, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
-    call = Call(n, k, float(temperature), int(select_mode), 0 if has_root else -1, int(prefix_len))
+    call = Call(n, k, float(temperature), int(select_mode), 0 if has_root else -1, int(prefix_len), float(top_p))
     res = Result(accept_len.data_ptr(), next_token.data_ptr(), commit.data_ptr(), status.data_ptr(), None)
     rc = lib.duo_spec_sample(logits.data_ptr(), _ptr(root_logits), vocab, draft_tokens.data_ptr(), draft_probs.data_ptr(),
                              uniforms.data_ptr(), C.byref(call), C.byref(res), ws.data_ptr(), nbytes.value, _stream_ptr())
@@ -417,7 +419,7 @@ def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temper
 
 def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, uniforms, first_tokens=None,
                     first_probs=None, uniforms_first=None, temperature: float = 1.0, has_root: bool = False,
-                    prefix_len: int = 0) -> Dict[str, object]:
+                    prefix_len: int = 0, top_p: float = 0.0) -> Dict[str, object]:
     """duo_deferred_sample on device tensors; returns host results."""
     import torch
     lib = load()
@@ -432,7 +434,7 @@ def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, un
     next_token = torch.zeros(1, dtype=torch.int32, device=dev)
     commit = torch.zeros(4, dtype=torch.int32, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
-    call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, 0 if has_root else -1, int(prefix_len))
+    call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, 0 if has_root else -1, int(prefix_len), float(top_p))
     res = Result(accept_len.data_ptr(), next_token.data_ptr(), commit.data_ptr(), status.data_ptr(), None)
     rc = lib.duo_deferred_sample(logits.data_ptr(), _ptr(root_logits), vocab, unverified_tokens.data_ptr(),
                                  unverified_probs.data_ptr(), uniforms.data_ptr(), _ptr(first_tokens), _ptr(first_probs),

@@ -50,6 +50,8 @@ struct Workspace {
     float* logits;   // fp32 [Mp][V]
     double* stats;   // sampler
     double* p_run;
+    double* nuc;     // nucleus records [DUO_MAX_ROWS + 1][4]
+    double* p_rows;  // nucleus search scratch [DUO_MAX_ROWS + 1][vocab]
     int32_t* acc;
     float* ssq;      // [Mp][d/16] partial sums of squares of the residual stream (for the next RMSNorm)
     float* ssq_full; // [Mp] complete sums of squares (written by the one-workgroup-per-row producers)
@@ -61,7 +63,8 @@ struct Workspace {
 
 size_t sample_ws_bytes(int vocab) {
     return align_up((size_t)2 * DUO_MAX_ROWS * STATS_SPLIT * 2 * sizeof(double), 256) + align_up((size_t)vocab * sizeof(double), 256) +
-           align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256);
+           align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256) + align_up((size_t)(DUO_MAX_ROWS + 1) * 4 * sizeof(double), 256) +
+           align_up((size_t)(DUO_MAX_ROWS + 1) * vocab * sizeof(double), 256);
 }
 
 void carve_sampler(char* base, size_t& off, int vocab, Workspace& ws) {
@@ -71,6 +74,10 @@ void carve_sampler(char* base, size_t& off, int vocab, Workspace& ws) {
     off += align_up((size_t)vocab * sizeof(double), 256);
     ws.acc = reinterpret_cast<int32_t*>(base + off);
     off += align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256);
+    ws.nuc = reinterpret_cast<double*>(base + off);
+    off += align_up((size_t)(DUO_MAX_ROWS + 1) * 4 * sizeof(double), 256);
+    ws.p_rows = reinterpret_cast<double*>(base + off);
+    off += align_up((size_t)(DUO_MAX_ROWS + 1) * vocab * sizeof(double), 256);
 }
 
 Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
@@ -369,10 +376,24 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     launch_projection<2>(M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
 }
 
-void enqueue_sampling(const SampleArgs& sa, int mode, u16* kc, u16* vc, const duo_model_config* c, int32_t* prefix_len,
-                      hipStream_t s) {
+// Nucleus sampling is on for 0 < top_p < 1 at a positive temperature (at temperature 0 the distribution is one-hot).
+bool nucleus_on(const duo_call* call) { return call->top_p > 0.f && call->top_p < 1.f && call->temperature > 0.f; }
+
+// After the statistics: the nucleus of every judging row (sa.nuc is where the other kernels will look for it).
+void enqueue_nucleus(const SampleArgs& sa, float top_p, const Workspace& ws, hipStream_t s) {
+    if (!sa.nuc) return;
+    prof(DUO_PROF_SAMPLE, s);
+    if (sa.V <= 32 * SAMPLE_THREADS)
+        DUO_LAUNCH(sample_nucleus_kernel<32>, dim3(1 + sa.n * sa.k), dim3(SAMPLE_THREADS), s, sa, (double)top_p, ws.p_rows, ws.nuc);
+    else
+        DUO_LAUNCH(sample_nucleus_kernel<0>, dim3(1 + sa.n * sa.k), dim3(SAMPLE_THREADS), s, sa, (double)top_p, ws.p_rows, ws.nuc);
+}
+
+void enqueue_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, int mode, u16* kc, u16* vc,
+                      const duo_model_config* c, int32_t* prefix_len, hipStream_t s) {
     prof(DUO_PROF_SAMPLE, s);
     DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, sa.n, STATS_SPLIT), dim3(256), s, sa);
+    enqueue_nucleus(sa, top_p, ws, s);
     prof(DUO_PROF_SAMPLE, s);
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST) {
         // one sequence: nothing to choose and nothing to move, the finish kernel writes the commit itself
@@ -395,6 +416,7 @@ int check_call(const duo_call* call, int vocab) {
     const int R = call->root_token >= 0 ? 1 : 0;
     if ((long long)call->n * call->k + R > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
     if (!(call->temperature >= 0.f)) return DUO_ERR_ARG;  // 0 is the greedy limit; NaN fails the comparison
+    if (call->top_p != call->top_p) return DUO_ERR_ARG;    // NaN
     if (call->select_mode != DUO_SELECT_INDEPENDENT_LONGEST && call->select_mode != DUO_SELECT_PAPER_SEQUENTIAL)
         return DUO_ERR_ARG;
     if (call->root_token >= vocab) return DUO_ERR_TOKEN_RANGE;
@@ -447,8 +469,9 @@ int duo_verify(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* 
     enqueue_forward(*cfg, *w, *cache, draft_tokens, call->root_token, plan, ws, logits, out->status, s);
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, call->n, call->k, R, call->host_prefix_len,
                   (double)call->temperature, draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run,
-                  out->accept_len, out->next_token, out->commit, out->status};
-    enqueue_sampling(sa, call->select_mode, cache->k, cache->v, cfg, cache->prefix_len, s);
+                  out->accept_len, out->next_token, out->commit, out->status,
+                  nucleus_on(call) ? ws.nuc : nullptr};
+    enqueue_sampling(sa, call->top_p, ws, call->select_mode, cache->k, cache->v, cfg, cache->prefix_len, s);
     return hip_ok(hipGetLastError(), "duo_verify launch");
 }
 
@@ -502,8 +525,9 @@ int duo_spec_sample(const float* logits, const float* root_logits, int vocab, co
     DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     SampleArgs sa{logits, vocab, root_logits, vocab, call->n, call->k, R, call->host_prefix_len, (double)call->temperature,
                   draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
-                  out->commit, out->status};
-    enqueue_sampling(sa, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
+                  out->commit, out->status,
+                  nucleus_on(call) ? ws.nuc : nullptr};
+    enqueue_sampling(sa, call->top_p, ws, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
     return hip_ok(hipGetLastError(), "duo_spec_sample launch");
 }
 
@@ -518,9 +542,11 @@ static int check_deferred(const duo_call* call, int vocab, const int32_t* first_
     return DUO_OK;
 }
 
-static void enqueue_deferred_sampling(const SampleArgs& sa, const DeferredArgs& da, hipStream_t s) {
+static void enqueue_deferred_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, const DeferredArgs& da,
+                                      hipStream_t s) {
     prof(DUO_PROF_SAMPLE, s);
     DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, 1, STATS_SPLIT), dim3(256), s, sa);
+    enqueue_nucleus(sa, top_p, ws, s);
     prof(DUO_PROF_SAMPLE, s);
     DUO_LAUNCH(sample_deferred_kernel, dim3(1), dim3(SAMPLE_THREADS), s, sa, da);
 }
@@ -554,8 +580,9 @@ int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_k
     enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s);
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, 1, call->k, R, call->host_prefix_len,
                   (double)call->temperature, unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run,
-                  out->accept_len, out->next_token, out->commit, out->status};
-    enqueue_deferred_sampling(sa, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, cache->prefix_len}, s);
+                  out->accept_len, out->next_token, out->commit, out->status,
+                  nucleus_on(call) ? ws.nuc : nullptr};
+    enqueue_deferred_sampling(sa, call->top_p, ws, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, cache->prefix_len}, s);
     return hip_ok(hipGetLastError(), "duo_verify_deferred launch");
 }
 
@@ -580,8 +607,9 @@ int duo_deferred_sample(const float* logits, const float* root_logits, int vocab
     DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     SampleArgs sa{logits, vocab, root_logits, vocab, 1, call->k, R, call->host_prefix_len, (double)call->temperature,
                   unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
-                  out->commit, out->status};
-    enqueue_deferred_sampling(sa, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, nullptr}, s);
+                  out->commit, out->status,
+                  nucleus_on(call) ? ws.nuc : nullptr};
+    enqueue_deferred_sampling(sa, call->top_p, ws, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, nullptr}, s);
     return hip_ok(hipGetLastError(), "duo_deferred_sample launch");
 }
 

@@ -17,10 +17,11 @@ def B():
     return binding
 
 
-def _oracle_outcome(x, x_tilde, judge_logits, p_n_logits, q_unv, u_unv, first_tok, first_q, u_first, r_final, T):
+def _oracle_outcome(x, x_tilde, judge_logits, p_n_logits, q_unv, u_unv, first_tok, first_q, u_first, r_final, T,
+                    top_p=0.0):
     """duodec_verify_alg2 on fp32 logits; returns (x_new, x_tilde_new)."""
-    p_unv = [O.target_probs(judge_logits[m], T) for m in range(len(x_tilde))]
-    p_n = O.target_probs(p_n_logits, T)
+    p_unv = [O.target_probs(judge_logits[m], T, top_p) for m in range(len(x_tilde))]
+    p_n = O.target_probs(p_n_logits, T, top_p)
     xhat = [[int(t)] for t in first_tok]  # only the first token of a new sequence matters to the verifier
     return O.duodec_verify_alg2(list(x) + list(x_tilde), list(x_tilde), [q.astype(np.float64) for q in q_unv], p_unv, p_n,
                                 xhat, [q.astype(np.float64) for q in first_q], [float(u) for u in u_unv],
@@ -117,6 +118,26 @@ def test_deferred_sampler_greedy_limit(B, V, l, s, variant):
         assert got["accept_len"] == l and got["selected"] == 1
     else:
         assert got["accept_len"] == l and got["selected"] == -1 and got["next_token"] == best_next
+
+
+@pytest.mark.parametrize("V,l,s", [(4099, 5, 3), (32000, 8, 2), (50, 3, 0)])
+@pytest.mark.parametrize("scenario", ["random", "accept_all", "second_new", "none_new", "argmax"])
+def test_deferred_sampler_with_top_p(B, V, l, s, scenario):
+    """Nucleus restriction in the deferred form, both sides on the same logits."""
+    top_p = 0.8
+    root, logits, q, toks, u, fq, ftoks, fu = _case(V, l, s, 4, scenario, peaked=(scenario == "argmax"))
+    say(f"deferred sampler top_p V={V} l={l} s={s} scenario={scenario}")
+    judge = [root] + [logits[m] for m in range(l - 1)]
+    margin = min(O.nucleus(O.target_probs(r, 1.0), top_p)[1] for r in judge + [logits[l - 1]])
+    x = [1, 2, 3]
+    ref = _oracle_outcome(x, toks.tolist(), judge, logits[l - 1], q, u[:l], ftoks, fq, fu, u[l], 1.0, top_p)
+    got = B.deferred_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u),
+                            to_dev(ftoks) if s else None, to_dev(fq) if s else None, to_dev(fu) if s else None,
+                            temperature=1.0, has_root=False, prefix_len=3, top_p=top_p)
+    assert got["status"] == 0
+    out = _gpu_outcome(x, toks.tolist(), got, ftoks)
+    if margin > 1e-12:
+        assert out[0] == ref[0], (out, ref, got)
 
 
 def test_deferred_sampler_flags_out_of_range_first_token(B):

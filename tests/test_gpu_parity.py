@@ -122,6 +122,59 @@ def test_sampler_greedy_limit_bit_exact(B, V, n, k, has_root, mode):
                (ref.selected, ref.commit_len, ref.commit_token, ref.new_prefix_len)
 
 
+def _nucleus_margin(logits, root, has_root, n, k, T, top_p):
+    """Smallest distance of a running mass from the nucleus cut over all judging rows (see oracle.nucleus)."""
+    rows = [logits[0] if has_root else root] + [logits[(1 if has_root else 0) + r] for r in range(n * k)]
+    return min(O.nucleus(O.target_probs(r, T), top_p)[1] for r in rows)
+
+
+@pytest.mark.parametrize("V,n,k,has_root,peaked", [(32000, 1, 8, False, False), (32000, 4, 8, True, True), (4099, 3, 5, False, True),
+                                                    (128256, 2, 16, False, True), (50, 2, 3, True, False)])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("top_p", [0.9, 0.35])
+def test_sampler_top_p_bit_exact_on_identical_logits(B, V, n, k, has_root, peaked, mode, top_p):
+    """Nucleus restriction of the target distributions on both sides; decisions whose margin (accept test, draw,
+    or the running mass at the nucleus cut) is within rounding of a tie are not compared."""
+    total = ties = 0
+    for seed in range(3):
+        T = 0.8 if seed == 1 else 1.0
+        say(f"top-p sampler V={V} n={n} k={k} root={has_root} peaked={peaked} mode={mode} top_p={top_p} seed={seed}")
+        logits, root, q, toks, u = _sampling_case(V, n, k, seed, has_root, peaked)
+        if seed == 2:  # several equal logits around the cut of the first rows: the ascending-id rule decides
+            for r in range(min(3, logits.shape[0])):
+                order = np.argsort(-logits[r])
+                full = O.target_probs(logits[r], T)
+                m = int(np.searchsorted(np.cumsum(full[order]), top_p))
+                grp = order[max(0, m - 2):m + 3]
+                logits[r, grp] = logits[r, order[m]]
+        ref = O.speculative_verify(logits, root, toks, q, u, prefix_len=100, temperature=T, select_mode=mode,
+                                   has_root=has_root, top_p=top_p)
+        got = B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u), temperature=T,
+                            select_mode=mode, has_root=has_root, prefix_len=100, top_p=top_p)
+        assert got["status"] == 0
+        total += 1
+        if (_nucleus_margin(logits, root, has_root, n, k, T, top_p) <= 1e-12 or ref.commit_margin <= 1e-9 or
+                (mode == 0 and min(ref.accept_margins.min(), ref.draw_margins.min()) <= 1e-9)):
+            ties += 1
+            continue
+        np.testing.assert_array_equal(got["accept_len"], ref.accept_len)
+        np.testing.assert_array_equal(got["next_token"], ref.next_token)
+        assert (got["selected"], got["commit_len"], got["commit_token"], got["new_prefix_len"]) == \
+               (ref.selected, ref.commit_len, ref.commit_token, ref.new_prefix_len)
+    assert ties < total
+
+
+def test_top_p_switched_off_values_change_nothing(B):
+    logits, root, q, toks, u = _sampling_case(4099, 2, 4, 1, False, True)
+    base = B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u))
+    for off in (1.0, 2.0, -0.5):
+        got = B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u), top_p=off)
+        assert got["commit_token"] == base["commit_token"] and got["commit_len"] == base["commit_len"]
+        np.testing.assert_array_equal(got["next_token"], base["next_token"])
+    with pytest.raises(B.DuoError):
+        B.spec_sample(to_dev(logits), to_dev(root), to_dev(toks), to_dev(q), to_dev(u), top_p=float("nan"))
+
+
 def test_negative_temperature_is_rejected(B):
     logits, root, q, toks, u = _sampling_case(50, 1, 2, 0, False, False)
     with pytest.raises(B.DuoError):
@@ -328,6 +381,39 @@ def test_other_width_single_layer(B, n, k, root):
     got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n + k, mode=0, root_token=root)
     if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
         _check_cache(eng, cache, cache.prefix_len)
+
+
+@pytest.mark.parametrize("mode,root,top_p", [(0, -1, 0.8), (1, 12, 0.5), (0, 3, 0.95)])
+def test_mid_config_top_p_step(B, mode, root, top_p):
+    """A whole step with nucleus sampling: logits against the oracle's forward pass, decisions against the oracle's
+    sampler applied to the logits the GPU returned (the nucleus of slightly different logits can differ)."""
+    import torch
+    shape = inputs.MID
+    n, k = 3, 5
+    say(f"MID top-p step mode={mode} root={root} top_p={top_p}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False)
+    q, toks, u = inputs.make_draft(shape.vocab, n, k, seed=6, easy_rows=inputs.easy_rows_for(n, k))
+    R = 1 if root >= 0 else 0
+    lg = torch.empty((R + n * k, shape.vocab), dtype=torch.float32, device="cuda")
+    eng.verify(to_dev(toks), to_dev(q), to_dev(u), temperature=0.9, select_mode=mode, root_token=root, logits_out=lg,
+               top_p=top_p)
+    got = eng.results(n)
+    assert got["status"] == 0
+    gl = lg.cpu().numpy()
+    ol = O.verify_forward(oshape, w, cache, toks, root).astype(np.float32)
+    ok, max_abs, worst = logits_close(gl, ol)
+    assert ok, (max_abs, worst)
+    groot = eng.root_logits.cpu().numpy()
+    ref = O.speculative_verify(gl, groot, toks, q, u, prefix_len=77, temperature=0.9, select_mode=mode, has_root=bool(R),
+                               top_p=top_p)
+    say(f"  gpu accept {got['accept_len']} commit {got['selected']}/{got['commit_len']}/{got['commit_token']}")
+    if (_nucleus_margin(gl, groot, bool(R), n, k, 0.9, top_p) <= 1e-12 or ref.commit_margin <= 1e-9 or
+            (mode == 0 and min(ref.accept_margins.min(), ref.draw_margins.min()) <= 1e-9)):
+        pytest.skip("a decision within rounding of a tie")
+    np.testing.assert_array_equal(got["accept_len"], ref.accept_len)
+    np.testing.assert_array_equal(got["next_token"], ref.next_token)
+    assert (got["selected"], got["commit_len"], got["commit_token"], got["new_prefix_len"]) == \
+           (ref.selected, ref.commit_len, ref.commit_token, ref.new_prefix_len)
 
 
 def test_cache_filled_to_the_last_slot(B):
