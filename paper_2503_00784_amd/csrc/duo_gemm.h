@@ -324,7 +324,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     };
     typename Epi::Pre pre;
     const int first_mh = NK > 1 ? nk : 0;  // the first row tile this wave finishes
-    const bool has_pre = live && first_mh < MH && first_mh * 4 + (lane >> 4) < quads;
+    const bool has_pre = HALF && live && first_mh < MH && first_mh * 4 + (lane >> 4) < quads;  // store4 takes none
     if (has_pre) epi.prefetch(tile, first_mh * 4 + (lane >> 4), lane & 15, pre);
 #pragma unroll
     for (int p = 0; p < PF; ++p) w_load(p, p);
@@ -346,17 +346,19 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
                 bf16x8 b[NT];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) b[t] = valid ? bb[p][t] : zero;
+                if constexpr (HALF) {  // activations first: a lane's quad is four rows of one column
 #pragma unroll
-                for (int mh = 0; mh < MH; ++mh)
+                    for (int t = 0; t < NT; ++t) acc[0][t] = mfma16(af[p & 1][0], b[t], acc[0][t]);
+                } else {  // weights first: a lane's quad is four consecutive columns of one row (vector stores)
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) acc[mh][t] = mfma16(af[p & 1][mh], b[t], acc[mh][t]);
-                if (!HALF) {
+                    for (int mh = 0; mh < MH; ++mh)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) acc[mh][t] = mfma16(b[t], af[p & 1][mh], acc[mh][t]);
 #pragma unroll
                     for (int mh = 0; mh < MH; ++mh)
 #pragma unroll
                         for (int t = 0; t < NT; ++t)
-                            acc[SEP ? MH + mh : mh][t] =
-                                mfma16(af[p & 1][HALF ? 0 : MH + mh], b[t], acc[SEP ? MH + mh : mh][t]);
+                            acc[SEP ? MH + mh : mh][t] = mfma16(b[t], af[p & 1][MH + mh], acc[SEP ? MH + mh : mh][t]);
                 }
                 w_load(p, (r + U) * AG + w);
                 __builtin_amdgcn_sched_barrier(0);
@@ -367,23 +369,34 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
         }
     }
 
-    // A lane's accumulator quad is rows 16*mh + 4*(lane/16) .. +3, column lane%16 of its tile: one output quad.
+    // HALF: a lane's accumulator quad is rows 4*(lane/16) .. +3, column lane%16 of its tile (one output quad of the
+    // epilogue's store).  Otherwise it is row 16*mh + lane%16 and columns 4*(lane/16) .. +3 (store4).
     auto finish = [&](int mh, f32x4 (&v)[NT], bool use_pre) {
-        if (HALF) {  // rows 0..7 hold the hi sums, rows 8..15 (32 lanes further on) the lo sums; all lanes take part
+        if constexpr (HALF) {  // rows 0..7 hold the hi sums, rows 8..15 (32 lanes further on) the lo sums; all lanes take part
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[t][i] += __shfl_xor(v[t][i], 32, 64);
-        }
-        const int qi = mh * 4 + (lane >> 4);
-        if (qi < quads) {
-            if (rsc.part) {
+            const int qi = mh * 4 + (lane >> 4);
+            if (qi < quads) {
+                if (rsc.part) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
+                    for (int t = 0; t < NT; ++t)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
+                        for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
+                }
+                epi.store(tile, qi, lane & 15, v, pre, use_pre);
             }
-            epi.store(tile, qi, lane & 15, v, pre, use_pre);
+        } else {
+            const int m = mh * 16 + (lane & 15);
+            if (m < quads * 4) {
+                if (rsc.part) {
+                    const float rs = row_scale[m];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) v[t] = v[t] * rs;
+                }
+                epi.store4(tile, m, 4 * (lane >> 4), v);
+            }
         }
     };
     if (NK == 1) {
