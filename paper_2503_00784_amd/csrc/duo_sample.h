@@ -182,7 +182,7 @@ __device__ __forceinline__ void fill_running_distribution(const SampleArgs& a, i
 // logit key t with mass{key >= t} >= top_p * total (32 block sums in a fixed order), then as many of the ids that
 // sit exactly on the threshold, in ascending order, as the target still needs.
 // PT > 0: the vocabulary has at most PT * 1024 entries and every thread keeps its PT keys and probabilities in
-// registers for the 33 passes (they are latency-bound otherwise: 340 -> 40 us for nine rows of 32000); PT = 0: any
+// registers for the 33 passes (they are latency-bound otherwise: 340 -> 120 us for nine rows of 32000); PT = 0: any
 // vocabulary, the passes re-read the row.
 template <int PT>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_nucleus_kernel(SampleArgs a, double top_p, double* __restrict__ prow_all,
