@@ -179,15 +179,15 @@ void launch_attention(int mtw, int nwv, dim3 grid, const AttnArgs& a, hipStream_
 // A projection whose epilogue finishes the rows (QKV, gate/up, LM head).  Up to eight rows every wave streams
 // its own bands and reads the activations itself; beyond that the waves of a workgroup share the activation
 // operand through LDS.
+// `cls`: the kernel class of the per-kernel timer.
 template <int NT, class Epi>
-void launch_projection(int M, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
+void launch_projection(int cls, int M, const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
                        hipStream_t s) {
     if (M > DUO_MAX_ROWS) {  // prefill pass: both operands staged in LDS; wider blocks once they still fill the chip
-        const int bands = tiles * NT, mh = pair_rows_for(M) / 16;
-        if (((bands + 15) / 16) * ((mh + 7) / 8) >= 160) launch_block<4, 8, NT>(X, W, K, bands, M, 1, rsc, epi, s);
-        else launch_block<4, 4, NT>(X, W, K, bands, M, 1, rsc, epi, s);
+        launch_block_rows<NT>(X, W, K, tiles * NT, M, rsc, epi, s, [&]() { prof(cls, s); });
         return;
     }
+    prof(cls, s);
     if (M <= 8) {
         if (!launch_wide_half<NT>(X, W, K, tiles, rsc, epi, s)) launch_gemm_rows<NT>(M, true, X, W, K, tiles, rsc, epi, s);
         return;
@@ -327,8 +327,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * c.max_seq * D;
         EpiQKV eq{Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
-        prof(DUO_PROF_QKV, s);
-        launch_projection<2>(M, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), (l == 0 || down_split) ? norm_full : norm_part,
+        launch_projection<2>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), (l == 0 || down_split) ? norm_full : norm_part,
                              eq, s);
 
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
@@ -357,23 +356,22 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         launch_residual_projection(M, ws.attn, w.wo[l], qd, eo, ws.split, ws.ssq_full, DUO_PROF_OPROJ, s);
 
         EpiSwiGLU eg{F, M, ws.act, AT, PR};
-        prof(DUO_PROF_GATEUP, s);
-        launch_projection<2>(M, ws.h, w.w_gate_up[l], d, F / 16, o_split ? norm_full : norm_part, eg, s);
+        launch_projection<2>(DUO_PROF_GATEUP, M, ws.h, w.w_gate_up[l], d, F / 16, o_split ? norm_full : norm_part, eg, s);
 
         const u16* gnext = l + 1 < c.n_layers ? w.g_attn[l + 1] : w.g_final;
         EpiResidual ed{d, M, ws.x, d, gnext, ws.h, PR, AT, ws.ssq};
         launch_residual_projection(M, ws.act, w.w_down[l], F, ed, ws.split, ws.ssq_full, DUO_PROF_DOWN, s);
     }
-    prof(DUO_PROF_LMHEAD, s);
     if (many) {
+        prof(DUO_PROF_LMHEAD, s);
         DUO_LAUNCH(last_row_operand_kernel, dim3(d / 32), dim3(64), s, ws.h, M - 1, PR, AT, ws.h_last);
         const RowScale last{ws.ssq + (size_t)(M - 1) * NP, NP, 1.0f / (float)d, c.rms_eps, down_split ? ws.ssq_full + (M - 1) : nullptr};
         EpiStoreF32 el{V, 1, 2, logits, V};
-        launch_projection<2>(1, ws.h_last, w.lm_head, d, (V + 31) / 32, last, el, s);
+        launch_projection<2>(DUO_PROF_LMHEAD, 1, ws.h_last, w.lm_head, d, (V + 31) / 32, last, el, s);
         return;
     }
     EpiStoreF32 el{V, M, 2, logits, V};
-    launch_projection<2>(M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
+    launch_projection<2>(DUO_PROF_LMHEAD, M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
 }
 
 // Nucleus sampling is on for 0 < top_p < 1 at a positive temperature (at temperature 0 the distribution is one-hot).
@@ -398,10 +396,12 @@ void enqueue_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, in
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST) {
         // one sequence: nothing to choose and nothing to move, the finish kernel writes the commit itself
         const bool self_commit = sa.n == 1;
-        DUO_LAUNCH(sample_finish_kernel, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
+        if (sa.nuc) DUO_LAUNCH(sample_finish_kernel<true>, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
+        else DUO_LAUNCH(sample_finish_kernel<false>, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
         if (self_commit) return;
     } else {
-        DUO_LAUNCH(sample_paper_kernel, dim3(1), dim3(SAMPLE_THREADS), s, sa);
+        if (sa.nuc) DUO_LAUNCH(sample_paper_kernel<true>, dim3(1), dim3(SAMPLE_THREADS), s, sa);
+        else DUO_LAUNCH(sample_paper_kernel<false>, dim3(1), dim3(SAMPLE_THREADS), s, sa);
     }
     CommitArgs ca{kc, vc, c ? c->n_kv_heads : 1, c ? c->head_dim : 0, c ? c->max_seq : 0, sa.P, sa.R, sa.n, sa.k, mode,
                   sa.accept_len, sa.next_token, sa.commit, prefix_len};
@@ -548,7 +548,8 @@ static void enqueue_deferred_sampling(const SampleArgs& sa, float top_p, const W
     DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, 1, STATS_SPLIT), dim3(256), s, sa);
     enqueue_nucleus(sa, top_p, ws, s);
     prof(DUO_PROF_SAMPLE, s);
-    DUO_LAUNCH(sample_deferred_kernel, dim3(1), dim3(SAMPLE_THREADS), s, sa, da);
+    if (sa.nuc) DUO_LAUNCH(sample_deferred_kernel<true>, dim3(1), dim3(SAMPLE_THREADS), s, sa, da);
+    else DUO_LAUNCH(sample_deferred_kernel<false>, dim3(1), dim3(SAMPLE_THREADS), s, sa, da);
 }
 
 int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* cache,

@@ -22,7 +22,7 @@
 
 template <int WM, int WN, int KS, int ENT, class Epi>
 __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__ X, const u16* __restrict__ W, int K,
-                                                         int split_steps, int nbands, int mh_total, int quads, RowScale rsc,
+                                                         int split_steps, int band_base, int nbands, int mh_total, int quads, RowScale rsc,
                                                          Epi epi) {
     constexpr int BMT = 2 * WM, BNT = 2 * WN;  // row tiles (hi) and bands per workgroup
     constexpr int PER = 2 * BMT + BNT;         // tiles per K step
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__
     const int k0 = blockIdx.y * split_steps;
     const int ns = min(steps - k0, split_steps);  // K steps of this split (the host makes it positive)
     const int rounds = (ns + KS - 1) / KS;
-    const int row_tile0 = blockIdx.z * BMT, band0 = blockIdx.x * BNT;
+    const int row_tile0 = blockIdx.z * BMT, band0 = band_base + blockIdx.x * BNT;  // bands [band_base, nbands) are this launch's
     const int row0 = row_tile0 * 16, nrows = quads * 4;
 
     // RMSNorm factors of this block's rows (all five waves)
@@ -158,19 +158,54 @@ __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__
     }
 }
 
-// Launch for M rows (operand of 2 * mh_total row tiles: hi tiles, then lo tiles), `nbands` bands of 16 columns,
-// K split `splits` ways over the grid's y dimension (returns the number of splits actually used).
+// Launch for M rows (operand of 2 * mh_total row tiles: hi tiles, then lo tiles) over the bands [band_begin, band_end) of
+// 16 columns each, K split `splits` ways over the grid's y dimension (returns the number of splits actually used).
 template <int WM, int WN, int ENT, class Epi>
-static inline int launch_block(const u16* X, const u16* W, int K, int nbands, int M, int splits, const RowScale& rsc,
-                               const Epi& epi, hipStream_t s) {
+static inline int launch_block_range(const u16* X, const u16* W, int K, int band_begin, int band_end, int M, int splits,
+                                     const RowScale& rsc, const Epi& epi, hipStream_t s) {
     constexpr int KS = (2 * (4 * WM + 2 * WN) <= 48) ? 2 : 1;  // stage of at most 48 KiB
     const int mh_total = pair_rows_for(M) / 16, quads = pair_rows_for(M) / 4;
     const int steps = K >> 5;
     int split_steps = (steps + splits - 1) / splits;
     split_steps = (split_steps + KS - 1) / KS * KS;
     const int S = (steps + split_steps - 1) / split_steps;
-    const dim3 grid((nbands + 2 * WN - 1) / (2 * WN), S, (mh_total + 2 * WM - 1) / (2 * WM));
-    DUO_LAUNCH((gemm_block_kernel<WM, WN, KS, ENT, Epi>), grid, dim3(320), s, X, W, K, split_steps, nbands, mh_total, quads, rsc,
-               epi);
+    const dim3 grid((band_end - band_begin + 2 * WN - 1) / (2 * WN), S, (mh_total + 2 * WM - 1) / (2 * WM));
+    DUO_LAUNCH((gemm_block_kernel<WM, WN, KS, ENT, Epi>), grid, dim3(320), s, X, W, K, split_steps, band_begin, band_end, mh_total,
+               quads, rsc, epi);
     return S;
+}
+template <int WM, int WN, int ENT, class Epi>
+static inline int launch_block(const u16* X, const u16* W, int K, int nbands, int M, int splits, const RowScale& rsc,
+                               const Epi& epi, hipStream_t s) {
+    return launch_block_range<WM, WN, ENT>(X, W, K, 0, nbands, M, splits, rsc, epi, s);
+}
+
+// A projection whose epilogue finishes the rows (no K split), for M > 80 rows.  Workgroups of 64 x 128 wave tiles are the
+// faster ones but come in few, large units: when their count leaves the last round of workgroups (one per compute unit)
+// mostly empty, the bands of that round are given to workgroups of 64 x 64 wave tiles instead, in a second launch.
+// Cost model in rounds of the large tile: a round of small tiles takes 0.55 of one.
+// `before_launch` is called in front of every launch (the caller's per-kernel timer).
+template <int ENT, class Epi, class Hook>
+static inline void launch_block_rows(const u16* X, const u16* W, int K, int nbands, int M, const RowScale& rsc, const Epi& epi,
+                                     hipStream_t s, Hook before_launch) {
+    constexpr int CUS = 256;
+    const int rb = (pair_rows_for(M) / 16 + 7) / 8;  // row blocks (128 rows)
+    const int n_large = (nbands + 15) / 16, n_small = (nbands + 7) / 8;
+    const auto rounds = [](int wgs) { return (wgs + CUS - 1) / CUS; };
+    const float all_large = (float)rounds(n_large * rb), all_small = 0.55f * (float)rounds(n_small * rb);
+    const int full = (n_large * rb) / CUS;                    // full rounds of large workgroups
+    const int main_blocks = full * CUS / rb;                  // whole band blocks (256 columns) inside them
+    const int rest_bands = nbands - main_blocks * 16;
+    const float mixed = (full > 0 && rest_bands > 0) ? (float)rounds(main_blocks * rb) + 0.55f * (float)rounds((rest_bands + 7) / 8 * rb)
+                                                      : 1e30f;
+    before_launch();
+    if (mixed < all_large && mixed < all_small) {
+        launch_block_range<4, 8, ENT>(X, W, K, 0, main_blocks * 16, M, 1, rsc, epi, s);
+        before_launch();
+        launch_block_range<4, 4, ENT>(X, W, K, main_blocks * 16, nbands, M, 1, rsc, epi, s);
+    } else if (all_large <= all_small && n_large * rb >= 160) {
+        launch_block_range<4, 8, ENT>(X, W, K, 0, nbands, M, 1, rsc, epi, s);
+    } else {
+        launch_block_range<4, 4, ENT>(X, W, K, 0, nbands, M, 1, rsc, epi, s);
+    }
 }

@@ -75,8 +75,10 @@ struct Nucleus {
         return !on ? p : (keeps(logit, v) ? p * inv : 0.0);
     }
 };
+// NUC = false: the kernels are compiled without the restriction (nothing of it is left in their loops)
+template <bool NUC>
 __device__ __forceinline__ Nucleus nucleus_of(const SampleArgs& a, int i, int j) {
-    if (!a.nuc) return Nucleus{false, 0u, 0, 1.0};
+    if (!NUC || !a.nuc) return Nucleus{false, 0u, 0, 1.0};
     const double* e = a.nuc + (size_t)a.nuc_row(i, j) * 4;
     return Nucleus{true, (uint32_t)e[0], (int)e[1], 1.0 / e[2]};
 }
@@ -162,6 +164,7 @@ __device__ __forceinline__ int merged_argmax(const SampleArgs& a, int i, int j) 
 }
 
 // p_run[v] = p(v) of judging distribution (i, j) for the whole vocabulary; ends with a barrier
+template <bool NUC>
 __device__ __forceinline__ void fill_running_distribution(const SampleArgs& a, int i, int j) {
     const float* row = a.judge_row(i, j);
     if (a.greedy()) {
@@ -170,7 +173,7 @@ __device__ __forceinline__ void fill_running_distribution(const SampleArgs& a, i
     } else {
         double zmax, Z;
         merged_stats(a, i, j, zmax, Z);
-        const Nucleus nc = nucleus_of(a, i, j);
+        const Nucleus nc = nucleus_of<NUC>(a, i, j);
         for (int v = threadIdx.x; v < a.V; v += blockDim.x)
             a.p_run[v] = nc.apply(exp((double)row[v] / a.T - zmax) / Z, row[v], v);
     }
@@ -287,6 +290,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_nucleus_kernel(SampleAr
 }
 
 // accept flags of sequence i, positions from..k-1 (one thread each), into acc[]; ends with a barrier
+template <bool NUC>
 __device__ __forceinline__ void accept_flags(const SampleArgs& a, int i, int from) {
     const int j = from + threadIdx.x;
     if (j < a.k) {
@@ -298,7 +302,7 @@ __device__ __forceinline__ void accept_flags(const SampleArgs& a, int i, int fro
         } else {
             double zmax, Z;
             merged_stats(a, i, j, zmax, Z);
-            p_t = nucleus_of(a, i, j).apply(exp((double)row[t] / a.T - zmax) / Z, row[t], t);
+            p_t = nucleus_of<NUC>(a, i, j).apply(exp((double)row[t] / a.T - zmax) / Z, row[t], t);
         }
         const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
         a.acc[i * a.k + j] = lhs < p_t ? 1 : 0;
@@ -393,6 +397,7 @@ __device__ int block_inverse_cdf(F w, int V, double u, double* sm_d, int* sm_i) 
 }
 
 // Correction / bonus token of sequence i after `a` accepted drafts.
+template <bool NUC>
 __device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_d, int* sm_i) {
     const float* row = a.judge_row(i, acc_len);
     if (a.greedy()) {  // one-hot p: same two draws over the one-hot weights
@@ -413,7 +418,7 @@ __device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_
     // bound by its double-precision arithmetic); the results differ from the quotients by an ulp at most
     const double iT = 1.0 / a.T, iZ = 1.0 / Z;
     const double u = (double)a.u[i * (a.k + 1) + a.k];
-    const Nucleus nc = nucleus_of(a, i, acc_len);
+    const Nucleus nc = nucleus_of<NUC>(a, i, acc_len);
     auto pw = [=](int v) { return nc.apply(exp((double)row[v] * iT - zmax) * iZ, row[v], v); };
     if (acc_len < a.k) {
         const float* qrow = a.q + ((size_t)i * a.k + acc_len) * a.V;
@@ -432,13 +437,14 @@ __device__ __forceinline__ int leading_accepts(const SampleArgs& a, int i, int f
 
 // self_commit (single-sequence calls): also write the commit record and advance the device prefix length, which
 // otherwise commit_kernel does after choosing among the sequences.
+template <bool NUC>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArgs a, int self_commit, int32_t* prefix_len) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
     const int i = blockIdx.x;
-    accept_flags(a, i, 0);
+    accept_flags<NUC>(a, i, 0);
     const int acc_len = leading_accepts(a, i, 0);
-    const int tok = finish_token(a, i, acc_len, sm_d, sm_i);
+    const int tok = finish_token<NUC>(a, i, acc_len, sm_d, sm_i);
     if (threadIdx.x == 0) {
         a.accept_len[i] = acc_len;
         a.next_token[i] = tok;
@@ -477,11 +483,12 @@ __device__ int sequential_first_tokens(double* p_run, int V, int s, const int32_
     return -1;
 }
 
+template <bool NUC>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs a) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
     const int tid = threadIdx.x;
-    fill_running_distribution(a, 0, 0);
+    fill_running_distribution<NUC>(a, 0, 0);
     const int sel = sequential_first_tokens(a.p_run, a.V, a.n, a.tokens, a.k, a.q, (size_t)a.k * a.V, a.u, a.k + 1, sm_d);
     int acc_len = 0, tok;
     if (sel < 0) {
@@ -489,9 +496,9 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
         auto pw = [=](int v) { return pr[v]; };
         tok = block_inverse_cdf(pw, a.V, (double)a.u[(a.n - 1) * (a.k + 1) + a.k], sm_d, sm_i);
     } else {
-        accept_flags(a, sel, 1);
+        accept_flags<NUC>(a, sel, 1);
         acc_len = leading_accepts(a, sel, 1);
-        tok = finish_token(a, sel, acc_len, sm_d, sm_i);
+        tok = finish_token<NUC>(a, sel, acc_len, sm_d, sm_i);
     }
     for (int i = tid; i < a.n; i += SAMPLE_THREADS) {
         a.accept_len[i] = sel < 0 ? 0 : (i < sel ? 0 : (i == sel ? acc_len : -1));
@@ -515,6 +522,7 @@ struct DeferredArgs {
     int32_t* prefix_len;  // device prefix length to advance, may be NULL (sampling only)
 };
 
+template <bool NUC>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleArgs a, DeferredArgs d) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
@@ -523,13 +531,13 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleA
         const int t = d.first_tokens[tid];
         if (t < 0 || t >= a.V) atomicOr(a.status, 1);
     }
-    accept_flags(a, 0, 0);
+    accept_flags<NUC>(a, 0, 0);
     const int acc_len = leading_accepts(a, 0, 0);
     int sel = -1, tok = -1;
     if (acc_len < a.k) {
-        tok = finish_token(a, 0, acc_len, sm_d, sm_i);  // residual draw at the first rejection
+        tok = finish_token<NUC>(a, 0, acc_len, sm_d, sm_i);  // residual draw at the first rejection
     } else {
-        fill_running_distribution(a, 0, a.k);  // the distribution after the last scored token
+        fill_running_distribution<NUC>(a, 0, a.k);  // the distribution after the last scored token
         sel = sequential_first_tokens(a.p_run, a.V, d.s, d.first_tokens, 1, d.first_probs, (size_t)a.V, d.uniforms_first, 1,
                                       sm_d);
         if (sel < 0) {
