@@ -205,13 +205,15 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 // through LDS, each taking its own group of NT weight bands (every weight byte still goes from HBM straight
 // into one wave's registers, PF steps ahead); hi and lo products accumulate into the same registers (for few
 // tiles into separate ones, so that dependent MFMAs on one accumulator have others in between), and the
-// epilogue runs straight from the accumulators: a lane's quad is an output quad.  The grid's y dimension
+// epilogue runs straight from the accumulators.  The weights are the FIRST MFMA operand here, so a lane's quad is
+// four consecutive columns of one output row and the epilogue stores vectors (store4).  The grid's y dimension
 // splits K across workgroups for matrices with few bands (partial results, see EpiStoreF32).  All loads of
 // the main loop are unconditional with clamped indices and invalid steps multiply by zero: no branches, so
 // the counted waits stay exact.
 //
 // With HALF the operand is the single tile of up to eight rows (hi rows 0..7, lo rows 8..15 of the same tile),
-// as the kernel above uses it; the two halves of the sums are then 32 lanes apart.
+// as the kernel above uses it, activations first (a lane's quad is four rows of one column); the two halves of the
+// sums are then 32 lanes apart.
 //
 // One extra wave per workgroup does nothing but move the activation operand:
 // wave NG copies the operand tiles of round r + 2 from global memory straight into a three-deep ring of
