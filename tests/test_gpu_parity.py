@@ -460,3 +460,33 @@ def test_full_size_shapes(B, name):
     say(f"{name}: verify n={n} k={k} P={P}")
     got, res, compared = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=1, mode=0, root_token=-1)
     say(f"  accept lengths compared away from ties: {compared}/{n}")
+
+
+def test_full_size_prefill_paths_agree(B):
+    """Llama-2-7B geometry, 1100 prompt tokens: the many-row pass (one chunk of 1024 rows and one of 76) against the
+    few-row pass (chunks of 80 rows) of the same library.  At this size the oracle would take an hour; each pass is
+    checked against it at small sizes above, here they must agree with each other: last-row logits within twice the
+    logit tolerance, cached keys and values within one bf16 rounding step of values of this size."""
+    import torch
+    shape = inputs.LLAMA2_7B
+    total = 1100
+    say("7B prefill: generating weights")
+    w = inputs.make_weights(shape, seed=0, threads=16)
+    dw = B.DeviceWeights(shape, w)
+    prompt = inputs.make_prefix_ids(shape, total, seed=3).tolist()
+    outs = []
+    for chunk in (1024, 80):
+        say(f"7B prefill in chunks of {chunk}")
+        eng = B.VerifyEngine(shape, None, 1152, weights=dw, max_prefill_rows=chunk)
+        eng.prefill(prompt, chunk=chunk)
+        torch.cuda.synchronize()
+        assert int(eng.prefix_len.item()) == total and int(eng.status.item()) == 0
+        kc, vc = eng.cache_to_host()
+        outs.append((eng.root_logits.cpu().numpy().copy(), O.bf16_bits_to_f64(kc[::8, :, :total]), O.bf16_bits_to_f64(vc[::8, :, :total])))
+        del eng
+    (la, ka, va), (lb, kb, vb) = outs
+    dl = np.abs(la - lb)
+    say(f"  last-row logits max abs diff {dl.max():.3e}; cache max abs diff k {np.abs(ka - kb).max():.3e} v {np.abs(va - vb).max():.3e}")
+    assert (dl <= 2 * (2e-2 + 1e-2 * np.abs(lb))).all()
+    assert np.abs(ka - kb).max() <= 0.07 and np.abs(va - vb).max() <= 0.07
+    assert np.abs(ka).max() > 0.5 and np.abs(la).max() > 0.5   # not comparing zeros
