@@ -514,10 +514,13 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     const int b0 = cb * a.blocks_per_wave;  // here: blocks per chunk
     int nb = NB - b0;
     nb = nb < 0 ? 0 : (nb > a.blocks_per_wave ? a.blocks_per_wave : nb);
+    // Row groups in reverse launch order: workgroups start in index order, and the late rows of a prompt chunk see the
+    // most keys, so the longest-running groups go first.
+    const int zg = (int)(gridDim.z - 1 - blockIdx.z);
     {
         // No row sees a key behind its own slot: the blocks behind the slot of this workgroup's last query row
         // are masked for all of its rows and are left out (a prompt chunk's early rows skip the chunk's late keys).
-        const int r_last = min(a.plan.M * a.group, (int)(blockIdx.z + 1) * NWV * MTW * 16) - 1;
+        const int r_last = min(a.plan.M * a.group, (zg + 1) * NWV * MTW * 16) - 1;
         const int nb_vis = (a.plan.P + r_last / a.group) / 32 + 1 - b0;
         nb = nb_vis < nb ? (nb_vis < 0 ? 0 : nb_vis) : nb;
     }
@@ -554,7 +557,7 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
 
     // ---- consumers
     const int MQ = a.plan.M * a.group;
-    const int tile0 = (blockIdx.z * NWV + wave) * MTW;  // first query tile of this wave
+    const int tile0 = (zg * NWV + wave) * MTW;  // first query tile of this wave
     bf16x8 qf[MTW][KS], ql[MTW][KS];
     int vis_lo[MTW], vis_hi[MTW];
 #pragma unroll
