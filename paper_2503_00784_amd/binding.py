@@ -266,13 +266,6 @@ class DeviceWeights:
             self._tables[key] = tab
             setattr(self.c, key, C.cast(tab, C.POINTER(C.c_void_p)))
 
-    def all_tensors(self):
-        """Every device tensor of the model (packed matrices, embedding, gains), in no particular order."""
-        out = []
-        for v in self.tensors.values():
-            out.extend(v if isinstance(v, list) else [v])
-        return out
-
 
 class VerifyEngine:
     """Owns the device buffers of one model instance (cache, workspace, results) and calls the C ABI."""
