@@ -183,3 +183,14 @@ def test_kv_cache_layout_formulas_agree_with_the_binding(D):
     assert torch.equal(B.v_tiles_to_rows(vt, D), rows)
     # every offset is hit exactly once
     assert sorted(kt.flatten().tolist()) == sorted(rows.flatten().tolist())
+
+
+def test_header_is_valid_c99_and_cxx():
+    """The boundary is a C ABI: the header must compile on its own as C and as C++."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "duo_verify.h")
+    if not shutil.which("gcc"):
+        pytest.skip("no gcc")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
