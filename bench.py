@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--draft-step-ms", type=float, default=0.0,
                     help="with --k-sweep: time of one draft-model step on the host; adds the cost coefficient c(k) and the "
                     "balanced draft budget gamma")
+    ap.add_argument("--dtype", choices=["bf16", "fp16"], default="bf16", help="16-bit type of the weights and the KV cache "
+                    "(bf16 is the configuration the metric is quoted on; fp16 is the paper's own precision)")
     ap.add_argument("--top-p", type=float, default=0.0, help="nucleus restriction of the target distributions in the timed step "
                     "(a variant; the headline number is quoted without it)")
     ap.add_argument("--prefill-tokens", type=int, default=0,
@@ -66,18 +68,18 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    if not os.path.exists(B.LIB_PATH):
+    if not os.path.exists(B.LIB_PATHS[args.dtype]):
         from paper_2503_00784_amd import build
         build.build(verbose=False)
-    B.load()
+    B.load(args.dtype)
 
     wl = inputs.WORKLOADS[args.workload]
     shape, P, n, k = wl.shape, wl.prefix_len, wl.n_seq, wl.k_draft
     max_seq = (max(P + n * k + 1, args.prefill_tokens) + 31) // 32 * 32 + 32
     t0 = time.time()
     log(f"[bench] workload {wl.name}: generating weights ({shape.weight_bytes() / 1e9:.2f} GB) ...")
-    w = inputs.make_weights(shape, seed=args.seed, threads=16)
-    kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=args.seed)
+    w = inputs.make_weights(shape, seed=args.seed, threads=16, dtype=args.dtype)
+    kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=args.seed, dtype=args.dtype)
     q, toks, u = inputs.make_draft(shape.vocab, n, k, seed=args.seed + 1, easy_rows=inputs.easy_rows_for(n, k))
     eng = B.VerifyEngine(shape, w, max_seq, max_prefill_rows=args.prefill_chunk if args.prefill_tokens > 0 else B.DUO_MAX_ROWS)
     eng.load_cache(kb, vb, P, root)
@@ -156,12 +158,12 @@ def main() -> int:
         del probe_buf
 
         # per-kernel timing pass (eager launches with HIP events between kernels on the same stream)
-        B.profile_enable(True)
+        B.profile_enable(True, args.dtype)
         prof_steps = min(args.steps, 20)
         for _ in range(prof_steps):
             step()
-        prof = B.profile_read()
-        B.profile_enable(False)
+        prof = B.profile_read(args.dtype)
+        B.profile_enable(False, args.dtype)
         stream.synchronize()
 
     algo_bytes = wl.algorithmic_bytes()
@@ -190,7 +192,7 @@ def main() -> int:
 
     out = {"metric": "verified_tokens_per_s", "value": round(tok_s, 1), "unit": "tok/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
            "config": {"workload": wl.name, "prefix_len": P, "n_seq": n, "k_draft": k, "rows": n * k,
                       "launch": "hip_graph_replay" if graph is not None else "eager",
                       **({"top_p": args.top_p} if 0.0 < args.top_p < 1.0 else {})},
@@ -246,11 +248,11 @@ def main() -> int:
                 eng.prefill(prompt, chunk=args.prefill_chunk)
                 stream.synchronize()
                 times.append(time.perf_counter() - t6)
-            B.profile_enable(True)  # one more pass with per-kernel events
+            B.profile_enable(True, args.dtype)  # one more pass with per-kernel events
             eng.set_prefix_len(0)
             eng.prefill(prompt, chunk=args.prefill_chunk)
-            pprof = B.profile_read()
-            B.profile_enable(False)
+            pprof = B.profile_read(args.dtype)
+            B.profile_enable(False, args.dtype)
             stream.synchronize()
         best = min(times)
         out["prefill"] = {"tokens": args.prefill_tokens, "chunk": args.prefill_chunk, "ms": round(best * 1e3, 3),

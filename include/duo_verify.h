@@ -16,7 +16,10 @@
  *   - All work is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = default
  *     stream) without host synchronisation.  Arguments are validated on the host before
  *     anything is enqueued; a negative return code means nothing was enqueued.
- *   - bf16 values are passed as uint16_t bit patterns.  Matrices compute y = x W^T, are 16-byte
+ *   - 16-bit values (weights, gains, embedding, KV cache) are passed as uint16_t bit patterns.  The library is
+ *     built twice from the same sources with the same entry points: libduo_verify.so takes them as bf16
+ *     (wherever this header says bf16), libduo_verify_fp16.so as IEEE fp16, the precision the paper ran its
+ *     target model in (Sec. 4.1).  A process may load both.  Matrices compute y = x W^T, are 16-byte
  *     aligned, and have an input dimension that is a multiple of 32.
  *   - A call with the same inputs and the same `host_prefix_len` is repeatable: cache slots
  *     below the prefix length are only read, slots at and above it are scratch.

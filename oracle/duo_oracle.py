@@ -43,10 +43,19 @@ MODE_INDEPENDENT_LONGEST = 0
 MODE_PAPER_SEQUENTIAL = 1
 
 
-# ----------------------------------------------------------------------------- bf16
+# ----------------------------------------------------------------------------- 16-bit storage types
+# Parameters and cache entries arrive either as bf16 bit patterns (uint16 arrays: this build's default contract) or
+# as numpy float16 arrays (IEEE fp16, the format of the paper's runs, Sec. 4.1); the array's dtype says which.
 def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
-    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    """Exact widening of 16-bit storage to float64: bf16 bit patterns (uint16) or float16 values."""
+    if bits.dtype == np.float16:
+        return bits.astype(np.float64)
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def round_to_fp16(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to the IEEE fp16 grid, result kept as float64."""
+    return np.asarray(x, dtype=np.float64).astype(np.float16).astype(np.float64)
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -146,13 +155,21 @@ class OracleCache:
 
 def _w(weights: Dict[str, object], name: str, layer: Optional[int] = None) -> np.ndarray:
     a = weights[name] if layer is None else weights[name][layer]
-    return bf16_bits_to_f64(a) if a.dtype == np.uint16 else np.asarray(a, dtype=np.float64)
+    return bf16_bits_to_f64(a) if a.dtype in (np.uint16, np.float16) else np.asarray(a, dtype=np.float64)
+
+
+def _storage_rounding(weights: Dict[str, object], rounding: str):
+    """The rounding applied where the 16-bit type is a storage format (the KV cache write): that of the parameters'
+    own type under the contract, none in `ideal` mode."""
+    if rounding != "contract":
+        return _identity
+    return round_to_fp16 if np.asarray(weights["embed"]).dtype == np.float16 else round_to_bf16
 
 
 def embed_rows(weights: Dict[str, object], tokens: Sequence[int]) -> np.ndarray:
     """x_r = E[token_r] as float64 [len(tokens), d]."""
     e = weights["embed"][np.asarray(tokens, dtype=np.int64)]
-    return bf16_bits_to_f64(e) if e.dtype == np.uint16 else np.asarray(e, dtype=np.float64)
+    return bf16_bits_to_f64(e) if e.dtype in (np.uint16, np.float16) else np.asarray(e, dtype=np.float64)
 
 
 def row_plan(prefix_len: int, n_seq: int, k_draft: int, has_root: bool
@@ -182,7 +199,7 @@ def verify_forward(shape: OracleShape, weights: Dict[str, object], cache: Oracle
     Writes the K/V of every row into its cache slot (scratch region beyond prefix_len).
     Row r's logits are the target's next-token scores after that row's token.
     """
-    rnd = round_to_bf16 if rounding == "contract" else _identity
+    rnd = _storage_rounding(weights, rounding)
     draft_tokens = np.asarray(draft_tokens)
     n_seq, k_draft = draft_tokens.shape
     has_root = root_token >= 0
@@ -244,7 +261,7 @@ def full_forward_uncached(shape: OracleShape, weights: Dict[str, object], tokens
     Independent of `verify_forward` on purpose (matrix form, explicit triangular mask): it is
     the brute-force pin for the cached, row-by-row pass.
     """
-    rnd = round_to_bf16 if rounding == "contract" else _identity
+    rnd = _storage_rounding(weights, rounding)
     T = len(tokens)
     Hq, Hkv, D = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
     x = embed_rows(weights, tokens)

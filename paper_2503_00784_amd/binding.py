@@ -13,7 +13,9 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libduo_verify.so")
+LIB_PATH = os.path.join(_HERE, "libduo_verify.so")            # bf16 weights and KV cache
+LIB_PATH_FP16 = os.path.join(_HERE, "libduo_verify_fp16.so")  # the same sources built for IEEE fp16
+LIB_PATHS = {"bf16": LIB_PATH, "fp16": LIB_PATH_FP16}
 
 DUO_MAX_ROWS = 80
 DUO_MAX_PREFILL_ROWS = 1024
@@ -65,18 +67,23 @@ class DuoError(RuntimeError):
         super().__init__(f"{where}: {detail} (code {code})")
 
 
-_lib = None
+_libs: Dict[str, C.CDLL] = {}
 
 
-def load() -> C.CDLL:
-    """Load the shared library (once).  Raises if it has not been built."""
-    global _lib
-    if _lib is not None:
-        return _lib
-    if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_00784_amd.build` "
+def dtype_of(host_array) -> str:
+    """Element type of a host array of 16-bit parameters: numpy float16 arrays are fp16, uint16 arrays bf16 bit patterns."""
+    return "fp16" if np.asarray(host_array).dtype == np.float16 else "bf16"
+
+
+def load(dtype: str = "bf16") -> C.CDLL:
+    """Load the shared library of one element type (once).  Raises if it has not been built."""
+    if dtype in _libs:
+        return _libs[dtype]
+    path = LIB_PATHS[dtype]
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2503_00784_amd.build` "
                            "(there is no CPU fallback)")
-    lib = C.CDLL(LIB_PATH)
+    lib = C.CDLL(path)
     lib.duo_workspace_bytes.argtypes = [C.POINTER(ModelConfig), C.c_int, C.POINTER(C.c_size_t)]
     lib.duo_verify.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(KVCache), C.c_void_p, C.c_void_p,
                                C.c_void_p, C.POINTER(Call), C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -116,7 +123,7 @@ def load() -> C.CDLL:
     lib.duo_status_string.restype = C.c_char_p
     lib.duo_last_hip_error.argtypes = []
     lib.duo_last_hip_error.restype = C.c_char_p
-    _lib = lib
+    _libs[dtype] = lib
     return lib
 
 
@@ -133,16 +140,16 @@ def _check(code: int, where: str) -> None:
         raise DuoError(code, where, detail)
 
 
-def profile_enable(on: bool) -> None:
-    _check(load().duo_profile_enable(1 if on else 0), "duo_profile_enable")
+def profile_enable(on: bool, dtype: str = "bf16") -> None:
+    _check(load(dtype).duo_profile_enable(1 if on else 0), "duo_profile_enable")
 
 
-def profile_read() -> Dict[str, Dict[str, float]]:
+def profile_read(dtype: str = "bf16") -> Dict[str, Dict[str, float]]:
     """{class: {"ms": total milliseconds, "launches": count}} since the last read."""
     n = len(PROF_CLASSES)
     ms = (C.c_double * n)()
     cnt = (C.c_int32 * n)()
-    _check(load().duo_profile_read(ms, cnt), "duo_profile_read")
+    _check(load(dtype).duo_profile_read(ms, cnt), "duo_profile_read")
     return {PROF_CLASSES[i]: {"ms": ms[i], "launches": cnt[i]} for i in range(n)}
 
 
@@ -222,7 +229,8 @@ def pack_activations(x_bits):
 
 
 class DeviceWeights:
-    """bf16 parameters on the GPU in the library's streaming layout (torch int16 tensors) + the C tables.
+    """16-bit parameters (bf16 bit patterns as uint16 arrays, or numpy float16 arrays) on the GPU in the library's
+    streaming layout (torch int16 tensors) + the C tables.  `dtype` is "bf16" or "fp16" accordingly.
 
     Row-major host matrices are uploaded one layer at a time, repacked on the device by the
     duo_pack_* entry points and dropped; only the packed copies stay resident.
@@ -230,7 +238,8 @@ class DeviceWeights:
 
     def __init__(self, shape, host_weights: Dict[str, object], device: str = "cuda:0"):
         import torch
-        lib = load()
+        lib = load()  # repacking moves 16-bit patterns: the same in both builds
+        self.dtype = dtype_of(host_weights["embed"])
         cfg = make_config(shape, 32)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
         empty = lambda n: torch.empty(n, dtype=torch.int16, device=device)
@@ -275,12 +284,13 @@ class VerifyEngine:
                  max_prefill_rows: int = DUO_MAX_ROWS):
         import torch
         self.torch = torch
-        self.lib = load()
         self.shape = shape
         self.device = device
         self.cfg = make_config(shape, max_seq)
         self.max_seq = max_seq
         self.weights = weights if weights is not None else DeviceWeights(shape, host_weights, device)
+        self.dtype = self.weights.dtype   # the library build that matches the parameters' element type
+        self.lib = load(self.dtype)
         L, H, D = shape.n_layers, shape.n_kv_heads, shape.head_dim
         # planes of max_seq * D elements in the library's tiled layouts (see k_rows_to_tiles / v_rows_to_tiles)
         self.k = torch.zeros((L, H, max_seq * D), dtype=torch.int16, device=device)
@@ -321,8 +331,9 @@ class VerifyEngine:
     def cache_to_host(self):
         """(k, v) as uint16 [L][Hkv][max_seq][D] in the row layout."""
         D = self.shape.head_dim
-        k = k_tiles_to_rows(self.k, D).cpu().numpy().view(np.uint16)
-        v = v_tiles_to_rows(self.vT, D).cpu().numpy().view(np.uint16)
+        host_type = np.float16 if self.dtype == "fp16" else np.uint16
+        k = k_tiles_to_rows(self.k, D).cpu().numpy().view(host_type)
+        v = v_tiles_to_rows(self.vT, D).cpu().numpy().view(host_type)
         return k, v
 
     # ---- entry points
@@ -441,7 +452,7 @@ def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, un
             "status": int(status.cpu().numpy()[0])}
 
 
-def skinny_gemm(x_bits, w_bits):
+def skinny_gemm(x_bits, w_bits, dtype: str = "bf16"):
     """y = x W^T through duo_pack_activations / duo_pack_matrix / duo_skinny_gemm.
     x_bits int16 [rows][K], w_bits int16 [N][K] (row-major bf16 bit patterns on the device)."""
     import torch
@@ -449,11 +460,11 @@ def skinny_gemm(x_bits, w_bits):
     N = w_bits.shape[0]
     xp, wp = pack_activations(x_bits), pack_matrix(w_bits)
     y = torch.empty((rows, N), dtype=torch.float32, device=x_bits.device)
-    _check(load().duo_skinny_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_skinny_gemm")
+    _check(load(dtype).duo_skinny_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_skinny_gemm")
     return y
 
 
-def block_gemm(hi_bits, lo_bits, w_bits):
+def block_gemm(hi_bits, lo_bits, w_bits, dtype: str = "bf16"):
     """y = (hi + lo) W^T through duo_pack_activations / duo_pack_matrix / duo_block_gemm.
     hi_bits, lo_bits int16 [rows][K] (the two bf16 halves of the activations), w_bits int16 [N][K]."""
     import torch
@@ -465,7 +476,7 @@ def block_gemm(hi_bits, lo_bits, w_bits):
     both[pr:pr + rows] = lo_bits
     xp, wp = pack_activations(both), pack_matrix(w_bits)
     y = torch.empty((rows, N), dtype=torch.float32, device=hi_bits.device)
-    _check(load().duo_block_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_block_gemm")
+    _check(load(dtype).duo_block_gemm(xp.data_ptr(), wp.data_ptr(), y.data_ptr(), rows, N, K, _stream_ptr()), "duo_block_gemm")
     return y
 
 

@@ -78,10 +78,10 @@ __device__ __forceinline__ void attn_merge_row(const AttnArgs& a, int hk, int r,
 #pragma unroll
     for (int e = 0; e < D / 64; ++e) {
         const float o = acc[e] / L;
-        const u16 hi = f32_to_bf16(o);
+        const u16 hi = f32_to_elem(o);
         const int col = col0 + lane + e * 64;
         a.out[operand_offset(m, col, a.out_tiles)] = hi;
-        a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(o - bf16_to_f32(hi));
+        a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_elem(o - elem_to_f32(hi));
     }
 }
 
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
 
     // Visibility of draft slots, branch-free: with mk = key - P, row m sees mk < R (prefix and root)
     // and vis_lo <= mk <= vis_hi (its own sequence up to itself).
-    bf16x8 qf[MTW][KS], ql[MTW][KS];
+    elem8 qf[MTW][KS], ql[MTW][KS];
     int vis_lo[MTW], vis_hi[MTW];
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
     // K and V^T tiles of one 32-key block, stored in MFMA operand layout.  S^T tile t, MFMA row 4g'+i' is
     // key kb + 8g' + 4t + i'; V^T operand dt is (channel dt*16 + c, keys kb + 8g .. +8).  Slots of the block at or
     // beyond Ktot may hold anything: their scores are replaced by -inf (a select), their values zeroed.
-    bf16x8 kf[2][2][KS], vf[2][DT];  // double buffered: the next block is loaded while this one is used
+    elem8 kf[2][2][KS], vf[2][DT];  // double buffered: the next block is loaded while this one is used
     auto load_k = [&](int buf, int kb) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
                 pw[j] = exp2f(sc[j] - m_safe);
                 ps += pw[j];
             }
-            split_bf16x8(pw, pf.q, pl.q);
+            split_elem8(pw, pf.q, pl.q);
             l_run[mt] = l_run[mt] * alpha + ps;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
@@ -297,10 +297,10 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float v = o[mt][dt][i] * inv;
-                    const u16 hi = f32_to_bf16(v);
+                    const u16 hi = f32_to_elem(v);
                     const int col = col0 + dt * 16 + g * 4 + i;
                     a.out[operand_offset(m, col, a.out_tiles)] = hi;
-                    a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+                    a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_elem(v - elem_to_f32(hi));
                 }
         } else {
             float* pp = a.part + (((size_t)hk * a.mq_pad + r) * a.nchunks + cb) * (D + 4);
@@ -337,7 +337,7 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
     const int R = a.plan.R;
     const int vis_lo = !ok ? 0x7fffffff : (m < R ? 0 : R + ((m - R) / a.plan.k) * a.plan.k);
     const int vis_hi = ok ? m : -1;
-    bf16x8 qf[KS], ql[KS];
+    elem8 qf[KS], ql[KS];
     {
         const u16* qp = a.q + (size_t)m * a.ldq + (hk * a.group + gq) * D + g * 8;
 #pragma unroll
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
     int nb = (NB - wave + NWV - 1) / NWV;
     nb = nb < 0 ? 0 : nb;
 
-    bf16x8 kf[BATCH][2][KS], vf[BATCH][DT];
+    elem8 kf[BATCH][2][KS], vf[BATCH][DT];
     auto load_v = [&](int b) {
         const int kb = (wave + NWV * b) * 32;
 #pragma unroll
@@ -443,7 +443,7 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
                 pw[j] = exp2f(sc[b][j] - m_safe);
                 l_run += pw[j];
             }
-            split_bf16x8(pw, pf.q, pl.q);
+            split_elem8(pw, pf.q, pl.q);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 o[dt] = mfma16(vf[b][dt], pl.v, o[dt]);
@@ -481,10 +481,10 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float v = acc[i] * inv;
-        const u16 hi = f32_to_bf16(v);
+        const u16 hi = f32_to_elem(v);
         const int col = col0 + wave * 16 + g * 4 + i;
         a.out[operand_offset(m, col, a.out_tiles)] = hi;
-        a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+        a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_elem(v - elem_to_f32(hi));
     }
 }
 
@@ -558,7 +558,7 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     // ---- consumers
     const int MQ = a.plan.M * a.group;
     const int tile0 = (zg * NWV + wave) * MTW;  // first query tile of this wave
-    bf16x8 qf[MTW][KS], ql[MTW][KS];
+    elem8 qf[MTW][KS], ql[MTW][KS];
     int vis_lo[MTW], vis_hi[MTW];
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
@@ -598,7 +598,7 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
         float scs[MTW][8];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            bf16x8 kf[KS];
+            elem8 kf[KS];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) kf[ks] = frag(t * KS + ks).v;
 #pragma unroll
@@ -641,7 +641,7 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
                 pw[j] = exp2f(sc[j] - m_safe);
                 ps += pw[j];
             }
-            split_bf16x8(pw, pf[mt].q, pl[mt].q);  // softmax weights as bf16 pairs (hi + lo)
+            split_elem8(pw, pf[mt].q, pl[mt].q);  // softmax weights as bf16 pairs (hi + lo)
             l_run[mt] = l_run[mt] * alpha[mt] + ps;
             // the running maximum rarely moves after the first blocks: rescale only when some row's did
             if (__ballot(alpha[mt] != 1.0f) != 0) {
@@ -685,10 +685,10 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float v = o[mt][dt][i] * inv;
-                    const u16 hi = f32_to_bf16(v);
+                    const u16 hi = f32_to_elem(v);
                     const int col = col0 + dt * 16 + g * 4 + i;
                     a.out[operand_offset(m, col, a.out_tiles)] = hi;
-                    a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_bf16(v - bf16_to_f32(hi));
+                    a.out[operand_offset(a.pair_rows + m, col, a.out_tiles)] = f32_to_elem(v - elem_to_f32(hi));
                 }
         } else {
             float* pp = a.part + (((size_t)hk * a.mq_pad + r) * a.nchunks + cb) * (D + 4);

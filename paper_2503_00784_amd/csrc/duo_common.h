@@ -4,7 +4,6 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -27,46 +26,65 @@ static LaunchEvents g_launch_events;
         }                                                                                                       \
     } while (0)
 
-// bf16 <-> fp32 (round to nearest even); inputs here are finite.
-__device__ __forceinline__ float bf16_to_f32(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ u16 f32_to_bf16(float f) {
+// The 16-bit element type of the weights, the KV cache and the operand buffers.  The library is built twice from
+// the same sources: bf16 (the default; every comment that says "bf16" describes this build) and, with DUO_FP16
+// defined, IEEE fp16, the format the paper ran its target model in (Sec. 4.1).  Everything type-dependent is in
+// this block: conversions (round to nearest even), the two-element pack, and the MFMA.  Buffers are uint16_t
+// bit patterns of whichever type the build uses; inputs here are finite.
+#ifdef DUO_FP16
+typedef _Float16 elem_t;
+__device__ __forceinline__ float elem_to_f32(u16 b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ u16 f32_to_elem(float f) { return __builtin_bit_cast(u16, (_Float16)f); }
+#else
+typedef __bf16 elem_t;
+__device__ __forceinline__ float elem_to_f32(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ u16 f32_to_elem(float f) {
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (u16)(u >> 16);
 }
-
-// Two floats -> two bf16 (round to nearest even) in one register, a in the low half: the hardware conversion.
-typedef __bf16 hwbf16x2 __attribute__((ext_vector_type(2)));
+#endif
+typedef elem_t elem8 __attribute__((ext_vector_type(8)));
+typedef elem_t elem2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    const hwbf16x2 v = __builtin_convertvector(f32x2{a, b}, hwbf16x2);
+
+// Two floats -> two elements (round to nearest even) in one register, a in the low half: the hardware conversion.
+__device__ __forceinline__ uint32_t pack_elem2(float a, float b) {
+    const elem2 v = __builtin_convertvector(f32x2{a, b}, elem2);
     return __builtin_bit_cast(uint32_t, v);
 }
-// x[0..7] -> hi = bf16(x), lo = bf16(x - hi), as MFMA operand registers
-__device__ __forceinline__ void split_bf16x8(const float (&x)[8], u32x4& hi, u32x4& lo) {
+// the two halves of such a register back as floats
+__device__ __forceinline__ float elem2_lo_f32(uint32_t p) { return elem_to_f32((u16)(p & 0xffffu)); }
+__device__ __forceinline__ float elem2_hi_f32(uint32_t p) { return elem_to_f32((u16)(p >> 16)); }
+// x[0..7] -> hi = elem(x), lo = elem(x - hi), as MFMA operand registers
+__device__ __forceinline__ void split_elem8(const float (&x)[8], u32x4& hi, u32x4& lo) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const uint32_t h = pack_bf16x2(x[2 * j], x[2 * j + 1]);
+        const uint32_t h = pack_elem2(x[2 * j], x[2 * j + 1]);
         hi[j] = h;
-        lo[j] = pack_bf16x2(x[2 * j] - __uint_as_float(h << 16), x[2 * j + 1] - __uint_as_float(h & 0xffff0000u));
+        lo[j] = pack_elem2(x[2 * j] - elem2_lo_f32(h), x[2 * j + 1] - elem2_hi_f32(h));
     }
 }
 
 union Frag8 {  // eight bf16 values = one 16-byte load = one MFMA operand
-    bf16x8 v;
+    elem8 v;
     u32x4 q;
     u16 h[8];
 };
 
-__device__ __forceinline__ bf16x8 load_frag(const u16* p) {
+__device__ __forceinline__ elem8 load_frag(const u16* p) {
     Frag8 f;
     f.q = *reinterpret_cast<const u32x4*>(p);
     return f.v;
 }
-__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+__device__ __forceinline__ f32x4 mfma16(elem8 a, elem8 b, f32x4 c) {
     // D[16x16] += A[16x32] * B[32x16]; lane l supplies A[l%16][8*(l/16) .. +8] and
     // B[8*(l/16) .. +8][l%16]; it receives D[4*(l/16) .. +4][l%16].
+#ifdef DUO_FP16
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+#else
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+#endif
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

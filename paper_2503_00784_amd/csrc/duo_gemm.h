@@ -110,7 +110,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
     // loop and the number of loads in flight behind any MFMA is the same in every iteration.  All loads
     // are unconditional (indices clamped to the wave's last step) and scheduling barriers keep the
     // compiler from regrouping them, so the wait before each MFMA group is for exactly one slot.
-    bf16x8 bb[PF][NT], aa[PF][MT];
+    elem8 bb[PF][NT], aa[PF][MT];
     auto load_slot = [&](int p, int i) {
         const int st = step_of(i);
 #pragma unroll
@@ -307,8 +307,8 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     for (int m = 0; m < MA; ++m)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bf16x8 bb[PF][NT];
-    bf16x8 af[2][MT];
+    elem8 bb[PF][NT];
+    elem8 af[2][MT];
     auto w_load = [&](int p, int i) {  // i-th step of this wave: round i / AG, position nk * AG + i % AG in it; clamped
         int ls = (i / AG) * RS + nk * AG + (i % AG);
         ls = ls < ns ? ls : ns - 1;
@@ -335,7 +335,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     a_frags(0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const elem8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int r0 = 0; r0 < rounds; r0 += U) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -345,7 +345,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
                 const int p = u * AG + w;
                 if (w + 1 < AG) a_frags((p + 1) & 1, r, w + 1);
                 const bool valid = r * RS + nk * AG + w < ns;
-                bf16x8 b[NT];
+                elem8 b[NT];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) b[t] = valid ? bb[p][t] : zero;
                 if constexpr (HALF) {  // activations first: a lane's quad is four rows of one column
@@ -444,16 +444,16 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // four floats -> hi = bf16(x) and lo = bf16(x - hi), four bf16 values (8 bytes) each
-__device__ __forceinline__ void split_bf16x4(const f32x4& x, u32x2& hi, u32x2& lo) {
+__device__ __forceinline__ void split_elem4(const f32x4& x, u32x2& hi, u32x2& lo) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const uint32_t h = pack_bf16x2(x[2 * j], x[2 * j + 1]);
+        const uint32_t h = pack_elem2(x[2 * j], x[2 * j + 1]);
         hi[j] = h;
-        lo[j] = pack_bf16x2(x[2 * j] - __uint_as_float(h << 16), x[2 * j + 1] - __uint_as_float(h & 0xffff0000u));
+        lo[j] = pack_elem2(x[2 * j] - elem2_lo_f32(h), x[2 * j + 1] - elem2_hi_f32(h));
     }
 }
-__device__ __forceinline__ u32x2 pack_bf16x4(const f32x4& x) {
-    return u32x2{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+__device__ __forceinline__ u32x2 pack_elem4(const f32x4& x) {
+    return u32x2{pack_elem2(x[0], x[1]), pack_elem2(x[2], x[3])};
 }
 
 struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile*NT + t)*16 .. +16 of W
@@ -511,7 +511,7 @@ struct EpiResidual {
     };
     __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
         const int n = tile * 16 + c;
-        p.g = bf16_to_f32(gain[n]);
+        p.g = elem_to_f32(gain[n]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = qi * 4 + i;
@@ -520,7 +520,7 @@ struct EpiResidual {
     }
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[1], const Pre& p, bool use_pre) const {
         const int n = tile * 16 + c;
-        const float gn = use_pre ? p.g : bf16_to_f32(gain[n]);
+        const float gn = use_pre ? p.g : elem_to_f32(gain[n]);
         float sq[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -531,9 +531,9 @@ struct EpiResidual {
                 X[(size_t)m * ldx + n] = xn;
                 sq[i] = xn * xn;
                 const float u = xn * gn;
-                const u16 hi = f32_to_bf16(u);
+                const u16 hi = f32_to_elem(u);
                 h[operand_offset(m, n, h_tiles)] = hi;
-                h[operand_offset(pair_rows + m, n, h_tiles)] = f32_to_bf16(u - bf16_to_f32(hi));
+                h[operand_offset(pair_rows + m, n, h_tiles)] = f32_to_elem(u - elem_to_f32(hi));
             }
         }
 #pragma unroll
@@ -554,10 +554,10 @@ struct EpiResidual {
             *reinterpret_cast<f32x4*>(xp) = xn;
             sq = (xn[0] * xn[0] + xn[1] * xn[1]) + (xn[2] * xn[2] + xn[3] * xn[3]);
             const u32x2 gb = *reinterpret_cast<const u32x2*>(gain + n);
-            const f32x4 u = {xn[0] * __uint_as_float(gb[0] << 16), xn[1] * __uint_as_float(gb[0] & 0xffff0000u),
-                             xn[2] * __uint_as_float(gb[1] << 16), xn[3] * __uint_as_float(gb[1] & 0xffff0000u)};
+            const f32x4 u = {xn[0] * elem2_lo_f32(gb[0]), xn[1] * elem2_hi_f32(gb[0]), xn[2] * elem2_lo_f32(gb[1]),
+                             xn[3] * elem2_hi_f32(gb[1])};
             u32x2 hi, lo;
-            split_bf16x4(u, hi, lo);
+            split_elem4(u, hi, lo);
             *reinterpret_cast<u32x2*>(h + operand_offset(m, n, h_tiles)) = hi;
             *reinterpret_cast<u32x2*>(h + operand_offset(pair_rows + m, n, h_tiles)) = lo;
         }
@@ -584,9 +584,9 @@ struct EpiSwiGLU {
             if (m < M) {
                 const float gate = v[0][i], up = v[1][i];
                 const float a = gate / (1.f + expf(-gate)) * up;
-                const u16 hi = f32_to_bf16(a);
+                const u16 hi = f32_to_elem(a);
                 act[operand_offset(m, n, act_tiles)] = hi;
-                act[operand_offset(pair_rows + m, n, act_tiles)] = f32_to_bf16(a - bf16_to_f32(hi));
+                act[operand_offset(pair_rows + m, n, act_tiles)] = f32_to_elem(a - elem_to_f32(hi));
             }
         }
     }
@@ -597,7 +597,7 @@ struct EpiSwiGLU {
 #pragma unroll
         for (int i = 0; i < 4; ++i) a[i] = v[0][i] / (1.f + expf(-v[0][i])) * v[1][i];
         u32x2 hi, lo;
-        split_bf16x4(a, hi, lo);
+        split_elem4(a, hi, lo);
         *reinterpret_cast<u32x2*>(act + operand_offset(m, n, act_tiles)) = hi;
         *reinterpret_cast<u32x2*>(act + operand_offset(pair_rows + m, n, act_tiles)) = lo;
     }
@@ -646,20 +646,20 @@ struct EpiQKV {
                 const float rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
                 if (head < Hq) {
                     u16* q = q_out + (size_t)m * ldq + head * D + d;
-                    const u16 l1 = f32_to_bf16(rl), h1 = f32_to_bf16(rh);
+                    const u16 l1 = f32_to_elem(rl), h1 = f32_to_elem(rh);
                     q[0] = l1;
                     q[half] = h1;
-                    q[q_plane] = f32_to_bf16(rl - bf16_to_f32(l1));
-                    q[q_plane + half] = f32_to_bf16(rh - bf16_to_f32(h1));
+                    q[q_plane] = f32_to_elem(rl - elem_to_f32(l1));
+                    q[q_plane + half] = f32_to_elem(rh - elem_to_f32(h1));
                 } else {
                     u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
-                    kp[k_cache_offset(D, plan.slot(m), d)] = f32_to_bf16(rl);
-                    kp[k_cache_offset(D, plan.slot(m), d + half)] = f32_to_bf16(rh);
+                    kp[k_cache_offset(D, plan.slot(m), d)] = f32_to_elem(rl);
+                    kp[k_cache_offset(D, plan.slot(m), d + half)] = f32_to_elem(rh);
                 }
             } else {
                 u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
-                vp[v_cache_offset(D, plan.slot(m), d)] = f32_to_bf16(lo);
-                vp[v_cache_offset(D, plan.slot(m), d + half)] = f32_to_bf16(hi);
+                vp[v_cache_offset(D, plan.slot(m), d)] = f32_to_elem(lo);
+                vp[v_cache_offset(D, plan.slot(m), d + half)] = f32_to_elem(hi);
             }
         }
     }
@@ -675,23 +675,23 @@ struct EpiQKV {
             if (head < Hq) {
                 u16* q = q_out + (size_t)m * ldq + head * D + d;
                 u32x2 l1, l2, h1, h2;
-                split_bf16x4(rl, l1, l2);
-                split_bf16x4(rh, h1, h2);
+                split_elem4(rl, l1, l2);
+                split_elem4(rh, h1, h2);
                 *reinterpret_cast<u32x2*>(q) = l1;
                 *reinterpret_cast<u32x2*>(q + half) = h1;
                 *reinterpret_cast<u32x2*>(q + q_plane) = l2;
                 *reinterpret_cast<u32x2*>(q + q_plane + half) = h2;
             } else {  // four consecutive channels are contiguous in a key tile
                 u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
-                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d)) = pack_bf16x4(rl);
-                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d + half)) = pack_bf16x4(rh);
+                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d)) = pack_elem4(rl);
+                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d + half)) = pack_elem4(rh);
             }
         } else {  // the value tiles keep eight SLOTS of one channel together: element stores
             u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                vp[v_cache_offset(D, plan.slot(m), d + i)] = f32_to_bf16(lo[i]);
-                vp[v_cache_offset(D, plan.slot(m), d + half + i)] = f32_to_bf16(hi[i]);
+                vp[v_cache_offset(D, plan.slot(m), d + i)] = f32_to_elem(lo[i]);
+                vp[v_cache_offset(D, plan.slot(m), d + half + i)] = f32_to_elem(hi[i]);
             }
         }
     }

@@ -112,7 +112,7 @@ __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__
         for (int ks = 0; ks < KS; ++ks) {
             if (r * KS + ks < ns) {  // wave-uniform
                 const u32x4* st = stage + ks * PER * 64;
-                bf16x8 ah[WM], al[WM], b[WN];
+                elem8 ah[WM], al[WM], b[WN];
 #pragma unroll
                 for (int m = 0; m < WM; ++m) {
                     Frag8 f, g;

@@ -47,12 +47,12 @@ __global__ __launch_bounds__(256) void embed_kernel(const u16* __restrict__ embe
         float sq = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const float xv = bf16_to_f32(ev.h[j]);
+            const float xv = elem_to_f32(ev.h[j]);
             xr[j8 + j] = xv;
             sq += xv * xv;
-            const float u = xv * bf16_to_f32(gv.h[j]);
-            hi.h[j] = f32_to_bf16(u);
-            lo.h[j] = f32_to_bf16(u - bf16_to_f32(hi.h[j]));
+            const float u = xv * elem_to_f32(gv.h[j]);
+            hi.h[j] = f32_to_elem(u);
+            lo.h[j] = f32_to_elem(u - elem_to_f32(hi.h[j]));
         }
         *reinterpret_cast<u32x4*>(h + operand_offset(m, j8, tiles)) = hi.q;
         *reinterpret_cast<u32x4*>(h + operand_offset(pair_rows + m, j8, tiles)) = lo.q;
@@ -103,9 +103,9 @@ __global__ __launch_bounds__(512) void residual_reduce_kernel(const float* __res
         for (int j = 0; j < 8; ++j) {
             const float xv = j < 4 ? a0[j] : a1[j - 4];
             sq += xv * xv;
-            const float u = xv * bf16_to_f32(gv.h[j]);
-            hi.h[j] = f32_to_bf16(u);
-            lo.h[j] = f32_to_bf16(u - bf16_to_f32(hi.h[j]));
+            const float u = xv * elem_to_f32(gv.h[j]);
+            hi.h[j] = f32_to_elem(u);
+            lo.h[j] = f32_to_elem(u - elem_to_f32(hi.h[j]));
         }
         *reinterpret_cast<u32x4*>(h + operand_offset(m, j8, tiles)) = hi.q;
         *reinterpret_cast<u32x4*>(h + operand_offset(pair_rows + m, j8, tiles)) = lo.q;

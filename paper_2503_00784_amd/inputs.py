@@ -97,13 +97,14 @@ def _rng(seed: int, *stream: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, *stream])))
 
 
-def _normal_bf16(shape: Tuple[int, ...], std: float, mean: float, seed: int, *stream: int) -> np.ndarray:
+def _normal_16(shape: Tuple[int, ...], std: float, mean: float, dtype: str, seed: int, *stream: int) -> np.ndarray:
+    """Normal draws rounded to the 16-bit element type: bf16 bit patterns (uint16) or numpy float16."""
     g = _rng(seed, *stream)
     x = g.standard_normal(shape, dtype=np.float32)
     x *= np.float32(std)
     if mean != 0.0:
         x += np.float32(mean)
-    return f32_to_bf16_bits(x)
+    return x.astype(np.float16) if dtype == "fp16" else f32_to_bf16_bits(x)
 
 
 # tensor ids (second element of the seed sequence)
@@ -113,8 +114,9 @@ _T_LAYER = {"wq": 10, "wk": 11, "wv": 12, "wo": 13, "w_gate": 14, "w_up": 15, "w
 _T_PREFIX, _T_KV, _T_ROOT, _T_Q, _T_TOK, _T_UNI = 30, 31, 32, 33, 34, 35
 
 
-def make_weights(shape: ModelShape, seed: int = 0, threads: int = 8) -> Dict[str, object]:
-    """bf16 bit patterns of every parameter.
+def make_weights(shape: ModelShape, seed: int = 0, threads: int = 8, dtype: str = "bf16") -> Dict[str, object]:
+    """Every parameter in the 16-bit element type: bf16 bit patterns (uint16 arrays) or, for dtype "fp16", numpy
+    float16 arrays (the same draws, rounded to the other grid).
 
     Matrices, embedding and LM head ~ N(0, 0.02); RMSNorm gains ~ 1 + N(0, 0.02) (all-ones
     gains would hide a missing multiply).  Per-layer entries are lists of arrays.
@@ -134,7 +136,7 @@ def make_weights(shape: ModelShape, seed: int = 0, threads: int = 8) -> Dict[str
 
     def run(job):
         name, layer, dim, std, mean, tid = job
-        return name, layer, _normal_bf16(dim, std, mean, seed, tid, 0 if layer is None else layer)
+        return name, layer, _normal_16(dim, std, mean, dtype, seed, tid, 0 if layer is None else layer)
 
     out: Dict[str, object] = {name: [None] * shape.n_layers for name in dims}
     with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:
@@ -150,7 +152,7 @@ def make_prefix_ids(shape: ModelShape, prefix_len: int, seed: int = 0) -> np.nda
     return _rng(seed, _T_PREFIX).integers(0, shape.vocab, size=prefix_len, dtype=np.int32)
 
 
-def make_synthetic_cache(shape: ModelShape, prefix_len: int, max_seq: int, seed: int = 0
+def make_synthetic_cache(shape: ModelShape, prefix_len: int, max_seq: int, seed: int = 0, dtype: str = "bf16"
                          ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """A stand-in for a prefilled cache at sizes where a CPU prefill would take hours.
 
@@ -159,12 +161,13 @@ def make_synthetic_cache(shape: ModelShape, prefix_len: int, max_seq: int, seed:
     root logits ~ N(0, 1.28^2) fp32.  Layout [layer][kv_head][slot][head_dim].
     """
     L, H, D = shape.n_layers, shape.n_kv_heads, shape.head_dim
-    k = np.zeros((L, H, max_seq, D), dtype=np.uint16)
-    v = np.zeros((L, H, max_seq, D), dtype=np.uint16)
+    host_type = np.float16 if dtype == "fp16" else np.uint16
+    k = np.zeros((L, H, max_seq, D), dtype=host_type)
+    v = np.zeros((L, H, max_seq, D), dtype=host_type)
 
     def fill(layer: int) -> None:
-        k[layer, :, :prefix_len] = _normal_bf16((H, prefix_len, D), 1.28, 0.0, seed, _T_KV, layer, 0)
-        v[layer, :, :prefix_len] = _normal_bf16((H, prefix_len, D), 1.28, 0.0, seed, _T_KV, layer, 1)
+        k[layer, :, :prefix_len] = _normal_16((H, prefix_len, D), 1.28, 0.0, dtype, seed, _T_KV, layer, 0)
+        v[layer, :, :prefix_len] = _normal_16((H, prefix_len, D), 1.28, 0.0, dtype, seed, _T_KV, layer, 1)
 
     with ThreadPoolExecutor(max_workers=8) as pool:
         list(pool.map(fill, range(L)))

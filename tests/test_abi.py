@@ -25,8 +25,10 @@ def test_every_declared_entry_point_is_exported(lib):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(duo_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
-    for name in declared:
-        assert getattr(lib, name) is not None
+    for dtype in ("bf16", "fp16"):  # the two builds of the same sources export the same entry points
+        one = B.load(dtype)
+        for name in declared:
+            assert getattr(one, name) is not None
 
 
 def test_status_strings(lib):
@@ -137,10 +139,12 @@ def test_other_entry_points_validate(lib):
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
-    monkeypatch.setattr(B, "_lib", None)
-    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    monkeypatch.setattr(B, "_libs", {})
+    monkeypatch.setattr(B, "LIB_PATHS", {"bf16": str(tmp_path / "nope.so"), "fp16": str(tmp_path / "nope16.so")})
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.load()
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.load("fp16")
 
 
 def test_input_generators_are_seeded_and_shaped():

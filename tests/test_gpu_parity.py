@@ -189,12 +189,13 @@ def test_sampler_flags_out_of_range_token(B):
 
 
 # ------------------------------------------------------------------ the whole step
-def _engine_and_oracle(B, shape, P, max_seq, seed, synthetic_cache):
-    w = inputs.make_weights(shape, seed=seed, threads=16)
+def _engine_and_oracle(B, shape, P, max_seq, seed, synthetic_cache, dtype="bf16", max_prefill_rows=80):
+    w = inputs.make_weights(shape, seed=seed, threads=16, dtype=dtype)
     oshape = O.shape_from(shape)
-    eng = B.VerifyEngine(shape, w, max_seq)
+    eng = B.VerifyEngine(shape, w, max_seq, max_prefill_rows=max_prefill_rows)
+    assert eng.dtype == dtype
     if synthetic_cache:
-        kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=seed)
+        kb, vb, root = inputs.make_synthetic_cache(shape, P, max_seq, seed=seed, dtype=dtype)
         eng.load_cache(kb, vb, P, root)
         cache = O.OracleCache.from_bits(oshape, kb, vb, P, root)
         del kb, vb
@@ -490,3 +491,80 @@ def test_full_size_prefill_paths_agree(B):
     assert (dl <= 2 * (2e-2 + 1e-2 * np.abs(lb))).all()
     assert np.abs(ka - kb).max() <= 0.07 and np.abs(va - vb).max() <= 0.07
     assert np.abs(ka).max() > 0.5 and np.abs(la).max() > 0.5   # not comparing zeros
+
+
+# ------------------------------------------------------------------ the fp16 build (the same sources, DUO_FP16)
+@pytest.mark.parametrize("rows,N,K", [(8, 4096, 4096), (33, 4099, 1408), (80, 515, 96)])
+def test_fp16_skinny_gemm_matches_oracle_matmul(B, rows, N, K):
+    import torch
+    say(f"fp16 gemm rows={rows} N={N} K={K}")
+    g = np.random.default_rng(rows * 1000 + N)
+    x = g.normal(0, 1, (rows, K)).astype(np.float16)
+    w = g.normal(0, 0.02, (N, K)).astype(np.float16)
+    y = B.skinny_gemm(to_dev(x.view(np.int16)), to_dev(w.view(np.int16)), dtype="fp16")
+    torch.cuda.synchronize()
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    err = np.abs(y.cpu().numpy() - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= 2e-6 * np.sqrt(K) * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("rows,N,K", [(128, 4096, 4096), (300, 4099, 1408)])
+def test_fp16_block_gemm_matches_oracle_matmul(B, rows, N, K):
+    import torch
+    say(f"fp16 block gemm rows={rows} N={N} K={K}")
+    g = np.random.default_rng(rows * 1000 + N)
+    a = g.normal(0, 1, (rows, K)).astype(np.float32)
+    hi = a.astype(np.float16)
+    lo = (a.astype(np.float64) - hi.astype(np.float64)).astype(np.float16)
+    w = g.normal(0, 0.02, (N, K)).astype(np.float16)
+    y = B.block_gemm(to_dev(hi.view(np.int16)), to_dev(lo.view(np.int16)), to_dev(w.view(np.int16)), dtype="fp16")
+    torch.cuda.synchronize()
+    ref = (hi.astype(np.float64) + lo.astype(np.float64)) @ w.astype(np.float64).T
+    err = np.abs(y.cpu().numpy() - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= 2e-6 * np.sqrt(K) * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("n,k,mode,root", [(1, 8, 0, -1), (3, 5, 1, 17), (5, 16, 0, -1), (4, 8, 0, 3)])
+def test_fp16_mid_config_step(B, n, k, mode, root):
+    """fp16 parameters and KV cache (the paper's precision): prefill and one verify step against the oracle run on the
+    same float16 parameters, same tolerance as the bf16 build."""
+    shape = inputs.MID
+    say(f"fp16 MID n={n} k={k} mode={mode} root={root}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False, dtype="fp16")
+    ok, max_abs, worst = logits_close(eng.root_logits.cpu().numpy(), cache.root_logits)
+    assert ok
+    _check_cache(eng, cache, 77, atol=0.01)   # fp16 cache: a rounding flip is 8x smaller than in bf16
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 31 + k, mode=mode, root_token=root)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len, atol=0.01)
+
+
+def test_fp16_many_row_prefill(B):
+    shape = inputs.MID
+    chunks = (300, 95)
+    total = sum(chunks)
+    say("fp16 MID many-row prefill")
+    w = inputs.make_weights(shape, seed=4, threads=16, dtype="fp16")
+    oshape = O.shape_from(shape)
+    eng = B.VerifyEngine(shape, w, 448, max_prefill_rows=max(chunks))
+    prefix = inputs.make_prefix_ids(shape, total, seed=4)
+    at = 0
+    for c in chunks:
+        eng.prefill(prefix[at:at + c].tolist(), chunk=c)
+        at += c
+    cache = O.prefill(oshape, w, prefix.tolist(), 448)
+    ok, max_abs, worst = logits_close(eng.root_logits.cpu().numpy(), cache.root_logits)
+    say(f"  root logits max abs err {max_abs:.3e}")
+    assert ok
+    _check_cache(eng, cache, total, atol=0.01)
+
+
+def test_fp16_full_size_shape(B):
+    """Llama-2-7B geometry in fp16 at the benchmark's launch configuration (C1)."""
+    wl = inputs.WORKLOADS["C1"]
+    shape, P, n, k = wl.shape, wl.prefix_len, wl.n_seq, wl.k_draft
+    say("fp16 C1: generating weights")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, P + 128, seed=0, synthetic_cache=True, dtype="fp16")
+    got, res, compared = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=1, mode=0, root_token=-1)

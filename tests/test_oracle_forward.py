@@ -219,3 +219,41 @@ def test_row_plan_slots_positions_and_visibility():
     assert plan[6] == (13, 16, [0, 4, 5, 6])
     plan = O.row_plan(10, 2, 2, has_root=False)
     assert plan == [(10, 10, [0]), (11, 11, [0, 1]), (10, 12, [2]), (11, 13, [2, 3])]
+
+
+# ------------------------------------------------------------------ fp16 as the storage type (the paper's precision)
+def test_fp16_rounding_and_generator_match_torch():
+    import torch
+    from paper_2503_00784_amd import inputs
+    assert O.round_to_fp16(np.array([1.0 + 2.0 ** -11]))[0] == 1.0                   # tie -> even mantissa
+    assert O.round_to_fp16(np.array([1.0 + 3 * 2.0 ** -11]))[0] == 1.0 + 2.0 ** -9
+    x = np.random.default_rng(5).normal(size=4096).astype(np.float32)
+    t = torch.from_numpy(x).to(torch.float16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_fp16(x), t)
+    w = inputs.make_weights(inputs.ModelShape(1, 64, 4, 2, 16, 96, 50), seed=2, threads=2, dtype="fp16")
+    b = inputs.make_weights(inputs.ModelShape(1, 64, 4, 2, 16, 96, 50), seed=2, threads=2)
+    assert w["wq"][0].dtype == np.float16 and b["wq"][0].dtype == np.uint16
+    # the same draws on two grids: equal to within the coarser (bf16) rounding step
+    np.testing.assert_allclose(w["wq"][0].astype(np.float64), O.bf16_bits_to_f64(b["wq"][0]), rtol=2.0 ** -8, atol=0)
+    np.testing.assert_array_equal(O.bf16_bits_to_f64(w["wq"][0]), w["wq"][0].astype(np.float64))
+
+
+def test_fp16_parameters_only_change_widening_and_the_cache_grid():
+    """With float16 parameters the forward pass is the same arithmetic on the widened values (ideal mode equals the pass
+    over the same values given as float64), and the contract rounds what the cache stores to the fp16 grid."""
+    from paper_2503_00784_amd import inputs
+    shape_in = inputs.ModelShape(2, 64, 4, 2, 16, 96, 101)
+    shape = O.shape_from(shape_in)
+    w16 = inputs.make_weights(shape_in, seed=1, threads=2, dtype="fp16")
+    w64 = {k: ([a.astype(np.float64) for a in v] if isinstance(v, list) else v.astype(np.float64)) for k, v in w16.items()}
+    toks = list(range(3, 15))
+    np.testing.assert_array_equal(O.full_forward_uncached(shape, w16, toks, rounding="ideal"),
+                                  O.full_forward_uncached(shape, w64, toks, rounding="ideal"))
+    cache = O.prefill(shape, w16, toks[:8], max_seq=16, rounding="contract")
+    kept = cache.k[:, :, :8]
+    np.testing.assert_array_equal(kept, kept.astype(np.float16).astype(np.float64))   # on the fp16 grid
+    assert np.abs(kept - O.round_to_bf16(kept)).max() > 0                              # and not on the bf16 grid
+    ideal = O.full_forward_uncached(shape, w16, toks, rounding="ideal")
+    contract = O.full_forward_uncached(shape, w16, toks, rounding="contract")
+    err = np.abs(ideal - contract).max()
+    assert 0 < err < 3e-3 * max(1.0, np.abs(ideal).max())                             # fp16 cache: 8x finer than bf16
