@@ -323,12 +323,19 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         nchunks = (NB + 4 * bpw - 1) / (4 * bpw);
     }
 
+    // The bands of the Q/K/V matrix are independent of each other, so a wave may take one or two.  One band per wave
+    // where that makes a single, nearly full round of workgroups (measured at 768 bands of 4096 input channels:
+    // 18.5 against 21.1 us for up to eight rows, 18.8 / 21.8 / 28.7 / 32.4 against 22.0 / 24.8 / 32.1 / 35.2 us for
+    // 16 / 32 / 64 / 80 rows; at 384 bands the same or slightly better beyond eight rows).
+    const int qkv_bands = (Hq + 2 * Hkv) * (D / 16);
+    const int qkv_nt = M > DUO_MAX_ROWS ? 2 : (M <= 8 ? ((qkv_bands > 512 && qkv_bands <= 768) ? 1 : 2) : (qkv_bands <= 768 ? 1 : 2));
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * c.max_seq * D;
-        EpiQKV eq{Hq, Hkv, D, half, half / 16, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
-        launch_projection<2>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, (Hq + 2 * Hkv) * (half / 16), (l == 0 || down_split) ? norm_full : norm_part,
-                             eq, s);
+        EpiQKV eq{Hq, Hkv, D, half, D / 16, qkv_nt, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
+        const RowScale& qkv_norm = (l == 0 || down_split) ? norm_full : norm_part;
+        if (qkv_nt == 1) launch_projection<1>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands, qkv_norm, eq, s);
+        else launch_projection<2>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands / 2, qkv_norm, eq, s);
 
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,
                     1.4426950408889634f / sqrtf((float)D), ws.part, ws.attn, AT, PR};
@@ -674,8 +681,8 @@ int duo_pack_qkv(const duo_model_config* cfg, const uint16_t* wq, const uint16_t
     if (!aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(dst)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    const int D = cfg->head_dim, half = D / 2, bph = half / 16;
-    const int bands = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * bph * 2;
+    const int D = cfg->head_dim, half = D / 2, bph = D / 16;
+    const int bands = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * bph;
     DUO_LAUNCH((pack_bands_kernel<QKVRows>), dim3(bands), dim3(256), s,
                        QKVRows{wq, wk, wv, cfg->n_q_heads, cfg->n_kv_heads, D, half, bph, cfg->d_model}, cfg->d_model / 32, dst);
     return hip_ok(hipGetLastError(), "duo_pack_qkv launch");

@@ -603,12 +603,13 @@ struct EpiSwiGLU {
     }
 };
 
-// Fused Q/K/V projection: a workgroup's two bands are rows d.. and d + D/2.. of one head, the two
-// halves of a rotary pair, so the rotation is thread-local.  Q goes to the query buffer as a bf16 pair
-// (hi plane, lo plane), K
-// (rotated) and V into their cache slots (tiled layouts, see k_cache_offset / v_cache_offset).
+// Fused Q/K/V projection.  A band holds eight channels of one head and, eight columns further on, their rotary
+// partners (channel + D/2), so the rotation needs one exchange between two lanes of the wave that owns the band and
+// bands are independent of each other.  Q goes to the query buffer as a pair of planes (hi, lo), K (rotated) and V
+// into their cache slots (tiled layouts, see k_cache_offset / v_cache_offset).
 struct EpiQKV {
-    int Hq, Hkv, D, half, bph;  // bph = (D/2)/16 workgroup tiles per head
+    int Hq, Hkv, D, half, bph;  // bph = D/16 bands per head
+    int nt;                     // bands per workgroup tile of the launch that uses this epilogue (1 or 2)
     u16* q_out;  // hi plane; the lo plane starts q_plane elements further on
     int ldq;
     size_t q_plane;
@@ -619,79 +620,92 @@ struct EpiQKV {
     const float* rope_sin;
     RowPlan plan;
     struct Pre {
-        float cs[4], sn[4];
+        float cs[2][4], sn[2][4];
     };
+    // Column c of band (head, j) is channel 8j + c (c < 8) or its rotary partner D/2 + 8j + c - 8.
     __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
-        const int head = tile / bph;
-        const int d = (tile - head * bph) * 16 + c;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = qi * 4 + i;
-            const bool rot = m < plan.M && head < Hq + Hkv;
-            p.cs[i] = rot ? rope_cos[m * half + d] : 1.f;
-            p.sn[i] = rot ? rope_sin[m * half + d] : 0.f;
-        }
-    }
-    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2], const Pre& p, bool use_pre) const {
-        int head = tile / bph;
-        const int d = (tile - head * bph) * 16 + c;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = qi * 4 + i;
-            if (m >= plan.M) continue;
-            const float lo = v[0][i], hi = v[1][i];
-            if (head < Hq + Hkv) {
-                const float cs = use_pre ? p.cs[i] : rope_cos[m * half + d];
-                const float sn = use_pre ? p.sn[i] : rope_sin[m * half + d];
-                const float rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
-                if (head < Hq) {
-                    u16* q = q_out + (size_t)m * ldq + head * D + d;
-                    const u16 l1 = f32_to_elem(rl), h1 = f32_to_elem(rh);
-                    q[0] = l1;
-                    q[half] = h1;
-                    q[q_plane] = f32_to_elem(rl - elem_to_f32(l1));
-                    q[q_plane + half] = f32_to_elem(rh - elem_to_f32(h1));
-                } else {
-                    u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
-                    kp[k_cache_offset(D, plan.slot(m), d)] = f32_to_elem(rl);
-                    kp[k_cache_offset(D, plan.slot(m), d + half)] = f32_to_elem(rh);
-                }
-            } else {
-                u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
-                vp[v_cache_offset(D, plan.slot(m), d)] = f32_to_elem(lo);
-                vp[v_cache_offset(D, plan.slot(m), d + half)] = f32_to_elem(hi);
-            }
-        }
-    }
-    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[2]) const {
-        if (m >= plan.M) return;
-        const int head = tile / bph;
-        const int d = (tile - head * bph) * 16 + c4;
-        const f32x4 lo = v[0], hi = v[1];
-        if (head < Hq + Hkv) {
-            const f32x4 cs = *reinterpret_cast<const f32x4*>(rope_cos + m * half + d);
-            const f32x4 sn = *reinterpret_cast<const f32x4*>(rope_sin + m * half + d);
-            const f32x4 rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
-            if (head < Hq) {
-                u16* q = q_out + (size_t)m * ldq + head * D + d;
-                u32x2 l1, l2, h1, h2;
-                split_elem4(rl, l1, l2);
-                split_elem4(rh, h1, h2);
-                *reinterpret_cast<u32x2*>(q) = l1;
-                *reinterpret_cast<u32x2*>(q + half) = h1;
-                *reinterpret_cast<u32x2*>(q + q_plane) = l2;
-                *reinterpret_cast<u32x2*>(q + q_plane + half) = h2;
-            } else {  // four consecutive channels are contiguous in a key tile
-                u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
-                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d)) = pack_elem4(rl);
-                *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), d + half)) = pack_elem4(rh);
-            }
-        } else {  // the value tiles keep eight SLOTS of one channel together: element stores
-            u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
+        for (int t = 0; t < 2; ++t) {
+            if (t >= nt) break;
+            const int band = tile * nt + t, head = band / bph;
+            const int d = (band - head * bph) * 8 + (c & 7);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                vp[v_cache_offset(D, plan.slot(m), d + i)] = f32_to_elem(lo[i]);
-                vp[v_cache_offset(D, plan.slot(m), d + half + i)] = f32_to_elem(hi[i]);
+                const int m = qi * 4 + i;
+                const bool rot = m < plan.M && head < Hq + Hkv;
+                p.cs[t][i] = rot ? rope_cos[m * half + d] : 1.f;
+                p.sn[t][i] = rot ? rope_sin[m * half + d] : 0.f;
+            }
+        }
+    }
+    // A lane holds rows 4*qi .. +3 of column c; the partner column is eight lanes away (same rows).
+    template <int NTT>
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT], const Pre& p, bool use_pre) const {
+        static_assert(NTT <= 2, "Pre holds the factors of two bands");
+        const bool upper = c >= 8;
+#pragma unroll
+        for (int t = 0; t < NTT; ++t) {
+            const int band = tile * NTT + t, head = band / bph;
+            const int d = (band - head * bph) * 8 + (c & 7);
+            const int ch = upper ? half + d : d;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = qi * 4 + i;
+                const float mine = v[t][i];
+                const float other = __shfl_xor(mine, 8, 64);  // both lanes of a pair are active together
+                if (m >= plan.M) continue;
+                if (head < Hq + Hkv) {
+                    const float cs = use_pre ? p.cs[t][i] : rope_cos[m * half + d];
+                    const float sn = use_pre ? p.sn[t][i] : rope_sin[m * half + d];
+                    const float r = upper ? mine * cs + other * sn : mine * cs - other * sn;
+                    if (head < Hq) {
+                        u16* q = q_out + (size_t)m * ldq + head * D + ch;
+                        const u16 r1 = f32_to_elem(r);
+                        q[0] = r1;
+                        q[q_plane] = f32_to_elem(r - elem_to_f32(r1));
+                    } else {
+                        u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
+                        kp[k_cache_offset(D, plan.slot(m), ch)] = f32_to_elem(r);
+                    }
+                } else {
+                    u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
+                    vp[v_cache_offset(D, plan.slot(m), ch)] = f32_to_elem(mine);
+                }
+            }
+        }
+    }
+    // A lane holds columns c4 .. c4+3 of row m; the partner columns are 32 lanes away (same row).
+    template <int NTT>
+    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[NTT]) const {
+        const bool upper = c4 >= 8;
+#pragma unroll
+        for (int t = 0; t < NTT; ++t) {
+            const int band = tile * NTT + t, head = band / bph;
+            const int d = (band - head * bph) * 8 + (c4 & 7);
+            const int ch = upper ? half + d : d;
+            const f32x4 mine = v[t];
+            f32x4 other;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(mine[i], 32, 64);
+            if (m >= plan.M) continue;
+            if (head < Hq + Hkv) {
+                const f32x4 cs = *reinterpret_cast<const f32x4*>(rope_cos + m * half + d);
+                const f32x4 sn = *reinterpret_cast<const f32x4*>(rope_sin + m * half + d);
+                const f32x4 r = upper ? mine * cs + other * sn : mine * cs - other * sn;
+                if (head < Hq) {
+                    u16* q = q_out + (size_t)m * ldq + head * D + ch;
+                    u32x2 r1, r2;
+                    split_elem4(r, r1, r2);
+                    *reinterpret_cast<u32x2*>(q) = r1;
+                    *reinterpret_cast<u32x2*>(q + q_plane) = r2;
+                } else {  // four consecutive channels are contiguous in a key tile
+                    u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
+                    *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), ch)) = pack_elem4(r);
+                }
+            } else {  // the value tiles keep eight SLOTS of one channel together: element stores
+                u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vp[v_cache_offset(D, plan.slot(m), ch + i)] = f32_to_elem(mine[i]);
             }
         }
     }

@@ -1,7 +1,7 @@
 // One-time repacking of row-major bf16 matrices into the MFMA-tile streaming layout of duo_gemm.h:
 // band b (16 rows), K step ks, lane l  ->  eight values row(b, l % 16), columns 32*ks + 8*(l/16) .. +8,
 // stored at element ((b * K/32 + ks) * 64 + l) * 8.  Which source rows make up band b is the packer's
-// choice: plain order, Q/K/V bands paired for the rotary embedding, gate/up bands interleaved.
+// choice: plain order, Q/K/V channels next to their rotary partners, gate/up bands interleaved.
 #pragma once
 #include "duo_common.h"
 
@@ -14,15 +14,14 @@ struct PlainRows {  // band b = rows 16b .. 16b+15; rows beyond N are zero
     }
 };
 
-struct QKVRows {  // band 2*w + s of workgroup tile w = (head, blk): rows s*D/2 + 16*blk .. of that head
+struct QKVRows {  // band (head, j): rows 0..7 are channels 8j .. 8j+7 of that head, rows 8..15 their rotary partners D/2 + 8j ..
     const u16* wq;
     const u16* wk;
     const u16* wv;
-    int Hq, Hkv, D, half, bph, K;
+    int Hq, Hkv, D, half, bph, K;  // bph = D/16 bands per head
     __device__ __forceinline__ const u16* row(int band, int c) const {
-        const int w = band >> 1, s = band & 1;
-        int head = w / bph;
-        const int r = s * half + (w - head * bph) * 16 + c;
+        int head = band / bph;
+        const int r = (band - head * bph) * 8 + (c & 7) + (c >= 8 ? half : 0);
         if (head < Hq) return wq + (size_t)(head * D + r) * K;
         head -= Hq;
         if (head < Hkv) return wk + (size_t)(head * D + r) * K;
