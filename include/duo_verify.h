@@ -90,7 +90,7 @@ typedef struct duo_weights {
  * model).  src matrices are row-major bf16, 16-byte aligned, K a multiple of 32.  dst needs
  * duo_packed_elems(N, K) uint16 elements: N is rounded up to a multiple of 32 rows, missing rows are
  * zero.  duo_pack_qkv needs duo_packed_elems((n_q_heads + 2*n_kv_heads)*head_dim, d_model) and orders
- * the bands so that the two halves of every rotary pair land in the same workgroup;
+ * the rows so that every band holds eight channels of a head next to their eight rotary partners;
  * duo_pack_gate_up needs duo_packed_elems(2*d_ff, d_model) and interleaves gate and up bands.
  */
 size_t duo_packed_elems(int N, int K);
