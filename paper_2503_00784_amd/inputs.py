@@ -73,6 +73,8 @@ LLAMA3_8B = ModelShape(32, 4096, 32, 8, 128, 14336, 128256, rope_theta=500000.0)
 MID = ModelShape(3, 512, 8, 2, 64, 1408, 4099)
 # one 7B-wide layer (GQA, heads of 128): the launch shapes a prompt chunk of ~1000 rows takes at full width
 WIDE1 = ModelShape(1, 4096, 32, 8, 128, 4096, 1000)
+# one layer of 7B width exactly (32 heads of 128 without GQA, d_ff 11008): the launch shapes of the benchmark step
+WIDE7 = ModelShape(1, 4096, 32, 32, 128, 11008, 1000)
 # one layer of 13B width (d_model 5120, 40 heads, d_ff 13824): band counts and K ranges other than the 7B/8B ones
 WIDE13 = ModelShape(1, 5120, 40, 40, 128, 13824, 1000)
 

@@ -384,6 +384,18 @@ def test_other_width_single_layer(B, n, k, root):
         _check_cache(eng, cache, cache.prefix_len)
 
 
+@pytest.mark.parametrize("n,k,root", [(1, 8, -1), (1, 7, 5), (4, 8, -1), (5, 16, -1), (2, 3, -1)])
+def test_7b_width_single_layer(B, n, k, root):
+    """One layer of 7B width: the launch shapes of the benchmark step (768 independent Q/K/V bands, one per wave up to
+    80 rows; gate/up and down at d_ff 11008) at 6, 8, 32 and 80 rows."""
+    shape = inputs.WIDE7
+    say(f"WIDE7 n={n} k={k} root={root}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, 300, 448, seed=17, synthetic_cache=True)
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=2 * n + k, mode=0, root_token=root)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len)
+
+
 @pytest.mark.parametrize("mode,root,top_p", [(0, -1, 0.8), (1, 12, 0.5), (0, 3, 0.95)])
 def test_mid_config_top_p_step(B, mode, root, top_p):
     """A whole step with nucleus sampling: logits against the oracle's forward pass, decisions against the oracle's
