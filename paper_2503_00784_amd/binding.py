@@ -83,6 +83,10 @@ def load(dtype: str = "bf16") -> C.CDLL:
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2503_00784_amd.build` "
                            "(there is no CPU fallback)")
+    # The device memory and the streams handed to the library are torch's, so the library has to bind to the HIP
+    # runtime that torch brought into the process; loading it first would bring in a second runtime (the system's),
+    # which then finds no device.
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     lib.duo_workspace_bytes.argtypes = [C.POINTER(ModelConfig), C.c_int, C.POINTER(C.c_size_t)]
     lib.duo_verify.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(KVCache), C.c_void_p, C.c_void_p,
