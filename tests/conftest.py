@@ -27,3 +27,11 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_libraries():
+    """The tests load what is built; only a tree with nothing built compiles here (about a minute)."""
+    from paper_2503_00784_amd import binding, build
+    if not all(os.path.exists(p) for p in binding.LIB_PATHS.values()):
+        build.build(verbose=False)
