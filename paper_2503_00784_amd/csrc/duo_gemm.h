@@ -790,8 +790,8 @@ static inline void launch_wide(const u16* X, const u16* W, int K, int tiles, int
 }
 
 // Up to eight rows (hi and lo halves in one operand tile): the same kernel pays for matrices of 257..768 workgroup
-// tiles (measured at 4096 input channels: 20.6 against 21.4 us for 384 tiles, 32.0 against 33.5 us for 688; not
-// for 1000 tiles).  Returns false when the caller should use gemm_skinny_kernel.
+// tiles (measured at 4096 input channels: 32.0 against 33.5 us for 688 tiles of two bands, 18.5 against 18.9 us for
+// 768 tiles of one band; not for 1000 tiles).  Returns false when the caller should use gemm_skinny_kernel.
 template <int NT, class Epi>
 static inline bool launch_wide_half(const u16* X, const u16* W, int K, int tiles, const RowScale& rsc, const Epi& epi,
                                     hipStream_t s) {
