@@ -54,7 +54,7 @@ struct Workspace {
     double* p_rows;  // nucleus search scratch [DUO_MAX_ROWS + 1][vocab]
     int32_t* acc;
     float* ssq;      // [Mp][d/16] partial sums of squares of the residual stream (for the next RMSNorm)
-    float* ssq_full; // [Mp] complete sums of squares (written by the one-workgroup-per-row producers)
+    float* ssq_full; // [Mp][RowScale::FULL_PARTS] sums of squares over column ranges (written by the few-workgroups-per-row producers)
     float* split;    // [splits][Mp][d] partial results of the K-split residual projections
     u16* h_last;     // many-row pass: the last row of h as an operand of its own (one tile per K step)
     size_t q_plane;  // elements between the two query planes
@@ -106,7 +106,7 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.rope_s = reinterpret_cast<float*>(take(Mp * (c.head_dim / 2) * 4));
     ws.logits = reinterpret_cast<float*>(take((many ? 16 : Mp) * V * 4));
     ws.ssq = reinterpret_cast<float*>(take(Mp * (d / 16) * 4));
-    ws.ssq_full = reinterpret_cast<float*>(take(Mp * 4));
+    ws.ssq_full = reinterpret_cast<float*>(take(Mp * RowScale::FULL_PARTS * 4));
     ws.split = reinterpret_cast<float*>(take((size_t)(many ? block_splits(max_rows, c.d_model) : WIDE_MAX_SPLIT) * Mp * d * 4));
     ws.h_last = reinterpret_cast<u16*>(take(16 * d * 2));
     carve_sampler(base, off, c.vocab, ws);
@@ -235,8 +235,7 @@ void launch_residual_projection(int M, const u16* X, const u16* W, int K, const 
         default: S = launch_wide_split<5>(X, W, K, d, M, split, none, s); break;
     }
     prof(DUO_PROF_RESID_REDUCE, s);
-    DUO_LAUNCH(residual_reduce_kernel, dim3(M), dim3(512), s, split, S, (size_t)M * d, er.X, er.gain, er.h, d, er.pair_rows,
-               er.h_tiles, er.ssq_part, ssq_full);
+    launch_residual_reduce(M, split, S, (size_t)M * d, er.X, er.gain, er.h, d, er.pair_rows, er.h_tiles, er.ssq_part, ssq_full, s);
 }
 
 template <int D>
@@ -372,7 +371,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     if (many) {
         prof(DUO_PROF_LMHEAD, s);
         DUO_LAUNCH(last_row_operand_kernel, dim3(d / 32), dim3(64), s, ws.h, M - 1, PR, AT, ws.h_last);
-        const RowScale last{ws.ssq + (size_t)(M - 1) * NP, NP, 1.0f / (float)d, c.rms_eps, down_split ? ws.ssq_full + (M - 1) : nullptr};
+        const RowScale last{ws.ssq + (size_t)(M - 1) * NP, NP, 1.0f / (float)d, c.rms_eps, down_split ? ws.ssq_full + (size_t)(M - 1) * RowScale::FULL_PARTS : nullptr};
         EpiStoreF32 el{V, 1, 2, logits, V};
         launch_projection<2>(DUO_PROF_LMHEAD, 1, ws.h_last, w.lm_head, d, (V + 31) / 32, last, el, s);
         return;

@@ -42,7 +42,15 @@ struct RowScale {
     const float* part;  // [rows][n_part] partial sums of squares, nullptr: operand is not normalised
     int n_part;         // multiple of 4, at most 512
     float inv_d, eps;
-    const float* full;  // [rows] complete sums of squares when the producer was one workgroup per row, else nullptr
+    // [rows][FULL_PARTS] sums of squares over FULL_PARTS equal column ranges of the row (unused ranges hold zero) when
+    // the producer was a few workgroups per row, else nullptr
+    const float* full;
+    static constexpr int FULL_PARTS = 8;
+    __device__ __forceinline__ float full_row(int m) const {  // fixed order
+        const f32x4 a = *reinterpret_cast<const f32x4*>(full + (size_t)m * FULL_PARTS);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(full + (size_t)m * FULL_PARTS + 4);
+        return ((a.x + a.y) + (a.z + a.w)) + ((b.x + b.y) + (b.z + b.w));
+    }
     static constexpr int MAXQ = 16;  // float4 loads per lane: 8 lanes x 16 x 4 = 512 partials per row
     // Eight rows at a time: lane = (row r0 + lane % 8, segment lane / 8); a lane adds its segment of the
     // row's partials in index order, the eight segments are then added by a fixed butterfly.  The loads
@@ -251,7 +259,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     const u32x4* xg = reinterpret_cast<const u32x4*>(X) + (size_t)k0 * MT * 64 + lane;
 
     if (rsc.full) {
-        for (int m = threadIdx.x; m < quads * 4; m += NTH) row_scale[m] = 1.0f / sqrtf(rsc.full[m] * rsc.inv_d + rsc.eps);
+        for (int m = threadIdx.x; m < quads * 4; m += NTH) row_scale[m] = 1.0f / sqrtf(rsc.full_row(m) * rsc.inv_d + rsc.eps);
     } else if (rsc.part) {
         const int nrows = quads * 4;
         f32x4 rsv[RowScale::MAXQ];

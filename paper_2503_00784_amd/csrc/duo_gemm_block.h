@@ -45,7 +45,7 @@ __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__
     if (rsc.full) {
         for (int i = threadIdx.x; i < BMT * 16; i += 320) {
             const int m = row0 + i;
-            row_scale[i] = m < nrows ? 1.0f / sqrtf(rsc.full[m] * rsc.inv_d + rsc.eps) : 0.f;
+            row_scale[i] = m < nrows ? 1.0f / sqrtf(rsc.full_row(m) * rsc.inv_d + rsc.eps) : 0.f;
         }
     } else if (rsc.part) {
         f32x4 rsv[RowScale::MAXQ];

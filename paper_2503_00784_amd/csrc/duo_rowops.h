@@ -60,23 +60,26 @@ __global__ __launch_bounds__(256) void embed_kernel(const u16* __restrict__ embe
         sq += __shfl_xor(sq, 1, 64);  // two runs of eight = one 16-column tile
         if (!(threadIdx.x & 1)) ssq_part[(size_t)m * (d >> 4) + (j8 >> 4)] = sq;
     }
-    block_row_sum<4>(total, wsum, ssq_full + m);
+    block_row_sum<4>(total, wsum, ssq_full + (size_t)m * RowScale::FULL_PARTS);  // one range: the whole row
+    if (threadIdx.x >= 1 && threadIdx.x < RowScale::FULL_PARTS) ssq_full[(size_t)m * RowScale::FULL_PARTS + threadIdx.x] = 0.f;
 }
 
 // Second half of a residual projection whose K range was split over workgroups: x[m] += sum of the S
 // partial results (added in split order), then what EpiResidual does for the next RMSNorm: u = x * gain
-// as bf16 pairs in operand layout and the partial sums of x^2 per 16-column tile, plus, because one
-// workgroup sees the whole row, the row's complete sum of squares.
-// One workgroup (512 threads) per row, eight consecutive channels per thread and turn; the loads of all
+// as bf16 pairs in operand layout and the partial sums of x^2 per 16-column tile, plus the sum of squares over this
+// workgroup's whole column range (RowScale::full), which the consumer reads instead of 256 partials per row.
+// grid = (rows, P): workgroup (m, pt) takes columns pt * d/P .. of row m (d/P a multiple of 64; P <= FULL_PARTS),
+// NWV waves, eight consecutive channels per thread and turn; the loads of all
 // splits are issued together (S <= 8, indices beyond S re-read the last split and are not added).
-__global__ __launch_bounds__(512) void residual_reduce_kernel(const float* __restrict__ part, int S, size_t split_stride,
-                                                               float* __restrict__ x, const u16* __restrict__ gain,
-                                                               u16* __restrict__ h, int d, int pair_rows, int tiles,
-                                                               float* __restrict__ ssq_part, float* __restrict__ ssq_full) {
-    __shared__ float wsum[8];
-    const int m = blockIdx.x;
+template <int NWV>
+__global__ __launch_bounds__(NWV * 64) void residual_reduce_kernel(const float* __restrict__ part, int S, size_t split_stride,
+                                                                   float* __restrict__ x, const u16* __restrict__ gain,
+                                                                   u16* __restrict__ h, int d, int pair_rows, int tiles,
+                                                                   float* __restrict__ ssq_part, float* __restrict__ ssq_full) {
+    __shared__ float wsum[NWV];
+    const int m = blockIdx.x, P = gridDim.y, cols = d / P, c0 = blockIdx.y * cols;
     float total = 0.f;
-    for (int j8 = threadIdx.x * 8; j8 < d; j8 += 512 * 8) {  // d is a multiple of 64: lanes leave in pairs
+    for (int j8 = c0 + threadIdx.x * 8; j8 < c0 + cols; j8 += NWV * 64 * 8) {  // lanes leave in pairs
         float* xr = x + (size_t)m * d + j8;
         const float* pr = part + (size_t)m * d + j8;
         f32x4 p0[8], p1[8];
@@ -113,7 +116,26 @@ __global__ __launch_bounds__(512) void residual_reduce_kernel(const float* __res
         sq += __shfl_xor(sq, 1, 64);
         if (!(threadIdx.x & 1)) ssq_part[(size_t)m * (d >> 4) + (j8 >> 4)] = sq;
     }
-    block_row_sum<8>(total, wsum, ssq_full + m);
+    block_row_sum<NWV>(total, wsum, ssq_full + (size_t)m * RowScale::FULL_PARTS + blockIdx.y);
+    if (blockIdx.y == 0 && (int)threadIdx.x >= P && threadIdx.x < RowScale::FULL_PARTS)
+        ssq_full[(size_t)m * RowScale::FULL_PARTS + threadIdx.x] = 0.f;  // unused ranges
+}
+
+// Column ranges per row for residual_reduce_kernel: enough workgroups to fill the chip when there are few rows.
+static inline int reduce_parts(int M, int d) {
+    int P = M <= 32 ? 8 : (M <= 80 ? 4 : (M < 256 ? 2 : 1));
+    while (P > 1 && d % (P * 64) != 0) P >>= 1;
+    return P;
+}
+static inline void launch_residual_reduce(int M, const float* part, int S, size_t split_stride, float* x, const u16* gain,
+                                          u16* h, int d, int pair_rows, int tiles, float* ssq_part, float* ssq_full,
+                                          hipStream_t s) {
+    const int P = reduce_parts(M, d), cols = d / P;
+    const dim3 grid(M, P);
+    if (cols <= 512) DUO_LAUNCH(residual_reduce_kernel<1>, grid, dim3(64), s, part, S, split_stride, x, gain, h, d, pair_rows, tiles, ssq_part, ssq_full);
+    else if (cols <= 1024) DUO_LAUNCH(residual_reduce_kernel<2>, grid, dim3(128), s, part, S, split_stride, x, gain, h, d, pair_rows, tiles, ssq_part, ssq_full);
+    else if (cols <= 2048) DUO_LAUNCH(residual_reduce_kernel<4>, grid, dim3(256), s, part, S, split_stride, x, gain, h, d, pair_rows, tiles, ssq_part, ssq_full);
+    else DUO_LAUNCH(residual_reduce_kernel<8>, grid, dim3(512), s, part, S, split_stride, x, gain, h, d, pair_rows, tiles, ssq_part, ssq_full);
 }
 
 // cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.  As the first kernel of a
