@@ -3,8 +3,8 @@
  * (arxiv 2503.00784).
  *
  * One call scores n draft sequences of k tokens with the target model in a single forward
- * pass (Alg. 1, right column: p <- M_p(x); Sec. 1 "evaluates all candidate tokens in a single
- * forward pass"), the sequences being independent branches of a shared prefix (Sec. 3.2,
+ * pass (Alg. 1, right column: p <- M_p(x); Sec. 1: all candidates are scored by one pass of the
+ * target), the sequences being independent branches of a shared prefix (Sec. 3.2,
  * Fig. 2), then verifies them by speculative sampling (Alg. 2, Sec. 3.3) and commits the
  * accepted tokens' keys and values to the cache.  The draft model, the draft budget and the
  * CPU/GPU scheduling of Alg. 1 are host work and not part of this library: draft tokens,
@@ -49,7 +49,11 @@ extern "C" {
 #define DUO_MAX_PREFILL_ROWS 1024 /* rows of one duo_prefill_chunk call */
 
 /* Bits of the device-side status word (duo_result.status), set by kernels that cannot be
- * checked on the host without a synchronisation. */
+ * checked on the host without a synchronisation.  A call whose status word is not clean FAILED ON THE DEVICE and
+ * commits nothing: *cache.prefix_len and every cache slot below it are left exactly as they were (on a prefix
+ * mismatch the pass writes no keys or values at all; slots at and above the device's prefix length are scratch in any
+ * case), root_logits is not replaced by duo_prefill_chunk, and the commit record reads
+ * {-1, 0, -1, unchanged prefix length}.  accept_len / next_token / logits_out then hold no usable result. */
 #define DUO_STATUS_TOKEN_CLAMPED   1  /* a draft token id was outside [0, vocab) and was clamped */
 #define DUO_STATUS_PREFIX_MISMATCH 2  /* *cache.prefix_len differed from call.host_prefix_len */
 
@@ -169,8 +173,8 @@ int duo_workspace_bytes(const duo_model_config *cfg, int max_rows, size_t *bytes
  *
  * Speculative sampling (Alg. 2; accept iff u * q(t) < p(t), i.e. with probability
  * min(1, p/q); on rejection sample norm(max(0, p - q)) by inverse CDF over ascending ids):
- *   INDEPENDENT_LONGEST  every sequence is verified on its own (Sec. 3.3, "same procedure as
- *                        speculative sampling"); the longest (lowest index on ties) is committed.
+ *   INDEPENDENT_LONGEST  every sequence is verified on its own, token by token, as one sequence is in plain
+ *                        speculative sampling (Sec. 3.3); the longest (lowest index on ties) is committed.
  *   PAPER_SEQUENTIAL     first tokens are tested in order against the root distribution, which
  *                        is replaced by its normalised residual after each rejection (Alg. 2,
  *                        multi-sequence block); the first accepted sequence is verified to its
@@ -231,6 +235,10 @@ int duo_spec_sample(const float *logits, const float *root_logits, int vocab,
  * 0: then the pointers may be NULL and the last case applies).  call->n must be 1, call->k = l,
  * call->select_mode must hold a valid value and is otherwise ignored, root_token / host_prefix_len as in
  * duo_verify; s <= DUO_MAX_ROWS.
+ * l = 0 is the round after a rejection (Alg. 2 then leaves no unverified suffix) and the first round after the
+ * prompt: unverified_tokens / unverified_probs may be NULL, uniforms holds the one uniform of the final draw, and
+ * the new sequences are judged by the distribution after the root token (the pass scores that one row), or, with
+ * root_token < 0, by cache.root_logits without any forward pass.
  * Outputs: out->accept_len[0] = number of accepted suffix tokens a (0..l); out->commit =
  * {index of the accepted new sequence or -1, a, emitted token or -1 when a sequence was accepted,
  * new prefix length P + R + a}; out->next_token[0] = the emitted token or -1.  The keys/values of
@@ -287,8 +295,10 @@ int duo_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, int sin
  * duo_prefill_chunk launch carries a start and a stop HIP event that take the dispatch's own begin and
  * end timestamps; duo_profile_read waits for them, adds each kernel's duration to its class, returns
  * the sums (milliseconds) and launch counts accumulated since the last read, and resets them.
- * Enabling allocates a pool of events, and at most 4096 launches are recorded between two reads; a
- * call made while profiling is therefore not allocation-free or capturable.  Not thread-safe.
+ * Enabling allocates a pool of events, and at most 8192 launches are recorded between two reads (a 64-row step is
+ * about 260); duo_profile_dropped returns how many launches since the last read (or enable) found the pool
+ * empty and went untimed -- call it before duo_profile_read, which resets it.  A call made while profiling is
+ * not allocation-free or capturable.  Not thread-safe.
  * ms and launches are HOST arrays of DUO_PROF_CLASSES entries.
  */
 #define DUO_PROF_SETUP     0  /* rotary table, embedding gather + first RMSNorm */
@@ -305,6 +315,11 @@ int duo_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, int sin
 #define DUO_PROF_CLASSES   11
 int duo_profile_enable(int enable);
 int duo_profile_read(double *ms, int32_t *launches);
+int duo_profile_dropped(void);
+/* Name, with template arguments as a kernel trace prints them, of the projection kernel most recently launched under
+ * class `cls` while the timer was enabled ("" if none, or if that class's kernels are not named); HOST string, valid until
+ * the next profiled launch of the class.  It lets a timing be matched with profiler counter summaries of that kernel. */
+const char *duo_profile_kernel_name(int cls);
 
 const char *duo_status_string(int code);
 const char *duo_last_hip_error(void);

@@ -13,7 +13,7 @@ What it computes
     (RMSNorm, rotary embedding with half-split pairs, grouped-query attention, SwiGLU),
     the architecture of the paper's targets (Sec. 4.1 "Models").
   * `speculative_verify`: Alg. 2 recast for one fused call -- chain verification of a
-    sequence (the "same procedure as speculative sampling" of Sec. 3.3) and the
+    sequence (token by token, as plain speculative sampling verifies one: Sec. 3.3) and the
     sequential first-token test over s sequences with residual updates (Alg. 2, the
     "verify multi-sequence drafts" block), including the all-rejected case.
   * `duodec_verify_alg2`: Alg. 2 in the paper's own deferred form (unverified suffix first,

@@ -25,9 +25,10 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm", "duo_block_gemm", "duo_stream_read_probe", "duo_k_cache_offset",
+           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm",
+           "duo_block_gemm", "duo_stream_read_probe", "duo_k_cache_offset",
            "duo_v_cache_offset", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
-           "duo_profile_read", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
+           "duo_profile_read", "duo_profile_dropped", "duo_profile_kernel_name", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
 PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "residual_reduce", "gate_up_swiglu", "down_proj", "lm_head",
                 "sample", "commit"]
@@ -96,6 +97,10 @@ def load(dtype: str = "bf16") -> C.CDLL:
     lib.duo_sample_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     lib.duo_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Call),
                                     C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_profile_dropped.argtypes = []
+    lib.duo_profile_dropped.restype = C.c_int
+    lib.duo_profile_kernel_name.argtypes = [C.c_int]
+    lib.duo_profile_kernel_name.restype = C.c_char_p
     lib.duo_verify_deferred.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(KVCache), C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                         C.POINTER(Call), C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -146,6 +151,18 @@ def _check(code: int, where: str) -> None:
 
 def profile_enable(on: bool, dtype: str = "bf16") -> None:
     _check(load(dtype).duo_profile_enable(1 if on else 0), "duo_profile_enable")
+
+
+def profile_dropped(dtype: str = "bf16") -> int:
+    """Launches since the last read that went untimed because the event pool was empty (ask before profile_read)."""
+    return int(load(dtype).duo_profile_dropped())
+
+
+def profile_kernel_names(dtype: str = "bf16") -> Dict[str, str]:
+    """{class: name of the kernel last launched under it while profiling} for the classes whose kernels are named."""
+    lib = load(dtype)
+    names = {c: lib.duo_profile_kernel_name(i).decode() for i, c in enumerate(PROF_CLASSES)}
+    return {c: n for c, n in names.items() if n}
 
 
 def profile_read(dtype: str = "bf16") -> Dict[str, Dict[str, float]]:
@@ -374,13 +391,14 @@ class VerifyEngine:
         """Enqueue one round of Alg. 2 as listed (duo_verify_deferred) on torch's current stream.
         unverified_tokens int32 [l], unverified_probs fp32 [l][V], uniforms fp32 [l+1]; first_tokens int32 [s],
         first_probs fp32 [s][V], uniforms_first fp32 [s] (all three None for s = 0)."""
-        l = int(unverified_tokens.shape[0])
+        l = 0 if unverified_tokens is None else int(unverified_tokens.shape[0])  # None: an empty suffix
         s_new = 0 if first_tokens is None else int(first_tokens.shape[0])
         call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, int(root_token), self.host_prefix_len, float(top_p))
         res = Result(self.accept_len.data_ptr(), self.next_token.data_ptr(), self.commit.data_ptr(),
                      self.status.data_ptr(), _ptr(logits_out))
         rc = self.lib.duo_verify_deferred(C.byref(self.cfg), C.byref(self.weights.c), C.byref(self.cache_c),
-                                          unverified_tokens.data_ptr(), unverified_probs.data_ptr(), uniforms.data_ptr(),
+                                          _ptr(unverified_tokens) if l else None, _ptr(unverified_probs) if l else None,
+                                          uniforms.data_ptr(),
                                           _ptr(first_tokens), _ptr(first_probs), _ptr(uniforms_first), s_new,
                                           C.byref(call), C.byref(res), self.workspace.data_ptr(), self.ws_bytes,
                                           _stream_ptr())
@@ -428,15 +446,16 @@ def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temper
 def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, uniforms, first_tokens=None,
                     first_probs=None, uniforms_first=None, temperature: float = 1.0, has_root: bool = False,
                     prefix_len: int = 0, top_p: float = 0.0) -> Dict[str, object]:
-    """duo_deferred_sample on device tensors; returns host results."""
+    """duo_deferred_sample on device tensors; returns host results.  An empty suffix: unverified_tokens None (logits then
+    holds the root row only, or may be None without a root); `vocab` is then taken from root_logits."""
     import torch
     lib = load()
-    l = int(unverified_tokens.shape[0])
+    l = 0 if unverified_tokens is None else int(unverified_tokens.shape[0])
     s_new = 0 if first_tokens is None else int(first_tokens.shape[0])
-    vocab = logits.shape[-1]
+    vocab = (logits if logits is not None else root_logits).shape[-1]
     nbytes = C.c_size_t(0)
     _check(lib.duo_sample_workspace_bytes(vocab, 1, l, C.byref(nbytes)), "duo_sample_workspace_bytes")
-    dev = logits.device
+    dev = (logits if logits is not None else root_logits).device
     ws = torch.empty(nbytes.value, dtype=torch.uint8, device=dev)
     accept_len = torch.zeros(1, dtype=torch.int32, device=dev)
     next_token = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -444,8 +463,8 @@ def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, un
     status = torch.zeros(1, dtype=torch.int32, device=dev)
     call = Call(1, l, float(temperature), SELECT_PAPER_SEQUENTIAL, 0 if has_root else -1, int(prefix_len), float(top_p))
     res = Result(accept_len.data_ptr(), next_token.data_ptr(), commit.data_ptr(), status.data_ptr(), None)
-    rc = lib.duo_deferred_sample(logits.data_ptr(), _ptr(root_logits), vocab, unverified_tokens.data_ptr(),
-                                 unverified_probs.data_ptr(), uniforms.data_ptr(), _ptr(first_tokens), _ptr(first_probs),
+    rc = lib.duo_deferred_sample(_ptr(logits), _ptr(root_logits), vocab, _ptr(unverified_tokens) if l else None,
+                                 _ptr(unverified_probs) if l else None, uniforms.data_ptr(), _ptr(first_tokens), _ptr(first_probs),
                                  _ptr(uniforms_first), s_new, C.byref(call), C.byref(res), ws.data_ptr(), nbytes.value,
                                  _stream_ptr())
     _check(rc, "duo_deferred_sample")

@@ -21,6 +21,12 @@ namespace {
 
 thread_local char g_hip_err[256] = "";
 
+int hip_ok(hipError_t e, const char* what) {
+    if (e == hipSuccess) return DUO_OK;
+    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
+    return DUO_ERR_HIP;
+}
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -146,23 +152,24 @@ struct Profiler {
     std::vector<hipEvent_t> ev;  // pairs: start, stop
     std::vector<int> cls;        // class of pair i
     size_t used = 0;             // pairs in use
+    size_t dropped = 0;          // launches since the last read that found the pool empty
+    char names[DUO_PROF_CLASSES][128] = {};  // per class: the kernel last launched under it, as its launch helper spelled it
 };
 Profiler g_prof;
-constexpr size_t PROF_POOL = 4096;  // pairs
+constexpr size_t PROF_POOL = 8192;  // pairs
 
 // Called right before a launch of class `cls`: arms DUO_LAUNCH with the next event pair.
 inline void prof(int cls, hipStream_t) {
-    if (!g_prof.on || cls < 0 || g_prof.used >= g_prof.cls.size()) return;
+    if (!g_prof.on || cls < 0) return;
+    if (g_prof.used >= g_prof.cls.size()) {
+        ++g_prof.dropped;
+        return;
+    }
     g_launch_events.start = g_prof.ev[2 * g_prof.used];
     g_launch_events.stop = g_prof.ev[2 * g_prof.used + 1];
+    g_launch_events.name = cls < DUO_PROF_CLASSES ? g_prof.names[cls] : nullptr;
     g_prof.cls[g_prof.used] = cls;
     ++g_prof.used;
-}
-
-int hip_ok(hipError_t e, const char* what) {
-    if (e == hipSuccess) return DUO_OK;
-    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
-    return DUO_ERR_HIP;
 }
 
 template <int D>
@@ -331,7 +338,8 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * c.max_seq * D;
-        EpiQKV eq{Hq, Hkv, D, half, D / 16, qkv_nt, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan};
+        EpiQKV eq{Hq, Hkv, D, half, D / 16, qkv_nt, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan,
+                  cache.prefix_len, 1};
         const RowScale& qkv_norm = (l == 0 || down_split) ? norm_full : norm_part;
         if (qkv_nt == 1) launch_projection<1>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands, qkv_norm, eq, s);
         else launch_projection<2>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands / 2, qkv_norm, eq, s);
@@ -410,15 +418,16 @@ void enqueue_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, in
         else DUO_LAUNCH(sample_paper_kernel<false>, dim3(1), dim3(SAMPLE_THREADS), s, sa);
     }
     CommitArgs ca{kc, vc, c ? c->n_kv_heads : 1, c ? c->head_dim : 0, c ? c->max_seq : 0, sa.P, sa.R, sa.n, sa.k, mode,
-                  sa.accept_len, sa.next_token, sa.commit, prefix_len};
+                  sa.accept_len, sa.next_token, sa.commit, prefix_len, sa.status};
     const dim3 grid = kc ? dim3(c->n_kv_heads, c->n_layers) : dim3(1, 1);
     prof(DUO_PROF_COMMIT, s);
     DUO_LAUNCH(commit_kernel, grid, dim3(256), s, ca);
 }
 
-int check_call(const duo_call* call, int vocab) {
+// min_k: 1 for the fused step; 0 for the deferred form, whose unverified suffix may be empty
+int check_call(const duo_call* call, int vocab, int min_k = 1) {
     if (!call) return DUO_ERR_NULL;
-    if (call->n < 1 || call->k < 1) return DUO_ERR_SHAPE;
+    if (call->n < 1 || call->k < min_k) return DUO_ERR_SHAPE;
     const int R = call->root_token >= 0 ? 1 : 0;
     if ((long long)call->n * call->k + R > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
     if (!(call->temperature >= 0.f)) return DUO_ERR_ARG;  // 0 is the greedy limit; NaN fails the comparison
@@ -501,13 +510,13 @@ int duo_prefill_chunk(const duo_model_config* cfg, const duo_weights* w, duo_kv_
     enqueue_forward(*cfg, *w, *cache, tokens, -1, plan, ws, ws.logits, status, s);
     DUO_LAUNCH(prefill_finish_kernel, dim3((cfg->vocab + 255) / 256), dim3(256), s,
                        ws.logits + (m > DUO_MAX_ROWS ? 0 : (size_t)(m - 1) * cfg->vocab), cache->root_logits, cfg->vocab, cache->prefix_len,
-                       host_prefix_len + m);
+                       host_prefix_len + m, status);
     return hip_ok(hipGetLastError(), "duo_prefill_chunk launch");
 }
 
 int duo_sample_workspace_bytes(int vocab, int n, int k, size_t* bytes) {
     if (!bytes) return DUO_ERR_NULL;
-    if (vocab < 2 || n < 1 || k < 1 || (long long)n * k + 1 > DUO_MAX_ROWS + 1) return DUO_ERR_SHAPE;
+    if (vocab < 2 || n < 1 || k < 0 || (long long)n * k + 1 > DUO_MAX_ROWS + 1) return DUO_ERR_SHAPE;
     *bytes = sample_ws_bytes(vocab);
     return DUO_OK;
 }
@@ -540,7 +549,7 @@ int duo_spec_sample(const float* logits, const float* root_logits, int vocab, co
 // checks shared by the two deferred entry points
 static int check_deferred(const duo_call* call, int vocab, const int32_t* first_tokens, const float* first_probs,
                           const float* uniforms_first, int s) {
-    int rc = check_call(call, vocab);
+    int rc = check_call(call, vocab, 0);
     if (rc) return rc;
     if (call->n != 1) return DUO_ERR_SHAPE;
     if (s < 0 || s > DUO_MAX_ROWS) return DUO_ERR_SHAPE;
@@ -565,10 +574,9 @@ int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_k
     int rc = check_config(cfg);
     if (rc) return rc;
     if ((rc = check_weights(cfg, w))) return rc;
-    if (!cache || !cache->k || !cache->v || !cache->prefix_len || !unverified_tokens || !unverified_probs || !uniforms ||
-        !workspace)
-        return DUO_ERR_NULL;
+    if (!cache || !cache->k || !cache->v || !cache->prefix_len || !uniforms || !workspace) return DUO_ERR_NULL;
     if ((rc = check_deferred(call, cfg->vocab, first_tokens, first_probs, uniforms_first, s_new))) return rc;
+    if (call->k > 0 && (!unverified_tokens || !unverified_probs)) return DUO_ERR_NULL;  // an empty suffix needs neither
     if ((rc = check_result(out))) return rc;
     const int R = call->root_token >= 0 ? 1 : 0;
     if (!R && !cache->root_logits) return DUO_ERR_NULL;
@@ -577,14 +585,20 @@ int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_k
     if (!aligned16(cache->k) || !aligned16(cache->v) || !aligned16(workspace) || !aligned16(unverified_probs) ||
         (out->logits_out && !aligned16(out->logits_out)))
         return DUO_ERR_ALIGN;
-    const Workspace ws = carve(*cfg, M, workspace);
+    const Workspace ws = carve(*cfg, M > 0 ? M : 1, workspace);
     if (workspace_bytes < ws.total) return DUO_ERR_WORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
-    const RowPlan plan{call->host_prefix_len, R, 1, call->k, M};  // the pass's first kernel clears *status
     float* logits = out->logits_out ? out->logits_out : ws.logits;
-    enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s);
+    if (M > 0) {
+        // an empty suffix leaves the root token as the pass's only row (the plan's k is then never used as a divisor)
+        const RowPlan plan{call->host_prefix_len, R, 1, call->k > 0 ? call->k : 1, M};  // the pass's first kernel clears *status
+        enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s);
+    } else {
+        // nothing to score: the cached root logits judge the new sequences; only the device-side input check runs
+        DUO_LAUNCH(status_init_kernel, dim3(1), dim3(64), s, out->status, cache->prefix_len, call->host_prefix_len);
+    }
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, 1, call->k, R, call->host_prefix_len,
                   (double)call->temperature, unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run,
                   out->accept_len, out->next_token, out->commit, out->status,
@@ -602,8 +616,8 @@ int duo_deferred_sample(const float* logits, const float* root_logits, int vocab
     if (rc) return rc;
     if ((rc = check_result(out))) return rc;
     const int R = call->root_token >= 0 ? 1 : 0;
-    if (!logits || !unverified_tokens || !unverified_probs || !uniforms || !workspace || (!R && !root_logits))
-        return DUO_ERR_NULL;
+    if (!uniforms || !workspace || (!R && !root_logits) || (R + call->k > 0 && !logits)) return DUO_ERR_NULL;
+    if (call->k > 0 && (!unverified_tokens || !unverified_probs)) return DUO_ERR_NULL;
     if (!aligned16(workspace)) return DUO_ERR_ALIGN;
     if (workspace_bytes < sample_ws_bytes(vocab)) return DUO_ERR_WORKSPACE;
     Workspace ws{};
@@ -721,9 +735,14 @@ int duo_profile_enable(int enable) {
     }
     g_prof.on = enable != 0;
     g_prof.used = 0;
+    g_prof.dropped = 0;
     g_launch_events = LaunchEvents{};
     return DUO_OK;
 }
+
+int duo_profile_dropped(void) { return (int)g_prof.dropped; }
+
+const char* duo_profile_kernel_name(int cls) { return (cls >= 0 && cls < DUO_PROF_CLASSES) ? g_prof.names[cls] : ""; }
 
 int duo_profile_read(double* ms, int32_t* launches) {
     if (!ms || !launches) return DUO_ERR_NULL;
@@ -740,6 +759,7 @@ int duo_profile_read(double* ms, int32_t* launches) {
         launches[g_prof.cls[i]] += 1;
     }
     g_prof.used = 0;
+    g_prof.dropped = 0;
     return DUO_OK;
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <stdint.h>
+#include <stdio.h>
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16;
@@ -13,8 +14,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // begin and end timestamps, the same clock a kernel trace reads; otherwise it is a plain launch.
 struct LaunchEvents {
     hipEvent_t start = nullptr, stop = nullptr;
+    char* name = nullptr;  // armed: 128 bytes where the launch helper may leave the kernel's name with its template arguments
 };
 static LaunchEvents g_launch_events;
+// The kernel about to be launched, spelled as a kernel trace prints it (e.g. "gemm_wide_kernel<4, 2, 3, 1, 8, 4, EpiSwiGLU, false>"),
+// so that a timing taken here can be matched with counter summaries taken by a profiler.  No effect unless the timer is armed.
+#define DUO_KERNEL_NAME(...)                                                               \
+    do {                                                                                   \
+        if (g_launch_events.name) snprintf(g_launch_events.name, 128, __VA_ARGS__);        \
+    } while (0)
 #define DUO_LAUNCH(kernel, grid, block, stream, ...)                                                            \
     do {                                                                                                        \
         if (g_launch_events.start) {                                                                            \

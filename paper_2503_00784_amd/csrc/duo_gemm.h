@@ -135,6 +135,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
     // What the epilogue will read from memory (residual values, gains, rotary factors) is requested now,
     // for the first output quad of each thread, so that its latency hides behind the weight stream.
     typename Epi::Pre pre;
+    epi.arm();
     const bool has_pre = (int)threadIdx.x < quads * 16;
     if (has_pre) epi.prefetch(tile, threadIdx.x >> 4, threadIdx.x & 15, pre);
     // Per-row RMSNorm factors of the operand (see RowScale): the partial sums of the wave's first eight
@@ -333,6 +334,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
         }
     };
     typename Epi::Pre pre;
+    epi.arm();
     const int first_mh = NK > 1 ? nk : 0;  // the first row tile this wave finishes
     const bool has_pre = HALF && live && first_mh < MH && first_mh * 4 + (lane >> 4) < quads;  // store4 takes none
     if (has_pre) epi.prefetch(tile, first_mh * 4 + (lane >> 4), lane & 15, pre);
@@ -449,6 +451,8 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
 // store4(tile, m, c4, v): v[t][i] is the sum for row m, column c4 + i of tile slot t (c4 = 0, 4, 8, 12): what a
 // lane holds when the weights are the first MFMA operand.  Four consecutive columns are 16 bytes of an fp32
 // row and 8 bytes (half a 16-byte chunk) of a bf16 operand buffer, so the stores are vectors.
+// arm(): called once by every consumer wave before the weight stream starts; an epilogue that depends on device
+// state reads it here, so that its latency hides behind the stream.
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // four floats -> hi = bf16(x) and lo = bf16(x - hi), four bf16 values (8 bytes) each
@@ -465,11 +469,13 @@ __device__ __forceinline__ u32x2 pack_elem4(const f32x4& x) {
 }
 
 struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile*NT + t)*16 .. +16 of W
+    static constexpr const char* NAME = "EpiStoreF32";
     int N, M, NT;
     float* Y;
     int ldy;
     size_t split_stride;  // elements between the outputs of two K splits (grid y); 0 when K is not split
     struct Pre {};
+    __device__ __forceinline__ void arm() {}
     __device__ __forceinline__ void prefetch(int, int, int, Pre&) const {}
     template <int NTT>
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT], const Pre&, bool) const {
@@ -507,6 +513,7 @@ struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile
 // prepares the next RMSNorm (see RowScale): u = x * gain as a bf16 pair into the next projection's
 // operand buffer, and the tile's partial sum of x^2 per row.  One band per workgroup (NT = 1).
 struct EpiResidual {
+    static constexpr const char* NAME = "EpiResidual";
     int N, M;
     float* X;
     int ldx;
@@ -517,6 +524,7 @@ struct EpiResidual {
     struct Pre {
         float x[4], g;
     };
+    __device__ __forceinline__ void arm() {}
     __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
         const int n = tile * 16 + c;
         p.g = elem_to_f32(gain[n]);
@@ -578,10 +586,12 @@ struct EpiResidual {
 // band 0 = gate rows tile*16.., band 1 = up rows tile*16..; act[m][n] = silu(gate) * up, written as a
 // bf16 pair straight into the down projection's operand buffer (row m hi, row pair_rows + m lo)
 struct EpiSwiGLU {
+    static constexpr const char* NAME = "EpiSwiGLU";
     int F, M;
     u16* act;
     int act_tiles, pair_rows;
     struct Pre {};
+    __device__ __forceinline__ void arm() {}
     __device__ __forceinline__ void prefetch(int, int, int, Pre&) const {}
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[2], const Pre&, bool) const {
         const int n = tile * 16 + c;
@@ -616,6 +626,7 @@ struct EpiSwiGLU {
 // bands are independent of each other.  Q goes to the query buffer as a pair of planes (hi, lo), K (rotated) and V
 // into their cache slots (tiled layouts, see k_cache_offset / v_cache_offset).
 struct EpiQKV {
+    static constexpr const char* NAME = "EpiQKV";
     int Hq, Hkv, D, half, bph;  // bph = D/16 bands per head
     int nt;                     // bands per workgroup tile of the launch that uses this epilogue (1 or 2)
     u16* q_out;  // hi plane; the lo plane starts q_plane elements further on
@@ -627,9 +638,15 @@ struct EpiQKV {
     const float* rope_cos;  // [rows][D/2]
     const float* rope_sin;
     RowPlan plan;
+    // The device's own prefix length (may be nullptr: no check).  The rows of this pass go to cache slots plan.P ..;
+    // if the host's prefix length is not the device's, those slots may hold committed keys and values, so nothing is
+    // written to the cache (the pass is flagged DUO_STATUS_PREFIX_MISMATCH by its first kernel and commits nothing).
+    const int32_t* dev_prefix_len;
+    int cache_ok;  // set by arm()
     struct Pre {
         float cs[2][4], sn[2][4];
     };
+    __device__ __forceinline__ void arm() { cache_ok = !dev_prefix_len || *dev_prefix_len == plan.P; }
     // Column c of band (head, j) is channel 8j + c (c < 8) or its rotary partner D/2 + 8j + c - 8.
     __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
 #pragma unroll
@@ -671,11 +688,11 @@ struct EpiQKV {
                         const u16 r1 = f32_to_elem(r);
                         q[0] = r1;
                         q[q_plane] = f32_to_elem(r - elem_to_f32(r1));
-                    } else {
+                    } else if (cache_ok) {
                         u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
                         kp[k_cache_offset(D, plan.slot(m), ch)] = f32_to_elem(r);
                     }
-                } else {
+                } else if (cache_ok) {
                     u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
                     vp[v_cache_offset(D, plan.slot(m), ch)] = f32_to_elem(mine);
                 }
@@ -706,11 +723,11 @@ struct EpiQKV {
                     split_elem4(r, r1, r2);
                     *reinterpret_cast<u32x2*>(q) = r1;
                     *reinterpret_cast<u32x2*>(q + q_plane) = r2;
-                } else {  // four consecutive channels are contiguous in a key tile
+                } else if (cache_ok) {  // four consecutive channels are contiguous in a key tile
                     u16* kp = kc + (size_t)(head - Hq) * max_seq * D;
                     *reinterpret_cast<u32x2*>(kp + k_cache_offset(D, plan.slot(m), ch)) = pack_elem4(r);
                 }
-            } else {  // the value tiles keep eight SLOTS of one channel together: element stores
+            } else if (cache_ok) {  // the value tiles keep eight SLOTS of one channel together: element stores
                 u16* vp = vc + (size_t)(head - Hq - Hkv) * max_seq * D;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) vp[v_cache_offset(D, plan.slot(m), ch + i)] = f32_to_elem(mine[i]);
@@ -730,6 +747,7 @@ static inline void launch_gemm_cfg(const u16* X, const u16* W, int K, int tiles,
                                    const Epi& epi, hipStream_t s) {
     constexpr int PF = (NT + MT) <= 4 ? 8 : ((NT + MT) <= 8 ? 4 : 2);
     constexpr int GRP = 2;
+    DUO_KERNEL_NAME("gemm_skinny_kernel<%d, %d, %d, %d, %d, %s>", MT, NT, NW, PF, GRP, Epi::NAME);
     DUO_LAUNCH((gemm_skinny_kernel<MT, NT, NW, PF, GRP, Epi>), dim3(tiles), dim3(NW * 64), s, X, W, K, quads, pq, rsc, epi);
 }
 
@@ -781,6 +799,7 @@ static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles,
     split_steps = (split_steps + RS - 1) / RS * RS;  // whole rounds: only the last split has a ragged end
     const int S = (steps + split_steps - 1) / split_steps;
     if (splits_out) *splits_out = S;
+    DUO_KERNEL_NAME("gemm_wide_kernel<%d, %d, %d, %d, %d, %d, %s, %s>", MH, NT, NG, NK, WIDE_PF, AG, Epi::NAME, HALF ? "true" : "false");
     DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, NK, WIDE_PF, AG, Epi, HALF>), dim3((tiles + NG - 1) / NG, S),
                dim3((NG * NK + 1) * 64), s, X, W, K, split_steps, tiles, quads, rsc, epi);
 }

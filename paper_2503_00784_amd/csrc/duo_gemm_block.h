@@ -98,6 +98,7 @@ __global__ __launch_bounds__(320) void gemm_block_kernel(const u16* __restrict__
     }
 
     // ---- consumers: wave (wm, wn) of the 2 x 2 grid
+    epi.arm();
     const int wm = wave >> 1, wn = wave & 1;
     f32x4 acc[WM][WN];
 #pragma unroll
@@ -170,6 +171,7 @@ static inline int launch_block_range(const u16* X, const u16* W, int K, int band
     split_steps = (split_steps + KS - 1) / KS * KS;
     const int S = (steps + split_steps - 1) / split_steps;
     const dim3 grid((band_end - band_begin + 2 * WN - 1) / (2 * WN), S, (mh_total + 2 * WM - 1) / (2 * WM));
+    DUO_KERNEL_NAME("gemm_block_kernel<%d, %d, %d, %d, %s>", WM, WN, KS, ENT, Epi::NAME);
     DUO_LAUNCH((gemm_block_kernel<WM, WN, KS, ENT, Epi>), grid, dim3(320), s, X, W, K, split_steps, band_begin, band_end, mh_total,
                quads, rsc, epi);
     return S;

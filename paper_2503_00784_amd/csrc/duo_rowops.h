@@ -152,6 +152,12 @@ __global__ void rope_table_kernel(RowPlan plan, int D, double theta, float* __re
     }
 }
 
+// The device-side input check of a call that scores no row: the status word starts clean unless the device's prefix
+// length is not the host's.
+__global__ void status_init_kernel(int32_t* status, const int32_t* prefix_len, int host_P) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *status = (prefix_len && *prefix_len != host_P) ? 2 : 0;
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;

@@ -56,6 +56,20 @@ struct SampleArgs {
     }
 };
 
+// The status word as the kernels before this one left it (they OR their flags in with device-scope atomics).  A pass
+// whose status is not clean commits nothing: the device prefix length and every cache slot below it stay as they
+// were, and the commit record reads {-1, 0, -1, unchanged prefix length}.
+__device__ __forceinline__ int32_t status_now(int32_t* status) {
+    return status ? __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+}
+// commit record of a pass that failed on the device; P is the host's prefix length, used when there is no cache
+__device__ __forceinline__ void write_failed_commit(int32_t* commit, const int32_t* prefix_len, int P) {
+    commit[0] = -1;
+    commit[1] = 0;
+    commit[2] = -1;
+    commit[3] = prefix_len ? *prefix_len : P;
+}
+
 // Logits as unsigned keys in the same order (-0 counted as +0), and the nucleus test of one token.
 __device__ __forceinline__ uint32_t logit_key(float x) {
     const uint32_t b = __float_as_uint(x + 0.0f);
@@ -449,11 +463,15 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArg
         a.accept_len[i] = acc_len;
         a.next_token[i] = tok;
         if (self_commit) {
-            a.commit[0] = 0;
-            a.commit[1] = acc_len;
-            a.commit[2] = tok;
-            a.commit[3] = a.P + a.R + acc_len;
-            if (prefix_len) *prefix_len = a.P + a.R + acc_len;
+            if (status_now(a.status) != 0) {
+                write_failed_commit(a.commit, prefix_len, a.P);
+            } else {
+                a.commit[0] = 0;
+                a.commit[1] = acc_len;
+                a.commit[2] = tok;
+                a.commit[3] = a.P + a.R + acc_len;
+                if (prefix_len) *prefix_len = a.P + a.R + acc_len;
+            }
         }
     }
 }
@@ -546,14 +564,18 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleA
             tok = block_inverse_cdf(pw, a.V, (double)a.u[a.k], sm_d, sm_i);
         }
     }
-    if (tid == 0) {
+    if (tid == 0) {  // the flags of this kernel's own token check were set before the barriers above
         a.accept_len[0] = acc_len;
         a.next_token[0] = tok;
-        a.commit[0] = sel;
-        a.commit[1] = acc_len;
-        a.commit[2] = tok;
-        a.commit[3] = a.P + a.R + acc_len;
-        if (d.prefix_len) *d.prefix_len = a.P + a.R + acc_len;
+        if (status_now(a.status) != 0) {
+            write_failed_commit(a.commit, d.prefix_len, a.P);
+        } else {
+            a.commit[0] = sel;
+            a.commit[1] = acc_len;
+            a.commit[2] = tok;
+            a.commit[3] = a.P + a.R + acc_len;
+            if (d.prefix_len) *d.prefix_len = a.P + a.R + acc_len;
+        }
     }
 }
 
@@ -566,11 +588,17 @@ struct CommitArgs {
     const int32_t* next_token;
     int32_t* commit;
     int32_t* prefix_len;  // may be NULL (sampling only)
+    int32_t* status;
 };
 
 // grid (Hkv, L) for the copy; (1, 1) when there is no cache.  In longest mode every workgroup
-// recomputes the (cheap) selection; workgroup (0, 0) publishes it.
+// recomputes the (cheap) selection; workgroup (0, 0) publishes it.  A pass whose status word is not clean moves
+// nothing and leaves the prefix length alone.
 __global__ __launch_bounds__(256) void commit_kernel(CommitArgs a) {
+    if (status_now(a.status) != 0) {  // same value in every workgroup: all flags were set by earlier kernels
+        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) write_failed_commit(a.commit, a.prefix_len, a.P);
+        return;
+    }
     int sel, len, tok;
     if (a.mode == 0) {
         sel = 0;
@@ -610,9 +638,11 @@ __global__ __launch_bounds__(256) void commit_kernel(CommitArgs a) {
     }
 }
 
-// Prefill bookkeeping: all m rows join the prefix, the last row's logits become the root logits.
+// Prefill bookkeeping: all m rows join the prefix, the last row's logits become the root logits.  Nothing is
+// changed when the pass's status word is not clean.
 __global__ void prefill_finish_kernel(const float* __restrict__ last_logits, float* __restrict__ root_logits, int V,
-                                      int32_t* prefix_len, int newP) {
+                                      int32_t* prefix_len, int newP, int32_t* status) {
+    if (status_now(status) != 0) return;
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v < V) root_logits[v] = last_logits[v];
     if (v == 0) *prefix_len = newP;

@@ -16,6 +16,16 @@ Readings where the paper is silent: ties at exactly theta do not seed a sequence
 sequences is capped so that every sequence has at least one token; tokens after the seed are the
 draft model's most likely continuation unless uniforms are supplied, in which case they are
 drawn from its distribution by inverse CDF.
+
+Fidelity.  The sequential first-token rule of Alg. 2 (test each sequence's first token against the
+running target distribution, replace that by its normalised residual after a rejection) reproduces
+the target distribution when every first token is a DRAW from the draft distribution handed to the
+verifier.  Seeds picked by rank (the paper's Fig. 2: the most likely first tokens, one sequence
+each) are not draws from the first-position distribution, and verifying them against it is then not
+distribution-preserving: the emitted token over-represents the seeds.  `sample_seeds=True` keeps the
+rule's count of sequences but draws the s first tokens independently from the first-position
+distribution with caller-supplied uniforms (repeats are possible and harmless); that is the
+setting in which the sequential rule is lossless.  tests/test_drafting.py shows both facts.
 """
 from typing import Callable, Dict, List, Optional, Sequence
 
@@ -55,14 +65,17 @@ def _next_token(probs: np.ndarray, u: Optional[float]) -> int:
 
 
 def build_draft_sequences(draft_step: DraftStep, prefix: Sequence[int], gamma: int, max_sequences: int = 0,
-                          uniforms: Optional[np.ndarray] = None) -> Dict[str, object]:
+                          uniforms: Optional[np.ndarray] = None, sample_seeds: bool = False) -> Dict[str, object]:
     """Draft s sequences of k = gamma // s tokens after `prefix`.
 
     Returns {"tokens": int32 [s][k], "probs": float32 [s][k][V], "theta": float, "first_probs": the
     first-position distribution}.  probs[i][j] is the draft distribution that token (i, j) was taken
     from: for j = 0 the first-position distribution (shared by all sequences), which is what the
     verifier's residual updates need.  uniforms, if given, is [s][k] in [0, 1): entries (i, j >= 1)
-    draw the continuation tokens (the seeds are chosen by rank, not drawn).
+    draw the continuation tokens.  The seeds are chosen by rank (the threshold rule) unless
+    `sample_seeds` is set: then the rule still fixes how many sequences there are, but first token i
+    is drawn from the first-position distribution by inverse CDF with uniforms[i][0] (required), the
+    setting in which the verifier's sequential rule preserves the target distribution.
     """
     prefix = list(int(t) for t in prefix)
     q1 = np.asarray(draft_step(prefix), dtype=np.float64)
@@ -70,6 +83,10 @@ def build_draft_sequences(draft_step: DraftStep, prefix: Sequence[int], gamma: i
     q2_top = np.asarray(draft_step(prefix + [top1]), dtype=np.float64)
     seeds = seed_tokens(q1, float(np.max(q2_top)), gamma, max_sequences)
     s = len(seeds)
+    if sample_seeds:
+        if uniforms is None:
+            raise ValueError("sample_seeds needs uniforms[i][0] for the first tokens")
+        seeds = [_next_token(q1, float(uniforms[i, 0])) for i in range(s)]
     k = max(1, gamma // s)
     V = q1.shape[0]
     tokens = np.zeros((s, k), dtype=np.int32)
@@ -78,7 +95,7 @@ def build_draft_sequences(draft_step: DraftStep, prefix: Sequence[int], gamma: i
         seq = [seed]
         probs[i, 0] = q1
         for j in range(1, k):
-            q = q2_top if (i == 0 and j == 1) else np.asarray(draft_step(prefix + seq), dtype=np.float64)
+            q = q2_top if (j == 1 and seed == top1) else np.asarray(draft_step(prefix + seq), dtype=np.float64)
             probs[i, j] = q
             seq.append(_next_token(q, None if uniforms is None else float(uniforms[i, j])))
         tokens[i] = seq

@@ -122,6 +122,12 @@ def test_other_entry_points_validate(lib):
     ss = lambda **kw: lib.duo_spec_sample(kw.get("lg", 0x1000), kw.get("root", 0x1000), kw.get("V", 32000), 0x1000, 0x1000,
                                           0x1000, C.byref(call), C.byref(res), 0x1000, kw.get("nb", out.value), None)
     assert ss(lg=None) == -1 and ss(root=None) == -1 and ss(V=1) == -2 and ss(nb=16) == -5
+    # the deferred form takes an empty suffix (k = 0) but no negative one; n must be 1
+    ds = lambda c, **kw: lib.duo_deferred_sample(kw.get("lg", 0x1000), 0x1000, 32000, kw.get("toks", 0x1000), 0x1000, kw.get("u", 0x1000),
+                                                 None, None, None, 0, C.byref(c), C.byref(res), 0x1000, out.value, None)
+    assert ds(B.Call(1, -1, 1.0, 1, -1, 0)) == -2 and ds(B.Call(2, 4, 1.0, 1, -1, 0)) == -2
+    assert ds(B.Call(1, 4, 1.0, 1, -1, 0), toks=None) == -1 and ds(B.Call(1, 0, 1.0, 1, -1, 0), u=None) == -1
+    assert lib.duo_sample_workspace_bytes(32000, 1, 0, C.byref(out)) == 0
     g = lambda **kw: lib.duo_skinny_gemm(kw.get("x", 0x1000), 0x1000, 0x1000, kw.get("rows", 8), 64, kw.get("K", 64), None)
     assert g(x=None) == -1 and g(rows=0) == -2 and g(rows=81) == -2 and g(K=48) == -2 and g(x=0x1002) == -4
     assert lib.duo_packed_elems(4099, 512) == 4128 * 512 and lib.duo_packed_elems(32, 64) == 32 * 64

@@ -90,6 +90,31 @@ def test_deferred_sampler_bit_exact_on_identical_logits(B, V, l, s, scenario):
         assert branches == {"final"}
 
 
+@pytest.mark.parametrize("V,s,has_root", [(4099, 3, False), (32000, 2, True), (50, 0, False), (1031, 8, True), (128256, 4, False)])
+@pytest.mark.parametrize("scenario", ["random", "second_new", "none_new"])
+def test_deferred_sampler_empty_suffix(B, V, s, has_root, scenario):
+    """l = 0, the round after a rejection and the first round after the prompt: nothing to verify, the new sequences'
+    first tokens are judged by the distribution after the root token (has_root: the pass's only row) or by the cached
+    root logits; with none accepted (or s = 0) one token is drawn from the final residual."""
+    for seed in range(2):
+        say(f"deferred sampler, empty suffix V={V} s={s} root={has_root} scenario={scenario} seed={seed}")
+        T = 0.9 if seed == 1 else 1.0
+        root, logits, _, _, u, fq, ftoks, fu = _case(V, 1, s, seed + 7, scenario, peaked=False)
+        u = u[1:]  # the one uniform of the final draw
+        judge_logits = logits[0] if has_root else root
+        x = [5, 6]
+        ref = _oracle_outcome(x, [], [], judge_logits, [], [], ftoks, fq, fu, u[0], T)
+        got = B.deferred_sample(to_dev(logits[:1]) if has_root else None, to_dev(root), None, None, to_dev(u),
+                                to_dev(ftoks) if s else None, to_dev(fq) if s else None, to_dev(fu) if s else None,
+                                temperature=T, has_root=has_root, prefix_len=2)
+        assert got["status"] == 0 and got["accept_len"] == 0
+        assert got["new_prefix_len"] == 2 + (1 if has_root else 0)
+        out = _gpu_outcome(x, [], got, ftoks)
+        assert out[0] == ref[0], (out, ref, got)
+        if s == 0 or scenario == "none_new":
+            assert got["selected"] == -1 and got["next_token"] >= 0
+
+
 @pytest.mark.parametrize("V,l,s", [(4099, 4, 3), (32000, 6, 2), (50, 2, 0)])
 @pytest.mark.parametrize("variant", ["suffix_breaks", "second_new", "none_new"])
 def test_deferred_sampler_greedy_limit(B, V, l, s, variant):
@@ -192,3 +217,110 @@ def test_verify_deferred_end_to_end(B, l, s, root_token, scenario):
     vd = np.abs(O.bf16_bits_to_f64(vg[:, :, :upto]) - cache.v[:, :, :upto]).max()
     say(f"  accepted {a} of {l}; cache max abs diff k {kd:.3e} v {vd:.3e}")
     assert kd <= 0.07 and vd <= 0.07
+
+
+def _alg2_round(x, x_tilde, q_tilde, logits, root_logits, R, xhat, qhat0, u, u_first, T=1.0):
+    """One round of Alg. 2 through the oracle on the given fp32 logits (rows: root if R, then the suffix)."""
+    l = len(x_tilde)
+    judge = [(logits[0] if R else root_logits)] + [logits[R + m] for m in range(l - 1)] if l else []
+    p_n_logits = logits[R + l - 1] if R + l > 0 else root_logits
+    p_unv = [O.target_probs(judge[m], T) for m in range(l)]
+    return O.duodec_verify_alg2(list(x), list(x_tilde), [np.asarray(q, dtype=np.float64) for q in q_tilde], p_unv,
+                                O.target_probs(p_n_logits, T), [list(map(int, sq)) for sq in xhat],
+                                [np.asarray(q, dtype=np.float64) for q in qhat0], [float(v) for v in u[:l]],
+                                [float(v) for v in u_first], float(u[l]))
+
+
+def test_pipelined_loop_over_rounds(B):
+    """The target side of the pipelined loop (Alg. 1) with Alg. 2 as listed, round after round on one cache: what a
+    round accepts becomes the next round's root token and unverified suffix, a rejection hands over the correction
+    token alone.  The uniforms script every branch: a first round with nothing to verify, an accepted sequence, a
+    suffix that passes, a rejection inside the suffix, a round with the correction token as its only row, all new
+    sequences rejected.  After every round: logits against the oracle's pass, the decision against Alg. 2 on the
+    GPU's own logits (bit-exact) and on the oracle's logits (the token stream must be the oracle's; a draw within
+    rounding of a CDF edge would be a declared tie and end the comparison), prefix length and cache rows."""
+    import torch
+    shape = inputs.MID
+    V = shape.vocab
+    w = inputs.make_weights(shape, seed=21, threads=16)
+    oshape = O.shape_from(shape)
+    eng = B.VerifyEngine(shape, w, 256)
+    prompt = inputs.make_prefix_ids(shape, 45, seed=21).tolist()
+    eng.prefill(prompt)
+    cache = O.prefill(oshape, w, prompt, 256)
+    s_new, k_new = 3, 4
+    script = [dict(first="accept0"), dict(suffix="all", first="second"), dict(suffix="reject1"), dict(first="none"),
+              dict(first="accept0"), dict(suffix="all", first="none"), dict(first="second")]
+    x_ora, x_gpu = list(prompt), list(prompt)   # every token so far, unverified suffix included
+    x_tilde, q_tilde, root = [], [], -1
+    rounds_done = 0
+    for rnd, sc in enumerate(script):
+        l, R, P = len(x_tilde), (1 if root >= 0 else 0), cache.prefix_len
+        qn, tn, un = inputs.make_draft(V, s_new, k_new, seed=300 + rnd)  # the new sequences and the draft distributions they were drawn from
+        fu = un[:, 0].copy()
+        _, _, uu = inputs.make_draft(V, 1, max(l, 1), seed=400 + rnd)
+        u = uu[0, :l + 1].copy()
+        if sc.get("suffix") == "all":
+            u[:l] = 0.0
+        elif sc.get("suffix") == "reject1":
+            u[:l] = 0.0
+            u[min(1, l - 1)] = 0.9999
+        if sc.get("first") == "accept0":
+            fu[0] = 0.0
+        elif sc.get("first") == "second":
+            fu[0], fu[1] = 0.9999, 0.0
+        elif sc.get("first") == "none":
+            fu[:] = 0.9999
+        say(f"round {rnd}: P={P} root={root} l={l} script={sc}")
+        lg = torch.empty((max(R + l, 1), V), dtype=torch.float32, device="cuda")
+        eng.verify_deferred(to_dev(np.asarray(x_tilde, dtype=np.int32)) if l else None,
+                            to_dev(np.stack(q_tilde).astype(np.float32)) if l else None, to_dev(u), to_dev(tn[:, 0].copy()),
+                            to_dev(qn[:, 0].copy()), to_dev(fu), root_token=root, logits_out=lg)
+        got = eng.results(1)
+        assert got["status"] == 0
+        gl = lg.cpu().numpy()[:R + l]
+        groot = eng.root_logits.cpu().numpy()
+        oroot = cache.root_logits
+        ol = O.verify_forward(oshape, w, cache, np.asarray(x_tilde, dtype=np.int64).reshape(1, l), root_token=root).astype(np.float32) \
+            if R + l > 0 else np.zeros((0, V), dtype=np.float32)
+        if R + l > 0:
+            ok, max_abs, worst = logits_close(gl, ol)
+            say(f"  logits max abs err {max_abs:.3e} (worst err/bound {worst:.3f})")
+            assert ok
+        ref_gpu = _alg2_round(x_gpu, x_tilde, q_tilde, gl, groot, R, tn, qn[:, 0], u, fu)
+        ref_ora = _alg2_round(x_ora, x_tilde, q_tilde, ol, oroot, R, tn, qn[:, 0], u, fu)
+        # the library's outputs -> (x, x_tilde) of the next round
+        a = int(got["accept_len"][0])
+        assert got["commit_len"] == a and got["new_prefix_len"] == P + R + a == got["device_prefix_len"]
+        if a < l or got["selected"] < 0:
+            assert got["commit_token"] == int(got["next_token"][0]) >= 0
+            out = (x_gpu[:len(x_gpu) - l + a] + [got["commit_token"]], [])
+        else:
+            assert got["commit_token"] == -1
+            seq = [int(t) for t in tn[got["selected"]]]
+            out = (x_gpu + seq, seq[1:])
+        assert out == (list(ref_gpu[0]), list(ref_gpu[1])), (rnd, out, ref_gpu)   # bit-exact on identical logits
+        if out != (list(ref_ora[0]), list(ref_ora[1])):
+            say("  the oracle's own logits decide differently (a draw within rounding of a CDF edge): declared tie, stopping")
+            break
+        # both sides advance: root row and accepted suffix rows join the prefix where the pass wrote them
+        cache.prefix_len = P + R + a
+        cache.root_logits = None
+        kg, vg = eng.cache_to_host()
+        upto = cache.prefix_len
+        kd = np.abs(O.bf16_bits_to_f64(kg[:, :, :upto]) - cache.k[:, :, :upto]).max()
+        vd = np.abs(O.bf16_bits_to_f64(vg[:, :, :upto]) - cache.v[:, :, :upto]).max()
+        say(f"  accepted {a} of {l}, selected {got['selected']}, emitted {got['commit_token']}; cache max abs diff k {kd:.3e} v {vd:.3e}")
+        assert kd <= 0.07 and vd <= 0.07
+        x_ora, x_gpu = list(ref_ora[0]), list(out[0])
+        x_tilde = list(out[1])
+        if x_tilde:   # an accepted sequence: its first token is verified (next root), the rest is the unverified suffix
+            sel = got["selected"]
+            root = int(tn[sel, 0])
+            q_tilde = [qn[sel, j] for j in range(1, k_new)]
+        else:
+            root = int(out[0][-1])
+            q_tilde = []
+        rounds_done += 1
+    assert rounds_done >= 5, rounds_done
+    assert x_ora == x_gpu and len(x_ora) > len(prompt) + 5

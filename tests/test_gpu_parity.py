@@ -4,7 +4,7 @@ import pytest
 
 from oracle import duo_oracle as O
 from paper_2503_00784_amd import inputs
-from tests.gpu_util import (ACCEPT_TIE, compare_end_to_end, logits_close, say, to_dev)
+from tests.gpu_util import (ACCEPT_TIE, compare_end_to_end, logits_close, same_as_sampler_on, say, to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -212,6 +212,7 @@ def _check_step(B, shape, w, oshape, eng, cache, n, k, seed, mode, root_token, t
     q, toks, u = inputs.make_draft(V, n, k, seed=seed, easy_rows=inputs.easy_rows_for(n, k))
     R = 1 if root_token >= 0 else 0
     P = cache.prefix_len
+    cache_root = None if cache.root_logits is None else cache.root_logits.copy()  # the oracle's commit drops it
     logits_dev = torch.empty((R + n * k, V), dtype=torch.float32, device="cuda")
     eng.verify(to_dev(toks), to_dev(q), to_dev(u), temperature=temperature, select_mode=mode, root_token=root_token,
                logits_out=logits_dev)
@@ -224,13 +225,20 @@ def _check_step(B, shape, w, oshape, eng, cache, n, k, seed, mode, root_token, t
     say(f"  logits max abs err {max_abs:.3e} (worst err/bound {worst:.3f}); gpu accept {got['accept_len']} "
         f"oracle {res.accept_len} accept margins {np.round(res.accept_margins, 4)}")
     assert ok, (max_abs, worst)
-    compared = compare_end_to_end(got, res, n) if mode == 0 else 0
+    # decisions, both modes: (1) bit-exact against the oracle's sampler on the logits the GPU returned; (2) against the
+    # oracle's whole step on its own logits wherever its margins exceed the declared-tie bound
+    groot = eng.root_logits.cpu().numpy()
+    exact = same_as_sampler_on(got, gl, groot, toks, q, u, P, temperature, mode, bool(R))
+    compared = compare_end_to_end(got, res, n, mode, ol, cache_root, q, u, k, R, temperature)
+    say(f"  decisions: bit-exact on the GPU's logits {'compared' if exact else 'skipped (tie within 1e-9)'}; "
+        f"{compared} compared against the oracle's own logits")
     # the fused call's sampler sees the same logits it returned: same decisions as the stand-alone sampler entry point
     again = B.spec_sample(logits_dev, eng.root_logits, to_dev(toks), to_dev(q), to_dev(u), temperature=temperature,
                           select_mode=mode, has_root=bool(R), prefix_len=P)
     for key in ("selected", "commit_len", "commit_token", "new_prefix_len"):
         assert again[key] == got[key], key
     np.testing.assert_array_equal(again["accept_len"], got["accept_len"])
+    np.testing.assert_array_equal(again["next_token"], got["next_token"])
     assert got["new_prefix_len"] == P + R + got["commit_len"] == got["device_prefix_len"]
     return got, res, compared
 
@@ -242,6 +250,19 @@ def _check_cache(eng, cache, upto, atol=0.07):
     vd = np.abs(O.bf16_bits_to_f64(vg[:, :, :upto]) - cache.v[:, :, :upto])
     say(f"  cache max abs diff k {kd.max():.3e} v {vd.max():.3e}")
     assert kd.max() <= atol and vd.max() <= atol
+
+
+def _check_cache_rows(B, eng, cache, lo, hi, layers, atol=0.07):
+    """Cache slots [lo, hi) of a few layers against the oracle's, moved to the host slot range only (full-size caches
+    are gigabytes).  Returns the largest differences."""
+    D = eng.shape.head_dim
+    idx = list(layers)
+    kg = B.k_tiles_to_rows(eng.k[idx], D)[:, :, lo:hi].cpu().numpy().view(np.uint16)
+    vg = B.v_tiles_to_rows(eng.vT[idx], D)[:, :, lo:hi].cpu().numpy().view(np.uint16)
+    kd = np.abs(O.bf16_bits_to_f64(kg) - cache.k[idx][:, :, lo:hi]).max() if hi > lo else 0.0
+    vd = np.abs(O.bf16_bits_to_f64(vg) - cache.v[idx][:, :, lo:hi]).max() if hi > lo else 0.0
+    assert kd <= atol and vd <= atol, (lo, hi, kd, vd)
+    return kd, vd
 
 
 def test_tiny_config_prefill_and_verify_chain(B):
@@ -462,6 +483,77 @@ def test_verify_is_repeatable_and_flags_prefix_mismatch(B):
     assert eng.results(2)["status"] & B.STATUS_PREFIX_MISMATCH
 
 
+def test_device_detected_failures_commit_nothing(B):
+    """A call that fails on the device (stale host prefix length, draft token out of range) is flagged and leaves the
+    prefix length, the root logits and every committed cache slot exactly as they were; the next good call gives
+    what it gave before."""
+    import torch
+    shape = inputs.MID
+    P, max_seq = 40, 128
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, max_seq, seed=5, synthetic_cache=True)
+    q, toks, u = inputs.make_draft(shape.vocab, 2, 4, seed=1)
+    d = [to_dev(a) for a in (toks, q, u)]
+
+    def committed_state():
+        torch.cuda.synchronize()
+        kc, vc = eng.cache_to_host()
+        return kc[:, :, :P].copy(), vc[:, :, :P].copy(), int(eng.prefix_len.item()), eng.root_logits.cpu().numpy().copy()
+
+    def unchanged(before):
+        now = committed_state()
+        np.testing.assert_array_equal(now[0], before[0])
+        np.testing.assert_array_equal(now[1], before[1])
+        assert now[2] == before[2] == P
+        np.testing.assert_array_equal(now[3], before[3])
+
+    eng.verify(*d)
+    good = eng.results(2)
+    assert good["status"] == 0 and good["new_prefix_len"] == P + good["commit_len"]
+    eng.set_prefix_len(P)
+    before = committed_state()
+    for mode in (0, 1):
+        for stale in (33, 44):  # too small: the pass's rows would land on committed slots; too large: a hole
+            say(f"failure: host prefix {stale}, device prefix {P}, mode {mode}")
+            eng.host_prefix_len = stale
+            eng.verify(*d, select_mode=mode)
+            r = eng.results(2)
+            assert r["status"] & B.STATUS_PREFIX_MISMATCH
+            assert (r["selected"], r["commit_len"], r["commit_token"], r["new_prefix_len"]) == (-1, 0, -1, P)
+            assert eng.host_prefix_len == P  # the commit record reports the device's prefix length
+            unchanged(before)
+        say(f"failure: draft token out of range, mode {mode}")
+        bad = toks.copy()
+        bad[1, 2] = shape.vocab + 5
+        eng.verify(to_dev(bad), d[1], d[2], select_mode=mode)
+        r = eng.results(2)
+        assert r["status"] & B.STATUS_TOKEN_CLAMPED
+        assert (r["selected"], r["commit_len"], r["commit_token"], r["new_prefix_len"]) == (-1, 0, -1, P)
+        unchanged(before)
+    say("failure: single-sequence call (the sampler commits itself), deferred form, prompt chunk")
+    eng.host_prefix_len = 37
+    eng.verify(d[0][:1], d[1][:1], d[2][:1])
+    r = eng.results(1)
+    assert r["status"] & B.STATUS_PREFIX_MISMATCH and r["new_prefix_len"] == P and r["commit_len"] == 0
+    unchanged(before)
+    eng.host_prefix_len = 37
+    eng.verify_deferred(d[0][0], d[1][0], d[2][0], d[0][:, 0].contiguous(), d[1][:, 0].contiguous(), d[2][:, 0].contiguous(), root_token=3)
+    r = eng.results(1)
+    assert r["status"] & B.STATUS_PREFIX_MISMATCH and r["new_prefix_len"] == P and r["selected"] == -1
+    unchanged(before)
+    eng.host_prefix_len = 36
+    eng.prefill([1, 2, 3, 4, 5])  # a stale host: the chunk must not become part of the prefix
+    torch.cuda.synchronize()
+    assert int(eng.status.item()) & B.STATUS_PREFIX_MISMATCH
+    unchanged(before)
+    eng.host_prefix_len = P
+    eng.verify(*d)
+    again = eng.results(2)
+    assert again["status"] == 0
+    for key in ("selected", "commit_len", "commit_token", "new_prefix_len"):
+        assert again[key] == good[key], key
+    np.testing.assert_array_equal(again["accept_len"], good["accept_len"])
+
+
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4"])
 def test_full_size_shapes(B, name):
     """Llama-2-7B (C1-C3) and Llama-3-8B GQA (C4) geometry at the benchmark's launch configuration, synthetic
@@ -471,8 +563,26 @@ def test_full_size_shapes(B, name):
     say(f"{name}: generating weights")
     w, oshape, eng, cache = _engine_and_oracle(B, shape, P, P + 128, seed=0, synthetic_cache=True)
     say(f"{name}: verify n={n} k={k} P={P}")
+    root0 = cache.root_logits.copy()
     got, res, compared = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=1, mode=0, root_token=-1)
     say(f"  accept lengths compared away from ties: {compared}/{n}")
+    assert 2 * compared >= n
+    # the commit at full size: the selected branch's keys and values next to the prefix (first, middle and last layer),
+    # the prefix itself untouched (bit-identical to what was loaded), the prefix length advanced on the device
+    layers = sorted({0, shape.n_layers // 2, shape.n_layers - 1})
+    assert (got["selected"], got["commit_len"]) == (res.selected, res.commit_len), "no declared tie on these inputs"
+    assert cache.prefix_len == P + res.commit_len == got["device_prefix_len"]
+    kd, vd = _check_cache_rows(B, eng, cache, P, cache.prefix_len, layers)
+    _check_cache_rows(B, eng, cache, 0, 64, layers, atol=0.0)
+    _check_cache_rows(B, eng, cache, P - 64, P, layers, atol=0.0)
+    say(f"  committed rows [{P}, {cache.prefix_len}) of layers {layers}: max abs diff k {kd:.3e} v {vd:.3e}; prefix rows identical")
+    if n > 1:  # and the multi-sequence rule of Alg. 2 on the same state
+        eng.set_prefix_len(P)
+        cache.prefix_len = P
+        cache.root_logits = root0
+        say(f"{name}: the same step in paper mode")
+        got, res, compared = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=1, mode=1, root_token=-1)
+        assert compared >= 1
 
 
 def test_full_size_prefill_paths_agree(B):
@@ -496,6 +606,19 @@ def test_full_size_prefill_paths_agree(B):
         assert int(eng.prefix_len.item()) == total and int(eng.status.item()) == 0
         kc, vc = eng.cache_to_host()
         outs.append((eng.root_logits.cpu().numpy().copy(), O.bf16_bits_to_f64(kc[::8, :, :total]), O.bf16_bits_to_f64(vc[::8, :, :total])))
+        # What the oracle can compute one by one at this size: the first layer's keys and values of sampled prompt
+        # positions depend on their own token only (embedding, RMSNorm, the K/V projections, the rotation at the
+        # token's position), so they are checked against the oracle's pieces directly, through both row paths.
+        for t in (0, 1, 79, 80, 511, 1023, 1024, total - 1):
+            x = O.embed_rows(w, [prompt[t]])
+            h = O.rmsnorm(x, O._w(w, "g_attn", 0), shape.rms_eps)
+            k_ref = (h @ O._w(w, "wk", 0).T).reshape(shape.n_kv_heads, shape.head_dim)
+            k_ref = O.round_to_bf16(np.stack([O.rope(k_ref[a], t, shape.rope_theta) for a in range(shape.n_kv_heads)]))
+            v_ref = O.round_to_bf16((h @ O._w(w, "wv", 0).T).reshape(shape.n_kv_heads, shape.head_dim))
+            dk = np.abs(O.bf16_bits_to_f64(kc[0, :, t]) - k_ref).max()
+            dv = np.abs(O.bf16_bits_to_f64(vc[0, :, t]) - v_ref).max()
+            assert dk <= 0.07 and dv <= 0.07, (chunk, t, dk, dv)   # one bf16 step at values of this size
+            assert np.abs(k_ref).max() > 0.5
         del eng
     (la, ka, va), (lb, kb, vb) = outs
     dl = np.abs(la - lb)
