@@ -43,6 +43,7 @@ extern "C" {
 #define DUO_ERR_TOKEN_RANGE -6  /* root_token >= vocab */
 #define DUO_ERR_HIP         -7  /* a HIP call failed; see duo_last_hip_error() */
 #define DUO_ERR_ARG         -8  /* temperature < 0 or NaN, unknown select_mode, ... */
+#define DUO_ERR_SCRATCH     -9  /* duo_spec_sample_noalloc: vocabulary above DUO_NOALLOC_MAX_VOCAB, or top_p asked for */
 
 /* Most rows one call can score: n*k (+1 with a root token). */
 #define DUO_MAX_ROWS 80
@@ -217,6 +218,24 @@ int duo_spec_sample(const float *logits, const float *root_logits, int vocab,
                     const int32_t *draft_tokens, const float *draft_probs, const float *uniforms,
                     const duo_call *call, duo_result *out,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * duo_spec_sample for callers that cannot allocate or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same sampling kernels, with their scratch (softmax statistics, accept
+ * flags, one running distribution) in a static device array of DUO_NOALLOC_SCRATCH_BYTES inside the library, which
+ * every device the library runs on holds until the process ends.  Same arguments and results as duo_spec_sample
+ * without the workspace.  Limits: vocab <= DUO_NOALLOC_MAX_VOCAB and no nucleus restriction (0 < top_p < 1 at a
+ * positive temperature), else DUO_ERR_SCRATCH and nothing is enqueued.  Calls no hipMalloc / hipFree and no
+ * allocating routine.  The first call on a device (with that device current, as for every call) asks the runtime
+ * for the address of that device's copy of the array; make it outside a stream capture.  All calls on one device
+ * share the array: calls that overlap on one device (different streams) race, calls on one stream do not.  Nothing
+ * in the array needs clearing between calls: every entry a call reads it has written first.
+ */
+#define DUO_NOALLOC_MAX_VOCAB 131072
+#define DUO_NOALLOC_SCRATCH_BYTES (20480 + 131072 * 8 + 512)
+int duo_spec_sample_noalloc(const float *logits, const float *root_logits, int vocab,
+                            const int32_t *draft_tokens, const float *draft_probs, const float *uniforms,
+                            const duo_call *call, duo_result *out, void *hip_stream);
 
 /*
  * Alg. 2 in the form the paper lists it, for one round of the pipelined loop of Alg. 1: the pass

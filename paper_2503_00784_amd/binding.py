@@ -25,11 +25,12 @@ STATUS_TOKEN_CLAMPED = 1
 STATUS_PREFIX_MISMATCH = 2
 
 EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample_workspace_bytes",
-           "duo_spec_sample", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm",
+           "duo_spec_sample", "duo_spec_sample_noalloc", "duo_verify_deferred", "duo_deferred_sample", "duo_skinny_gemm",
            "duo_block_gemm", "duo_stream_read_probe", "duo_k_cache_offset",
            "duo_v_cache_offset", "duo_status_string", "duo_last_hip_error", "duo_profile_enable",
            "duo_profile_read", "duo_profile_dropped", "duo_profile_kernel_name", "duo_packed_elems", "duo_pack_matrix", "duo_pack_qkv", "duo_pack_gate_up",
            "duo_pack_activations"]
+NOALLOC_MAX_VOCAB = 131072
 PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "residual_reduce", "gate_up_swiglu", "down_proj", "lm_head",
                 "sample", "commit"]
 
@@ -97,6 +98,9 @@ def load(dtype: str = "bf16") -> C.CDLL:
     lib.duo_sample_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     lib.duo_spec_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Call),
                                     C.POINTER(Result), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.duo_spec_sample_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Call),
+                                            C.POINTER(Result), C.c_void_p]
+    lib.duo_spec_sample_noalloc.restype = C.c_int
     lib.duo_profile_dropped.argtypes = []
     lib.duo_profile_dropped.restype = C.c_int
     lib.duo_profile_kernel_name.argtypes = [C.c_int]
@@ -441,6 +445,38 @@ def spec_sample(logits, root_logits, draft_tokens, draft_probs, uniforms, temper
     return {"accept_len": accept_len.cpu().numpy(), "next_token": next_token.cpu().numpy(), "selected": int(c[0]),
             "commit_len": int(c[1]), "commit_token": int(c[2]), "new_prefix_len": int(c[3]),
             "status": int(status.cpu().numpy()[0])}
+
+
+class NoAllocSampler:
+    """duo_spec_sample_noalloc with result buffers allocated once, here, by the caller: the call itself allocates
+    nothing and takes no workspace.  Inputs are device tensors; `run` enqueues, `fetch` synchronises and reads."""
+
+    def __init__(self, max_n: int = DUO_MAX_ROWS, device: str = "cuda:0"):
+        import torch
+        self.accept_len = torch.zeros(max_n, dtype=torch.int32, device=device)
+        self.next_token = torch.zeros(max_n, dtype=torch.int32, device=device)
+        self.commit = torch.zeros(4, dtype=torch.int32, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+
+    def run(self, logits, root_logits, draft_tokens, draft_probs, uniforms, temperature: float = 1.0,
+            select_mode: int = SELECT_INDEPENDENT_LONGEST, has_root: bool = False, prefix_len: int = 0, top_p: float = 0.0,
+            dtype: str = "bf16") -> int:
+        """Returns the entry point's code (0 = enqueued) without raising, so that tests can look at error codes."""
+        n, k = draft_tokens.shape
+        vocab = logits.shape[-1]
+        call = Call(n, k, float(temperature), int(select_mode), 0 if has_root else -1, int(prefix_len), float(top_p))
+        res = Result(self.accept_len.data_ptr(), self.next_token.data_ptr(), self.commit.data_ptr(), self.status.data_ptr(), None)
+        return int(load(dtype).duo_spec_sample_noalloc(logits.data_ptr(), _ptr(root_logits), vocab, draft_tokens.data_ptr(),
+                                                       draft_probs.data_ptr(), uniforms.data_ptr(), C.byref(call), C.byref(res),
+                                                       _stream_ptr()))
+
+    def fetch(self, n: int) -> Dict[str, object]:
+        import torch
+        torch.cuda.synchronize()
+        c = self.commit.cpu().numpy()
+        return {"accept_len": self.accept_len[:n].cpu().numpy(), "next_token": self.next_token[:n].cpu().numpy(),
+                "selected": int(c[0]), "commit_len": int(c[1]), "commit_token": int(c[2]), "new_prefix_len": int(c[3]),
+                "status": int(self.status.cpu().numpy()[0])}
 
 
 def deferred_sample(logits, root_logits, unverified_tokens, unverified_probs, uniforms, first_tokens=None,

@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "duo_attn.h"
@@ -16,6 +17,19 @@
 #include "duo_pack.h"
 #include "duo_rowops.h"
 #include "duo_sample.h"
+
+// ---- scratch of the entry point that allocates nothing (duo_spec_sample_noalloc): what duo_spec_sample takes from its
+// workspace argument, sized for DUO_NOALLOC_MAX_VOCAB and without the nucleus search rows.  The array lives in every
+// device's copy of this code object; host code never passes its name to a kernel, only the per-device address that
+// hipGetSymbolAddress returned.
+constexpr size_t NOALLOC_STATS_BYTES = (size_t)2 * DUO_MAX_ROWS * STATS_SPLIT * 2 * sizeof(double);
+constexpr size_t NOALLOC_PRUN_BYTES = (size_t)DUO_NOALLOC_MAX_VOCAB * sizeof(double);
+constexpr size_t NOALLOC_ACC_BYTES = 512;  // DUO_MAX_ROWS accept flags
+static_assert(NOALLOC_STATS_BYTES % 256 == 0 && NOALLOC_PRUN_BYTES % 256 == 0 && DUO_MAX_ROWS * sizeof(int32_t) <= NOALLOC_ACC_BYTES,
+              "the three parts keep the array's alignment");
+constexpr size_t NOALLOC_SCRATCH_BYTES = NOALLOC_STATS_BYTES + NOALLOC_PRUN_BYTES + NOALLOC_ACC_BYTES;
+static_assert(NOALLOC_SCRATCH_BYTES == DUO_NOALLOC_SCRATCH_BYTES, "the header states the array's size");
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -444,6 +458,62 @@ int check_result(const duo_result* out) {
     return DUO_OK;
 }
 
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[NOALLOC_MAX_DEVICES];  // per device: address of that device's copy of `scratch`; nullptr until asked for
+
+// The current device's copy of `scratch`; the first call on a device asks the runtime for its address.
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    int rc = hip_ok(hipGetDevice(&dev), "hipGetDevice");
+    if (rc) return rc;
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) {
+        snprintf(g_hip_err, sizeof g_hip_err, "device index %d beyond the %d this library keeps scratch addresses for", dev, NOALLOC_MAX_DEVICES);
+        return DUO_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        rc = hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc) return rc;
+        if (!p) {
+            snprintf(g_hip_err, sizeof g_hip_err, "hipGetSymbolAddress(scratch) returned a null address");
+            return DUO_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DUO_OK;
+}
+
+// duo_spec_sample's sampling kernels on the static scratch array
+int spec_sample_on_scratch(const float* logits, const float* root_logits, int vocab, const int32_t* draft_tokens,
+                                  const float* draft_probs, const float* uniforms, const duo_call* call, duo_result* out,
+                                  void* hip_stream) {
+    if (vocab < 2) return DUO_ERR_SHAPE;
+    int rc = check_call(call, vocab);
+    if (rc) return rc;
+    if ((rc = check_result(out))) return rc;
+    const int R = call->root_token >= 0 ? 1 : 0;
+    if (!logits || !draft_tokens || !draft_probs || !uniforms || (!R && !root_logits)) return DUO_ERR_NULL;
+    if (vocab > DUO_NOALLOC_MAX_VOCAB || nucleus_on(call)) return DUO_ERR_SCRATCH;
+    void* base = nullptr;
+    if ((rc = scratch_of_current_device(&base))) return rc;
+    Workspace ws{};
+    char* b = static_cast<char*>(base);
+    ws.stats = reinterpret_cast<double*>(b);
+    ws.p_run = reinterpret_cast<double*>(b + NOALLOC_STATS_BYTES);
+    ws.acc = reinterpret_cast<int32_t*>(b + NOALLOC_STATS_BYTES + NOALLOC_PRUN_BYTES);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
+    SampleArgs sa{logits, vocab, root_logits, vocab, call->n, call->k, R, call->host_prefix_len, (double)call->temperature,
+                  draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
+                  out->commit, out->status, nullptr};
+    enqueue_sampling(sa, call->top_p, ws, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
+    return hip_ok(hipGetLastError(), "duo_spec_sample_noalloc launch");
+}
+
 }  // namespace
 
 extern "C" {
@@ -544,6 +614,12 @@ int duo_spec_sample(const float* logits, const float* root_logits, int vocab, co
                   nucleus_on(call) ? ws.nuc : nullptr};
     enqueue_sampling(sa, call->top_p, ws, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
     return hip_ok(hipGetLastError(), "duo_spec_sample launch");
+}
+
+int duo_spec_sample_noalloc(const float* logits, const float* root_logits, int vocab, const int32_t* draft_tokens,
+                            const float* draft_probs, const float* uniforms, const duo_call* call, duo_result* out,
+                            void* hip_stream) {
+    return spec_sample_on_scratch(logits, root_logits, vocab, draft_tokens, draft_probs, uniforms, call, out, hip_stream);
 }
 
 // checks shared by the two deferred entry points
@@ -774,6 +850,7 @@ const char* duo_status_string(int code) {
         case DUO_ERR_TOKEN_RANGE: return "token id out of range";
         case DUO_ERR_HIP: return "HIP error";
         case DUO_ERR_ARG: return "invalid argument";
+        case DUO_ERR_SCRATCH: return "request exceeds the static scratch of the no-allocation entry point (vocabulary above DUO_NOALLOC_MAX_VOCAB, or top_p)";
         default: return "unknown status";
     }
 }

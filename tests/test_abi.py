@@ -33,8 +33,8 @@ def test_every_declared_entry_point_is_exported(lib):
 
 def test_status_strings(lib):
     assert B.status_string(0) == "ok"
-    seen = {B.status_string(c) for c in range(-8, 1)}
-    assert len(seen) == 9 and "unknown status" not in seen
+    seen = {B.status_string(c) for c in range(-9, 1)}
+    assert len(seen) == 10 and "unknown status" not in seen
     assert B.status_string(-99) == "unknown status"
 
 
@@ -122,6 +122,13 @@ def test_other_entry_points_validate(lib):
     ss = lambda **kw: lib.duo_spec_sample(kw.get("lg", 0x1000), kw.get("root", 0x1000), kw.get("V", 32000), 0x1000, 0x1000,
                                           0x1000, C.byref(call), C.byref(res), 0x1000, kw.get("nb", out.value), None)
     assert ss(lg=None) == -1 and ss(root=None) == -1 and ss(V=1) == -2 and ss(nb=16) == -5
+    # the entry point without a workspace: same checks, plus the limits of its static scratch (all before any GPU call)
+    na = lambda **kw: lib.duo_spec_sample_noalloc(kw.get("lg", 0x1000), kw.get("root", 0x1000), kw.get("V", 32000), 0x1000,
+                                                  kw.get("q", 0x1000), 0x1000, C.byref(kw.get("call", call)), C.byref(res), None)
+    assert na(lg=None) == -1 and na(root=None) == -1 and na(q=None) == -1 and na(V=1) == -2
+    assert na(V=B.NOALLOC_MAX_VOCAB + 1) == -9
+    assert na(call=B.Call(1, 8, 1.0, 0, -1, 0, 0.9)) == -9            # the nucleus search needs rows the scratch does not hold
+    assert na(call=B.Call(1, 0, 1.0, 0, -1, 0)) == -2 and na(call=B.Call(1, 8, -1.0, 0, -1, 0)) == -8
     # the deferred form takes an empty suffix (k = 0) but no negative one; n must be 1
     ds = lambda c, **kw: lib.duo_deferred_sample(kw.get("lg", 0x1000), 0x1000, 32000, kw.get("toks", 0x1000), 0x1000, kw.get("u", 0x1000),
                                                  None, None, None, 0, C.byref(c), C.byref(res), 0x1000, out.value, None)
