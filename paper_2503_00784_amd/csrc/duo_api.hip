@@ -27,6 +27,8 @@ constexpr size_t NOALLOC_PRUN_BYTES = (size_t)DUO_NOALLOC_MAX_VOCAB * sizeof(dou
 constexpr size_t NOALLOC_ACC_BYTES = 512;  // DUO_MAX_ROWS accept flags
 static_assert(NOALLOC_STATS_BYTES % 256 == 0 && NOALLOC_PRUN_BYTES % 256 == 0 && DUO_MAX_ROWS * sizeof(int32_t) <= NOALLOC_ACC_BYTES,
               "the three parts keep the array's alignment");
+static_assert(((size_t)(DUO_MAX_ROWS + 1) * STATS_SPLIT + ROOT_STATS_PARTS) * 2 * sizeof(double) <= NOALLOC_STATS_BYTES,
+              "row and root statistics fit their part");
 constexpr size_t NOALLOC_SCRATCH_BYTES = NOALLOC_STATS_BYTES + NOALLOC_PRUN_BYTES + NOALLOC_ACC_BYTES;
 static_assert(NOALLOC_SCRATCH_BYTES == DUO_NOALLOC_SCRATCH_BYTES, "the header states the array's size");
 static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
@@ -68,7 +70,9 @@ struct Workspace {
     float* rope_c;   // [Mp][D/2]
     float* rope_s;
     float* logits;   // fp32 [Mp][V]
-    double* stats;   // sampler
+    double* stats_rows;  // sampler: partial softmax statistics [DUO_MAX_ROWS + 1][stats_parts][2]
+    double* stats_root;  // [STATS_SPLIT][2]
+    int stats_parts;
     double* p_run;
     double* nuc;     // nucleus records [DUO_MAX_ROWS + 1][4]
     double* p_rows;  // nucleus search scratch [DUO_MAX_ROWS + 1][vocab]
@@ -81,15 +85,25 @@ struct Workspace {
     size_t total;
 };
 
-size_t sample_ws_bytes(int vocab) {
-    return align_up((size_t)2 * DUO_MAX_ROWS * STATS_SPLIT * 2 * sizeof(double), 256) + align_up((size_t)vocab * sizeof(double), 256) +
+// Partial statistics per judging row: the LM head's epilogue leaves one part per tile of 32 vocabulary entries, the
+// statistics kernel of the sampling-only entry points STATS_SPLIT parts.
+int lm_head_parts(int vocab) { return (vocab + 31) / 32; }
+size_t stats_bytes(int parts) {
+    return align_up((size_t)(DUO_MAX_ROWS + 1) * parts * 2 * sizeof(double), 256) + align_up((size_t)ROOT_STATS_PARTS * 2 * sizeof(double), 256);
+}
+
+size_t sample_ws_bytes(int vocab, int parts = STATS_SPLIT) {
+    return stats_bytes(parts) + align_up((size_t)vocab * sizeof(double), 256) +
            align_up((size_t)DUO_MAX_ROWS * sizeof(int32_t), 256) + align_up((size_t)(DUO_MAX_ROWS + 1) * 4 * sizeof(double), 256) +
            align_up((size_t)(DUO_MAX_ROWS + 1) * vocab * sizeof(double), 256);
 }
 
-void carve_sampler(char* base, size_t& off, int vocab, Workspace& ws) {
-    ws.stats = reinterpret_cast<double*>(base + off);
-    off += align_up((size_t)2 * DUO_MAX_ROWS * STATS_SPLIT * 2 * sizeof(double), 256);
+void carve_sampler(char* base, size_t& off, int vocab, Workspace& ws, int parts = STATS_SPLIT) {
+    ws.stats_parts = parts;
+    ws.stats_rows = reinterpret_cast<double*>(base + off);
+    off += align_up((size_t)(DUO_MAX_ROWS + 1) * parts * 2 * sizeof(double), 256);
+    ws.stats_root = reinterpret_cast<double*>(base + off);
+    off += align_up((size_t)ROOT_STATS_PARTS * 2 * sizeof(double), 256);
     ws.p_run = reinterpret_cast<double*>(base + off);
     off += align_up((size_t)vocab * sizeof(double), 256);
     ws.acc = reinterpret_cast<int32_t*>(base + off);
@@ -129,7 +143,7 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.ssq_full = reinterpret_cast<float*>(take(Mp * RowScale::FULL_PARTS * 4));
     ws.split = reinterpret_cast<float*>(take((size_t)(many ? block_splits(max_rows, c.d_model) : WIDE_MAX_SPLIT) * Mp * d * 4));
     ws.h_last = reinterpret_cast<u16*>(take(16 * d * 2));
-    carve_sampler(base, off, c.vocab, ws);
+    carve_sampler(base, off, c.vocab, ws, lm_head_parts(c.vocab));
     ws.total = off;
     return ws;
 }
@@ -269,9 +283,12 @@ void launch_attention_shared(int mtw, int nwv, dim3 grid, const AttnArgs& a, hip
 
 // The target pass over the rows of `plan`: fills the cache slots P .. P+M-1 and writes fp32
 // logits [M][V] (row stride V) to `logits`.
+// `temperature` >= 0: the pass is followed by sampling at that temperature, so the LM head also leaves the softmax
+// statistics of its rows (ws.stats_rows) and, without a root row, the first kernel those of the cached root logits
+// (ws.stats_root); < 0: logits only.
 void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_kv_cache& cache,
                      const int32_t* tokens, int root_token, const RowPlan& plan, const Workspace& ws,
-                     float* logits, int32_t* status, hipStream_t s) {
+                     float* logits, int32_t* status, hipStream_t s, double temperature = -1.0) {
     const int M = plan.M, Mp = (M + 15) / 16 * 16, PR = pair_rows_for(M), AT = a_tiles_for(M, true);
     const int d = c.d_model, D = c.head_dim, half = D / 2, Hq = c.n_q_heads, Hkv = c.n_kv_heads;
     const int qd = Hq * D, F = c.d_ff, V = c.vocab, group = Hq / Hkv;
@@ -284,8 +301,11 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const bool o_split = residual_is_split(M, qd, d), down_split = residual_is_split(M, F, d);
     const bool many = M > DUO_MAX_ROWS;  // prefill pass: logits of the last row only (to logits[0 .. V))
     const int max_chunks = many ? MAX_CHUNKS_MANY_ROWS : MAX_CHUNKS;
+    const bool stats = temperature >= 0.0;
+    const bool root_stats = stats && plan.R == 0;
     prof(DUO_PROF_SETUP, s);
-    DUO_LAUNCH(rope_table_kernel, dim3(M), dim3(64), s, plan, D, (double)c.rope_theta, ws.rope_c, ws.rope_s, status);
+    DUO_LAUNCH(rope_table_kernel, dim3(M + (root_stats ? ROOT_STATS_PARTS : 0)), dim3(256), s, plan, D, (double)c.rope_theta, ws.rope_c,
+               ws.rope_s, status, RootStatsArgs{root_stats ? cache.root_logits : nullptr, V, temperature, ws.stats_root});
     prof(DUO_PROF_SETUP, s);
     DUO_LAUNCH(embed_kernel, dim3(M), dim3(256), s, w.embed, tokens, root_token, plan, V, cache.prefix_len,
                        status, ws.x, w.g_attn[0], ws.h, d, PR, AT, ws.ssq, ws.ssq_full);
@@ -398,8 +418,13 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         launch_projection<2>(DUO_PROF_LMHEAD, 1, ws.h_last, w.lm_head, d, (V + 31) / 32, last, el, s);
         return;
     }
-    EpiStoreF32 el{V, M, 2, logits, V};
-    launch_projection<2>(DUO_PROF_LMHEAD, M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
+    if (stats) {
+        EpiLogitsStats el{V, M, 2, logits, V, ws.stats_rows, ws.stats_parts, temperature};
+        launch_projection<2>(DUO_PROF_LMHEAD, M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
+    } else {
+        EpiStoreF32 el{V, M, 2, logits, V};
+        launch_projection<2>(DUO_PROF_LMHEAD, M, ws.h, w.lm_head, d, (V + 31) / 32, down_split ? norm_full : norm_part, el, s);
+    }
 }
 
 // Nucleus sampling is on for 0 < top_p < 1 at a positive temperature (at temperature 0 the distribution is one-hot).
@@ -415,10 +440,13 @@ void enqueue_nucleus(const SampleArgs& sa, float top_p, const Workspace& ws, hip
         DUO_LAUNCH(sample_nucleus_kernel<0>, dim3(1 + sa.n * sa.k), dim3(SAMPLE_THREADS), s, sa, (double)top_p, ws.p_rows, ws.nuc);
 }
 
+// have_stats: the forward pass that produced the logits left their softmax statistics (and the root row's) already
 void enqueue_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, int mode, u16* kc, u16* vc,
-                      const duo_model_config* c, int32_t* prefix_len, hipStream_t s) {
-    prof(DUO_PROF_SAMPLE, s);
-    DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, sa.n, STATS_SPLIT), dim3(256), s, sa);
+                      const duo_model_config* c, int32_t* prefix_len, hipStream_t s, bool have_stats = false) {
+    if (!have_stats) {
+        prof(DUO_PROF_SAMPLE, s);
+        DUO_LAUNCH(sample_stats_kernel, dim3(sa.R + sa.n * sa.k + (sa.R ? 0 : 1), STATS_SPLIT), dim3(256), s, sa);
+    }
     enqueue_nucleus(sa, top_p, ws, s);
     prof(DUO_PROF_SAMPLE, s);
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST) {
@@ -501,14 +529,16 @@ int spec_sample_on_scratch(const float* logits, const float* root_logits, int vo
     if ((rc = scratch_of_current_device(&base))) return rc;
     Workspace ws{};
     char* b = static_cast<char*>(base);
-    ws.stats = reinterpret_cast<double*>(b);
+    ws.stats_parts = STATS_SPLIT;
+    ws.stats_rows = reinterpret_cast<double*>(b);
+    ws.stats_root = ws.stats_rows + (size_t)(DUO_MAX_ROWS + 1) * STATS_SPLIT * 2;
     ws.p_run = reinterpret_cast<double*>(b + NOALLOC_STATS_BYTES);
     ws.acc = reinterpret_cast<int32_t*>(b + NOALLOC_STATS_BYTES + NOALLOC_PRUN_BYTES);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
     DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     SampleArgs sa{logits, vocab, root_logits, vocab, call->n, call->k, R, call->host_prefix_len, (double)call->temperature,
-                  draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
+                  draft_tokens, draft_probs, uniforms, ws.stats_rows, ws.stats_parts, ws.stats_root, STATS_SPLIT, ws.acc, ws.p_run, out->accept_len, out->next_token,
                   out->commit, out->status, nullptr};
     enqueue_sampling(sa, call->top_p, ws, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
     return hip_ok(hipGetLastError(), "duo_spec_sample_noalloc launch");
@@ -551,12 +581,12 @@ int duo_verify(const duo_model_config* cfg, const duo_weights* w, duo_kv_cache* 
     (void)hipGetLastError();
     const RowPlan plan{call->host_prefix_len, R, call->n, call->k, M};  // the pass's first kernel clears *status
     float* logits = out->logits_out ? out->logits_out : ws.logits;
-    enqueue_forward(*cfg, *w, *cache, draft_tokens, call->root_token, plan, ws, logits, out->status, s);
+    enqueue_forward(*cfg, *w, *cache, draft_tokens, call->root_token, plan, ws, logits, out->status, s, (double)call->temperature);
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, call->n, call->k, R, call->host_prefix_len,
-                  (double)call->temperature, draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run,
+                  (double)call->temperature, draft_tokens, draft_probs, uniforms, ws.stats_rows, ws.stats_parts, ws.stats_root, ROOT_STATS_PARTS, ws.acc, ws.p_run,
                   out->accept_len, out->next_token, out->commit, out->status,
                   nucleus_on(call) ? ws.nuc : nullptr};
-    enqueue_sampling(sa, call->top_p, ws, call->select_mode, cache->k, cache->v, cfg, cache->prefix_len, s);
+    enqueue_sampling(sa, call->top_p, ws, call->select_mode, cache->k, cache->v, cfg, cache->prefix_len, s, true);
     return hip_ok(hipGetLastError(), "duo_verify launch");
 }
 
@@ -609,7 +639,7 @@ int duo_spec_sample(const float* logits, const float* root_logits, int vocab, co
     (void)hipGetLastError();
     DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     SampleArgs sa{logits, vocab, root_logits, vocab, call->n, call->k, R, call->host_prefix_len, (double)call->temperature,
-                  draft_tokens, draft_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
+                  draft_tokens, draft_probs, uniforms, ws.stats_rows, ws.stats_parts, ws.stats_root, STATS_SPLIT, ws.acc, ws.p_run, out->accept_len, out->next_token,
                   out->commit, out->status,
                   nucleus_on(call) ? ws.nuc : nullptr};
     enqueue_sampling(sa, call->top_p, ws, call->select_mode, nullptr, nullptr, nullptr, nullptr, s);
@@ -634,9 +664,11 @@ static int check_deferred(const duo_call* call, int vocab, const int32_t* first_
 }
 
 static void enqueue_deferred_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, const DeferredArgs& da,
-                                      hipStream_t s) {
-    prof(DUO_PROF_SAMPLE, s);
-    DUO_LAUNCH(sample_stats_kernel, dim3(sa.k + 1, 1, STATS_SPLIT), dim3(256), s, sa);
+                                      hipStream_t s, bool have_stats = false) {
+    if (!have_stats) {
+        prof(DUO_PROF_SAMPLE, s);
+        DUO_LAUNCH(sample_stats_kernel, dim3(sa.R + sa.k + (sa.R ? 0 : 1), STATS_SPLIT), dim3(256), s, sa);
+    }
     enqueue_nucleus(sa, top_p, ws, s);
     prof(DUO_PROF_SAMPLE, s);
     if (sa.nuc) DUO_LAUNCH(sample_deferred_kernel<true>, dim3(1), dim3(SAMPLE_THREADS), s, sa, da);
@@ -670,16 +702,17 @@ int duo_verify_deferred(const duo_model_config* cfg, const duo_weights* w, duo_k
     if (M > 0) {
         // an empty suffix leaves the root token as the pass's only row (the plan's k is then never used as a divisor)
         const RowPlan plan{call->host_prefix_len, R, 1, call->k > 0 ? call->k : 1, M};  // the pass's first kernel clears *status
-        enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s);
+        enqueue_forward(*cfg, *w, *cache, unverified_tokens, call->root_token, plan, ws, logits, out->status, s, (double)call->temperature);
     } else {
         // nothing to score: the cached root logits judge the new sequences; only the device-side input check runs
         DUO_LAUNCH(status_init_kernel, dim3(1), dim3(64), s, out->status, cache->prefix_len, call->host_prefix_len);
     }
     SampleArgs sa{logits, cfg->vocab, cache->root_logits, cfg->vocab, 1, call->k, R, call->host_prefix_len,
-                  (double)call->temperature, unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run,
+                  (double)call->temperature, unverified_tokens, unverified_probs, uniforms, ws.stats_rows, ws.stats_parts, ws.stats_root, M > 0 ? ROOT_STATS_PARTS : STATS_SPLIT, ws.acc, ws.p_run,
                   out->accept_len, out->next_token, out->commit, out->status,
                   nucleus_on(call) ? ws.nuc : nullptr};
-    enqueue_deferred_sampling(sa, call->top_p, ws, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, cache->prefix_len}, s);
+    enqueue_deferred_sampling(sa, call->top_p, ws, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, cache->prefix_len}, s,
+                              M > 0);  // a pass that scored rows left their statistics and the root logits'
     return hip_ok(hipGetLastError(), "duo_verify_deferred launch");
 }
 
@@ -703,7 +736,7 @@ int duo_deferred_sample(const float* logits, const float* root_logits, int vocab
     (void)hipGetLastError();
     DUO_LAUNCH(fill_i32_kernel, dim3(1), dim3(64), s, out->status, 1, 0);
     SampleArgs sa{logits, vocab, root_logits, vocab, 1, call->k, R, call->host_prefix_len, (double)call->temperature,
-                  unverified_tokens, unverified_probs, uniforms, ws.stats, ws.acc, ws.p_run, out->accept_len, out->next_token,
+                  unverified_tokens, unverified_probs, uniforms, ws.stats_rows, ws.stats_parts, ws.stats_root, STATS_SPLIT, ws.acc, ws.p_run, out->accept_len, out->next_token,
                   out->commit, out->status,
                   nucleus_on(call) ? ws.nuc : nullptr};
     enqueue_deferred_sampling(sa, call->top_p, ws, DeferredArgs{first_tokens, first_probs, uniforms_first, s_new, nullptr}, s);

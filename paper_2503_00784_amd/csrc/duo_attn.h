@@ -665,9 +665,15 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
         }
     };
 
+    // No row of this wave sees a key behind the slot of the wave's last query row: such blocks are masked for all of its
+    // rows, so the wave leaves out their products and softmax (a prompt chunk's early rows against the chunk's late
+    // keys: causal attention per query tile, not only per workgroup) and only keeps the ring's pace.
+    const int r_wave_last = min(MQ, (tile0 + MTW) * 16) - 1;
+    const int kb_last = r_wave_last >= 0 ? a.plan.P + r_wave_last / a.group : -1;  // key slot of that row
     __syncthreads();  // block 0 is in LDS
     for (int ib = 0; ib < nb; ++ib) {
-        use_block(lds_kv[ib % NBUF], (b0 + ib) * 32);
+        const int kb = (b0 + ib) * 32;
+        if (kb <= kb_last) use_block(lds_kv[ib % NBUF], kb);  // wave-uniform
         __syncthreads();  // block ib + 1 is in LDS; block ib's buffer may be refilled
     }
 

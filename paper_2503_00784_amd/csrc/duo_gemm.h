@@ -509,6 +509,109 @@ struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile
     }
 };
 
+// LM head of the verify step (Alg. 2 works on p = softmax(logits / T)): stores the fp32 logits like EpiStoreF32 and,
+// from the same registers, the softmax statistics of every row over this tile's 16 * NT columns, in double: the max
+// of z = logit / T and sum exp(z - max), or at T == 0 (the greedy limit) the largest logit and the lowest id that
+// attains it.  parts [M][nparts][2], part index = tile; the sampling kernels merge a row's parts in index order.
+struct EpiLogitsStats {
+    static constexpr const char* NAME = "EpiLogitsStats";
+    int N, M, NT;
+    float* Y;
+    int ldy;
+    double* parts;
+    int nparts;
+    double T;
+    struct Pre {};
+    __device__ __forceinline__ void arm() {}
+    __device__ __forceinline__ void prefetch(int, int, int, Pre&) const {}
+    // one row's statistics from this lane's `cnt` values z (ids id[]), combined over the lanes `masks` apart
+    template <int CNT, int NMASK>
+    __device__ __forceinline__ void row_stats(const float (&x)[CNT], const int (&id)[CNT], const int (&masks)[NMASK], bool writer,
+                                              double* out) const {
+        double mx = -INFINITY;
+        if (T == 0.0) {
+#pragma unroll
+            for (int e = 0; e < CNT; ++e)
+                if (id[e] < N) mx = fmax(mx, (double)x[e]);
+#pragma unroll
+            for (int q = 0; q < NMASK; ++q) mx = fmax(mx, __shfl_xor(mx, masks[q], 64));
+            double first = 4.0e9;
+#pragma unroll
+            for (int e = 0; e < CNT; ++e)
+                if (id[e] < N && (double)x[e] == mx) first = fmin(first, (double)id[e]);
+#pragma unroll
+            for (int q = 0; q < NMASK; ++q) first = fmin(first, __shfl_xor(first, masks[q], 64));
+            if (writer) {
+                out[0] = mx;
+                out[1] = first;
+            }
+            return;
+        }
+        double z[CNT];
+#pragma unroll
+        for (int e = 0; e < CNT; ++e) {
+            z[e] = (double)x[e] / T;
+            if (id[e] < N) mx = fmax(mx, z[e]);
+        }
+#pragma unroll
+        for (int q = 0; q < NMASK; ++q) mx = fmax(mx, __shfl_xor(mx, masks[q], 64));
+        double sum = 0.0;
+#pragma unroll
+        for (int e = 0; e < CNT; ++e)
+            if (id[e] < N) sum += exp(z[e] - mx);
+#pragma unroll
+        for (int q = 0; q < NMASK; ++q) sum += __shfl_xor(sum, masks[q], 64);
+        if (writer) {
+            out[0] = mx;
+            out[1] = sum;
+        }
+    }
+    // rows 4*qi .. +3, column c of each band: the tile's 16 columns sit in 16 consecutive lanes (all of them call this)
+    template <int NTT>
+    __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[NTT], const Pre&, bool) const {
+        const int masks[4] = {8, 4, 2, 1};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = qi * 4 + i;
+            float x[NTT];
+            int id[NTT];
+#pragma unroll
+            for (int t = 0; t < NTT; ++t) {
+                x[t] = v[t][i];
+                id[t] = (tile * NT + t) * 16 + c;
+                if (m < M && id[t] < N) Y[(size_t)m * ldy + id[t]] = x[t];
+            }
+            row_stats<NTT, 4>(x, id, masks, c == 0 && m < M, parts + ((size_t)(m < M ? m : 0) * nparts + tile) * 2);
+        }
+    }
+    // row m, columns c4 .. c4+3 of each band: the tile's columns sit in the four lanes 16 apart that share the row
+    template <int NTT>
+    __device__ __forceinline__ void store4(int tile, int m, int c4, const f32x4 (&v)[NTT]) const {
+        if (m >= M) return;  // the four lanes of a row leave together
+        float* y = Y + (size_t)m * ldy;
+        float x[NTT * 4];
+        int id[NTT * 4];
+#pragma unroll
+        for (int t = 0; t < NTT; ++t) {
+            const int n = (tile * NT + t) * 16 + c4;
+            if (n + 3 < N && (ldy & 3) == 0) {
+                *reinterpret_cast<f32x4*>(y + n) = v[t];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n + i < N) y[n + i] = v[t][i];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[t * 4 + i] = v[t][i];
+                id[t * 4 + i] = n + i;
+            }
+        }
+        const int masks[2] = {16, 32};
+        row_stats<NTT * 4, 2>(x, id, masks, c4 == 0, parts + ((size_t)m * nparts + tile) * 2);
+    }
+};
+
 // x[m][n] += sum (fp32 residual stream, each element owned by one workgroup).  The same thread then
 // prepares the next RMSNorm (see RowScale): u = x * gain as a bf16 pair into the next projection's
 // operand buffer, and the tile's partial sum of x^2 per row.  One band per workgroup (NT = 1).

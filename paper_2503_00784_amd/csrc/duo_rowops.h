@@ -2,6 +2,7 @@
 #pragma once
 #include "duo_common.h"
 #include "duo_gemm.h"
+#include "duo_sample.h"
 
 // Sum of `v` over the NWV * 64 threads of a workgroup in a fixed order (lanes by butterfly, then the waves
 // in index order); thread 0 stores it.
@@ -139,12 +140,34 @@ static inline void launch_residual_reduce(int M, const float* part, int S, size_
 }
 
 // cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.  As the first kernel of a
-// pass it also clears the status word that the later kernels OR their flags into.
-__global__ void rope_table_kernel(RowPlan plan, int D, double theta, float* __restrict__ rc, float* __restrict__ rs,
-                                  int32_t* status) {
+// pass it also clears the status word that the later kernels OR their flags into, and, for a pass that will be
+// followed by sampling from cached root logits (root.logits != nullptr), its last ROOT_STATS_PARTS workgroups leave the
+// softmax statistics of those logits, slice by slice (see SampleArgs in duo_sample.h): work that is off the
+// critical path here and would otherwise need a launch of its own.
+struct RootStatsArgs {
+    const float* logits;  // fp32 [V], or nullptr: no statistics wanted
+    int V;
+    double T;
+    double* out;  // [ROOT_STATS_PARTS][2]
+};
+
+__global__ __launch_bounds__(256) void rope_table_kernel(RowPlan plan, int D, double theta, float* __restrict__ rc,
+                                                          float* __restrict__ rs, int32_t* status, RootStatsArgs root) {
+    __shared__ double sm[16];
     const int m = blockIdx.x, half = D / 2;
     if (m == 0 && threadIdx.x == 0 && status) *status = 0;
-    if (m >= plan.M) return;
+    if (m >= plan.M) {  // statistics of one slice of the root logits
+        if (!root.logits) return;
+        const int sl = m - plan.M, len = (root.V + ROOT_STATS_PARTS - 1) / ROOT_STATS_PARTS;
+        const int v0 = sl * len, v1 = min(root.V, v0 + len);
+        double zmax, Z;
+        slice_stats(root.logits, v0, v1, root.T, sm, zmax, Z);
+        if (threadIdx.x == 0) {
+            root.out[2 * sl] = zmax;
+            root.out[2 * sl + 1] = Z;
+        }
+        return;
+    }
     for (int d = threadIdx.x; d < half; d += blockDim.x) {
         const double ang = (double)plan.pos(m) * pow(theta, -2.0 * (double)d / (double)D);
         rc[m * half + d] = (float)cos(ang);

@@ -3,8 +3,9 @@
 // All probabilities are evaluated in double from the fp32 logits, so that the accept decision
 // u * q(t) < p(t) and the inverse-CDF draws are taken in the precision a plain reference uses;
 // the volumes are tiny next to the weight stream (two passes over a few vocabulary rows).
-//   sample_stats_kernel   max and normaliser of softmax(logits / T) for every judging distribution
-//                         (i, j), the vocabulary cut into slices for parallelism
+//   sample_stats_kernel   max and normaliser of softmax(logits / T) for every row of logits, the vocabulary cut into
+//                         slices for parallelism (caller-supplied logits only: in the verify step the LM head's
+//                         epilogue leaves these statistics, one part per 32-column tile, see EpiLogitsStats)
 //   sample_finish_kernel  one workgroup per sequence: accept flags, leading accepts, then the
 //                         correction token from norm(max(0, p - q)) or the bonus token from p
 //   sample_paper_kernel   the sequential first-token rule over the n sequences, with the
@@ -35,8 +36,14 @@ struct SampleArgs {
     const int32_t* tokens;  // [n][k]
     const float* q;         // [n][k][V]
     const float* u;         // [n][k+1]
-    double* stats;          // [n][k+1][STATS_SPLIT][2]: per vocabulary slice, max of z = logit / T and sum exp(z - max);
-                            // greedy: max logit and the lowest id that attains it
+    // Softmax statistics of the judging rows, as partial results over slices of the vocabulary: per slice the max of
+    // z = logit / T and sum exp(z - max) (greedy: the max logit and the lowest id that attains it).  stats_rows
+    // [R + n*k][parts][2] belongs to the rows of `logits`: written by the LM head's epilogue (one part per 32-column
+    // tile) or by sample_stats_kernel (STATS_SPLIT parts); stats_root [root_parts][2] to root_logits (R == 0).
+    double* stats_rows;
+    int parts;
+    double* stats_root;
+    int root_parts;  // STATS_SPLIT from sample_stats_kernel, ROOT_STATS_PARTS from the verify pass's first kernel
     int32_t* acc;           // [n][k] accept flags
     double* p_run;          // [V] running distribution of the sequential rule
     int32_t* accept_len;    // [n]
@@ -45,6 +52,8 @@ struct SampleArgs {
     int32_t* status;
     const double* nuc;      // nucleus records [1 + n*k][4] (threshold key, last tied id, kept mass, -), or nullptr
     __device__ __forceinline__ int nuc_row(int i, int j) const { return j == 0 ? 0 : 1 + i * k + (j - 1); }
+    // row of `logits` that judges draft (i, j), or -1 for root_logits
+    __device__ __forceinline__ int judge_index(int i, int j) const { return j == 0 ? (R ? 0 : -1) : R + i * k + j - 1; }
     __device__ __forceinline__ const float* judge_row(int i, int j) const {
         if (j == 0) return R ? logits : root_logits;
         return logits + (size_t)(R + i * k + j - 1) * ld;
@@ -98,7 +107,8 @@ __device__ __forceinline__ Nucleus nucleus_of(const SampleArgs& a, int i, int j)
 }
 
 constexpr int SAMPLE_THREADS = 1024;
-constexpr int STATS_SPLIT = 8;  // workgroups per judging distribution in sample_stats_kernel
+constexpr int STATS_SPLIT = 8;        // workgroups per row of logits in sample_stats_kernel
+constexpr int ROOT_STATS_PARTS = 32;  // slices of the cached root logits when the verify pass's first kernel takes their statistics
 
 __device__ __forceinline__ double block_sum_d(double v, double* sm) {
     v = wave_sum(v);
@@ -121,72 +131,104 @@ __device__ __forceinline__ double block_max_d(double v, double* sm) {
     return t;
 }
 
-// grid (k+1, n, STATS_SPLIT): slice s of the judging distribution (i, j)
-__global__ __launch_bounds__(256) void sample_stats_kernel(SampleArgs a) {
-    __shared__ double sm[16];
-    const int j = blockIdx.x, i = blockIdx.y, sl = blockIdx.z;
-    const float* row = a.judge_row(i, j);
-    const int len = (a.V + STATS_SPLIT - 1) / STATS_SPLIT;
-    const int v0 = sl * len, v1 = min(a.V, v0 + len);
+// Statistics of one slice [v0, v1) of a row of logits (all 256 threads of the workgroup): zmax and Z as SampleArgs
+// describes them.
+__device__ __forceinline__ void slice_stats(const float* __restrict__ row, int v0, int v1, double T, double* sm, double& zmax,
+                                            double& Z) {
     float lm = -INFINITY;
     for (int v = v0 + threadIdx.x; v < v1; v += 256) lm = fmaxf(lm, row[v]);
-    double zmax, Z;
-    if (a.greedy()) {  // Z: the lowest id of the slice that holds the slice's largest logit
+    if (T == 0.0) {  // Z: the lowest id of the slice that holds the slice's largest logit
         zmax = block_max_d((double)lm, sm);
-        int first = a.V;
+        int first = 0x7fffffff;
         for (int v = v0 + threadIdx.x; v < v1; v += 256)
             if ((double)row[v] == zmax) first = min(first, v);
         Z = -block_max_d(-(double)first, sm);
     } else {
-        zmax = block_max_d((double)lm, sm) / a.T;
+        zmax = block_max_d((double)lm, sm) / T;
         double s = 0.0;
-        for (int v = v0 + threadIdx.x; v < v1; v += 256) s += exp((double)row[v] / a.T - zmax);
+        for (int v = v0 + threadIdx.x; v < v1; v += 256) s += exp((double)row[v] / T - zmax);
         Z = block_sum_d(s, sm);
     }
+}
+
+// grid (R + n*k + (R ? 0 : 1), STATS_SPLIT): slice sl of row r of `logits`, the last row index being root_logits when
+// there is no root row.  Used when the logits come from the caller; the verify step's LM head leaves the same
+// statistics itself (EpiLogitsStats in duo_gemm.h) and the pass's first kernel those of root_logits.
+__global__ __launch_bounds__(256) void sample_stats_kernel(SampleArgs a) {
+    __shared__ double sm[16];
+    const int r = blockIdx.x, sl = blockIdx.y, rows = a.R + a.n * a.k;
+    const float* row = r < rows ? a.logits + (size_t)r * a.ld : a.root_logits;
+    const int len = (a.V + STATS_SPLIT - 1) / STATS_SPLIT;
+    const int v0 = sl * len, v1 = min(a.V, v0 + len);
+    double zmax, Z;
+    slice_stats(row, v0, v1, a.T, sm, zmax, Z);
     if (threadIdx.x == 0) {
-        double* st = a.stats + (((size_t)i * (a.k + 1) + j) * STATS_SPLIT + sl) * 2;
+        double* st = (r < rows ? a.stats_rows + ((size_t)r * a.parts + sl) * 2 : a.stats_root + sl * 2);
         st[0] = zmax;
         st[1] = Z;
-        if (sl == 0 && j < a.k) {
-            const int raw = a.tokens[i * a.k + j];
+        const int t = r - a.R;  // the draft token this row belongs to
+        if (sl == 0 && t >= 0 && t < a.n * a.k) {
+            const int raw = a.tokens[t];
             if ((raw < 0 || raw >= a.V) && a.status) atomicOr(a.status, 1);
         }
     }
 }
 
-// max and normaliser of judging distribution (i, j): the slices merged in slice order
-__device__ __forceinline__ void merged_stats(const SampleArgs& a, int i, int j, double& zmax, double& Z) {
-    const double* st = a.stats + ((size_t)i * (a.k + 1) + j) * STATS_SPLIT * 2;
-    zmax = st[0];
-    for (int s = 1; s < STATS_SPLIT; ++s) zmax = fmax(zmax, st[2 * s]);
-    Z = 0.0;
-    for (int s = 0; s < STATS_SPLIT; ++s)
-        if (st[2 * s + 1] > 0.0) Z += st[2 * s + 1] * exp(st[2 * s] - zmax);
+// The merged statistics of the judging rows of one sequence, position j -> {zmax, Z} (greedy: {max logit, arg max}),
+// kept in shared memory by the kernels below.
+struct SeqStats {
+    double (*t)[2];
+};
+
+// Merge of the partial statistics of judging rows (i, j0 .. j1) into st.t[j]: one wave per row, lanes stride over the
+// parts, fixed butterflies (deterministic).  All threads of the workgroup call it; ends with a barrier.
+__device__ __forceinline__ void load_seq_stats(const SampleArgs& a, int i, int j0, int j1, const SeqStats& st) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    for (int j = j0 + wave; j <= j1; j += nw) {
+        const int jr = a.judge_index(i, j);
+        const double* pt = jr < 0 ? a.stats_root : a.stats_rows + (size_t)jr * a.parts * 2;
+        const int np = jr < 0 ? a.root_parts : a.parts;
+        double mx = -INFINITY;
+#pragma unroll 4
+        for (int p = lane; p < np; p += 64) mx = fmax(mx, pt[2 * p]);
+        mx = wave_max(mx);
+        double Z;
+        if (a.greedy()) {  // the lowest id among the parts that hold the largest logit (parts are in id order)
+            double first = 4.0e9;
+            for (int p = lane; p < np; p += 64)
+                if (pt[2 * p] == mx) first = fmin(first, pt[2 * p + 1]);
+            Z = -wave_max(-first);
+        } else {
+            double sum = 0.0;
+#pragma unroll 4
+            for (int p = lane; p < np; p += 64)
+                if (pt[2 * p + 1] > 0.0) sum += pt[2 * p + 1] * exp(pt[2 * p] - mx);
+            Z = wave_sum(sum);
+        }
+        if (lane == 0) {
+            st.t[j][0] = mx;
+            st.t[j][1] = Z;
+        }
+    }
+    __syncthreads();
 }
 
-// greedy: the arg max of judging distribution (i, j), lowest id among equal logits (slices are in id order)
-__device__ __forceinline__ int merged_argmax(const SampleArgs& a, int i, int j) {
-    const double* st = a.stats + ((size_t)i * (a.k + 1) + j) * STATS_SPLIT * 2;
-    double best = st[0];
-    int arg = (int)st[1];
-    for (int s = 1; s < STATS_SPLIT; ++s)
-        if (st[2 * s] > best) {
-            best = st[2 * s];
-            arg = (int)st[2 * s + 1];
-        }
-    return arg;
+__device__ __forceinline__ void merged_stats(const SeqStats& st, int j, double& zmax, double& Z) {
+    zmax = st.t[j][0];
+    Z = st.t[j][1];
 }
+__device__ __forceinline__ int merged_argmax(const SeqStats& st, int j) { return (int)st.t[j][1]; }
 
 // p_run[v] = p(v) of judging distribution (i, j) for the whole vocabulary; ends with a barrier
 template <bool NUC>
-__device__ __forceinline__ void fill_running_distribution(const SampleArgs& a, int i, int j) {
+__device__ __forceinline__ void fill_running_distribution(const SampleArgs& a, const SeqStats& st, int i, int j) {
     const float* row = a.judge_row(i, j);
     if (a.greedy()) {
-        const int amax = merged_argmax(a, i, j);
+        const int amax = merged_argmax(st, j);
         for (int v = threadIdx.x; v < a.V; v += blockDim.x) a.p_run[v] = v == amax ? 1.0 : 0.0;
     } else {
         double zmax, Z;
-        merged_stats(a, i, j, zmax, Z);
+        merged_stats(st, j, zmax, Z);
         const Nucleus nc = nucleus_of<NUC>(a, i, j);
         for (int v = threadIdx.x; v < a.V; v += blockDim.x)
             a.p_run[v] = nc.apply(exp((double)row[v] / a.T - zmax) / Z, row[v], v);
@@ -206,12 +248,15 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_nucleus_kernel(SampleAr
                                                                         double* __restrict__ nuc_out) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[SAMPLE_THREADS / 64 + 2];
+    __shared__ double sm_st[DUO_MAX_ROWS + 1][2];
+    const SeqStats st{sm_st};
     const int r = blockIdx.x, tid = threadIdx.x;
     const int i = r == 0 ? 0 : (r - 1) / a.k, j = r == 0 ? 0 : (r - 1) % a.k + 1;
     const float* row = a.judge_row(i, j);
     double* prow = prow_all + (size_t)r * a.V;
+    load_seq_stats(a, i, j, j, st);
     double zmax, Z;
-    merged_stats(a, i, j, zmax, Z);
+    merged_stats(st, j, zmax, Z);
     constexpr int NR = PT > 0 ? PT : 1;
     uint32_t rk[NR];  // PT > 0: this thread's keys and probabilities, ids tid + e * 1024 (beyond the vocabulary: none)
     double rp[NR];
@@ -305,17 +350,17 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_nucleus_kernel(SampleAr
 
 // accept flags of sequence i, positions from..k-1 (one thread each), into acc[]; ends with a barrier
 template <bool NUC>
-__device__ __forceinline__ void accept_flags(const SampleArgs& a, int i, int from) {
+__device__ __forceinline__ void accept_flags(const SampleArgs& a, const SeqStats& st, int i, int from) {
     const int j = from + threadIdx.x;
     if (j < a.k) {
         const float* row = a.judge_row(i, j);
         const int t = a.token(i, j);
         double p_t;
         if (a.greedy()) {
-            p_t = t == merged_argmax(a, i, j) ? 1.0 : 0.0;
+            p_t = t == merged_argmax(st, j) ? 1.0 : 0.0;
         } else {
             double zmax, Z;
-            merged_stats(a, i, j, zmax, Z);
+            merged_stats(st, j, zmax, Z);
             p_t = nucleus_of<NUC>(a, i, j).apply(exp((double)row[t] / a.T - zmax) / Z, row[t], t);
         }
         const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
@@ -412,10 +457,10 @@ __device__ int block_inverse_cdf(F w, int V, double u, double* sm_d, int* sm_i) 
 
 // Correction / bonus token of sequence i after `a` accepted drafts.
 template <bool NUC>
-__device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_d, int* sm_i) {
+__device__ int finish_token(const SampleArgs& a, const SeqStats& st, int i, int acc_len, double* sm_d, int* sm_i) {
     const float* row = a.judge_row(i, acc_len);
     if (a.greedy()) {  // one-hot p: same two draws over the one-hot weights
-        const int amax = merged_argmax(a, i, acc_len);
+        const int amax = merged_argmax(st, acc_len);
         const double ug = (double)a.u[i * (a.k + 1) + a.k];
         auto pg = [=](int v) { return v == amax ? 1.0 : 0.0; };
         if (acc_len < a.k) {
@@ -427,7 +472,7 @@ __device__ int finish_token(const SampleArgs& a, int i, int acc_len, double* sm_
         return block_inverse_cdf(pg, a.V, ug, sm_d, sm_i);
     }
     double zmax, Z;
-    merged_stats(a, i, acc_len, zmax, Z);
+    merged_stats(st, acc_len, zmax, Z);
     // reciprocals once per call instead of two divisions per vocabulary entry (the single workgroup is
     // bound by its double-precision arithmetic); the results differ from the quotients by an ulp at most
     const double iT = 1.0 / a.T, iZ = 1.0 / Z;
@@ -455,10 +500,13 @@ template <bool NUC>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArgs a, int self_commit, int32_t* prefix_len) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
+    __shared__ double sm_st[DUO_MAX_ROWS + 1][2];
+    const SeqStats st{sm_st};
     const int i = blockIdx.x;
-    accept_flags<NUC>(a, i, 0);
+    load_seq_stats(a, i, 0, a.k, st);
+    accept_flags<NUC>(a, st, i, 0);
     const int acc_len = leading_accepts(a, i, 0);
-    const int tok = finish_token<NUC>(a, i, acc_len, sm_d, sm_i);
+    const int tok = finish_token<NUC>(a, st, i, acc_len, sm_d, sm_i);
     if (threadIdx.x == 0) {
         a.accept_len[i] = acc_len;
         a.next_token[i] = tok;
@@ -505,8 +553,11 @@ template <bool NUC>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs a) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
+    __shared__ double sm_st[DUO_MAX_ROWS + 1][2];
+    const SeqStats st{sm_st};
     const int tid = threadIdx.x;
-    fill_running_distribution<NUC>(a, 0, 0);
+    load_seq_stats(a, 0, 0, 0, st);  // the distribution that judges every first token
+    fill_running_distribution<NUC>(a, st, 0, 0);
     const int sel = sequential_first_tokens(a.p_run, a.V, a.n, a.tokens, a.k, a.q, (size_t)a.k * a.V, a.u, a.k + 1, sm_d);
     int acc_len = 0, tok;
     if (sel < 0) {
@@ -514,9 +565,10 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_paper_kernel(SampleArgs
         auto pw = [=](int v) { return pr[v]; };
         tok = block_inverse_cdf(pw, a.V, (double)a.u[(a.n - 1) * (a.k + 1) + a.k], sm_d, sm_i);
     } else {
-        accept_flags<NUC>(a, sel, 1);
+        load_seq_stats(a, sel, 1, a.k, st);  // the rows of the selected sequence
+        accept_flags<NUC>(a, st, sel, 1);
         acc_len = leading_accepts(a, sel, 1);
-        tok = finish_token<NUC>(a, sel, acc_len, sm_d, sm_i);
+        tok = finish_token<NUC>(a, st, sel, acc_len, sm_d, sm_i);
     }
     for (int i = tid; i < a.n; i += SAMPLE_THREADS) {
         a.accept_len[i] = sel < 0 ? 0 : (i < sel ? 0 : (i == sel ? acc_len : -1));
@@ -544,18 +596,21 @@ template <bool NUC>
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_deferred_kernel(SampleArgs a, DeferredArgs d) {
     __shared__ double sm_d[16];
     __shared__ int sm_i[4 + 16];
+    __shared__ double sm_st[DUO_MAX_ROWS + 1][2];
+    const SeqStats st{sm_st};
     const int tid = threadIdx.x;
     if (tid < d.s && a.status) {
         const int t = d.first_tokens[tid];
         if (t < 0 || t >= a.V) atomicOr(a.status, 1);
     }
-    accept_flags<NUC>(a, 0, 0);
+    load_seq_stats(a, 0, 0, a.k, st);
+    accept_flags<NUC>(a, st, 0, 0);
     const int acc_len = leading_accepts(a, 0, 0);
     int sel = -1, tok = -1;
     if (acc_len < a.k) {
-        tok = finish_token<NUC>(a, 0, acc_len, sm_d, sm_i);  // residual draw at the first rejection
+        tok = finish_token<NUC>(a, st, 0, acc_len, sm_d, sm_i);  // residual draw at the first rejection
     } else {
-        fill_running_distribution<NUC>(a, 0, a.k);  // the distribution after the last scored token
+        fill_running_distribution<NUC>(a, st, 0, a.k);  // the distribution after the last scored token
         sel = sequential_first_tokens(a.p_run, a.V, d.s, d.first_tokens, 1, d.first_probs, (size_t)a.V, d.uniforms_first, 1,
                                       sm_d);
         if (sel < 0) {
