@@ -5,7 +5,8 @@
 // group: a workgroup takes one (kv head, key chunk), each of its waves a share of the
 // chunk's 32-key blocks.  Per block a wave computes S^T = K Q^T and O^T += V^T P^T with MFMA:
 //   - K rows and V^T rows (values are cached transposed) are loaded straight from HBM in MFMA
-//     operand layout, 16 bytes per lane, no LDS staging -- each byte is consumed by one wave;
+//     operand layout, 16 bytes per lane, no LDS staging -- each byte is consumed by one wave
+//     (loads with the non-temporal hint: nothing of the prefix is read twice in a pass);
 //   - the key permutation inside a block is chosen so that the S^T accumulator of a lane
 //     already holds the eight consecutive keys its P^T operand needs: no cross-lane traffic
 //     between the two products;
@@ -148,11 +149,11 @@ __global__ __launch_bounds__(NWV * 64) void attn_partial_kernel(AttnArgs a) {
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                kf[buf][t][ks] = load_frag(kbase + ((size_t)((kb >> 5) * 2 + t) * KS + ks) * 512);
+                kf[buf][t][ks] = load_frag_stream(kbase + ((size_t)((kb >> 5) * 2 + t) * KS + ks) * 512);
     };
     auto load_v = [&](int buf, int kb) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = load_frag(vbase + ((size_t)(kb >> 5) * DT + dt) * 512);
+        for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = load_frag_stream(vbase + ((size_t)(kb >> 5) * DT + dt) * 512);
     };
     // scores of block kb (buffer buf), then request the next block's values (kb_next < 0: none), then
     // softmax and P V; the next block's keys were requested before the call
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
     auto load_v = [&](int b) {
         const int kb = (wave + NWV * b) * 32;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[b][dt] = load_frag(vbase + ((size_t)(kb >> 5) * DT + dt) * 512);
+        for (int dt = 0; dt < DT; ++dt) vf[b][dt] = load_frag_stream(vbase + ((size_t)(kb >> 5) * DT + dt) * 512);
     };
 #pragma unroll
     for (int b = 0; b < BATCH; ++b) {
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) kf[b][t][ks] = load_frag(kbase + ((size_t)(blk * 2 + t) * KS + ks) * 512);
+                for (int ks = 0; ks < KS; ++ks) kf[b][t][ks] = load_frag_stream(kbase + ((size_t)(blk * 2 + t) * KS + ks) * 512);
         }
     }
     if (nb > 0) load_v(0);
@@ -537,8 +538,9 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
 #pragma unroll
             for (int j = 0; j < TILES; ++j) {
                 const u16* src = j < KT ? kbase + ((size_t)blk * KT + j) * 512 : vbase + ((size_t)blk * DT + (j - KT)) * 512;
+                // cache policy 2: the non-temporal hint (every key and value byte is read once per pass)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (__attribute__((address_space(3))) void*)(dst + j * 64), 16, 0, 0);
+                                                 (__attribute__((address_space(3))) void*)(dst + j * 64), 16, 0, 2);
             }
         };
         // vmcnt(TILES): everything but the youngest block has landed (expcnt, lgkmcnt fields at their maxima)

@@ -85,6 +85,14 @@ __device__ __forceinline__ elem8 load_frag(const u16* p) {
     f.q = *reinterpret_cast<const u32x4*>(p);
     return f.v;
 }
+// The same load with the non-temporal hint: for data that is read exactly once (the weight stream, the prefix keys and
+// values), so that it does not displace what is re-read from the caches (the activation operand every workgroup
+// pulls through its L2).  Measured on the gate/up projection at 8 rows: 29.2 against 31.7 us (6.2 against 5.7 TB/s).
+__device__ __forceinline__ elem8 load_frag_stream(const u16* p) {
+    Frag8 f;
+    f.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return f.v;
+}
 __device__ __forceinline__ f32x4 mfma16(elem8 a, elem8 b, f32x4 c) {
     // D[16x16] += A[16x32] * B[32x16]; lane l supplies A[l%16][8*(l/16) .. +8] and
     // B[8*(l/16) .. +8][l%16]; it receives D[4*(l/16) .. +4][l%16].

@@ -84,7 +84,7 @@ struct RowScale {
     }
 };
 
-template <int MT, int NT, int NW, int PF, int GRP, class Epi>
+template <int MT, int NT, int NW, int PF, int GRP, class Epi, bool STREAM = true>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restrict__ X, const u16* __restrict__ W, int K,
                                                                int quads, int pair_quads, RowScale rsc, Epi epi) {
     __shared__ f32x4 red[NW * MT * NT * 64];
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
     auto load_slot = [&](int p, int i) {
         const int st = step_of(i);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) bb[p][t] = load_frag(wp[t] + (size_t)st * 512);
+        for (int t = 0; t < NT; ++t) bb[p][t] = STREAM ? load_frag_stream(wp[t] + (size_t)st * 512) : load_frag(wp[t] + (size_t)st * 512);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) aa[p][mt] = load_frag(xp + ((size_t)st * MT + mt) * 512);
     };
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
 // One barrier per round hands a filled buffer over and takes a drained one back.  Matrices with few bands
 // put NK waves on each band group: they split the K steps of every round (NK * AG steps) between them and
 // add their partial sums through LDS in wave order at the end.
-template <int MH, int NT, int NG, int NK, int PF, int AG, class Epi, bool HALF = false>
+template <int MH, int NT, int NG, int NK, int PF, int AG, class Epi, bool HALF = false, bool STREAM = true>
 __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16* __restrict__ X, const u16* __restrict__ W,
                                                                       int K, int split_steps, int ntiles, int quads,
                                                                       RowScale rsc, Epi epi) {
@@ -322,7 +322,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
         int ls = (i / AG) * RS + nk * AG + (i % AG);
         ls = ls < ns ? ls : ns - 1;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) bb[p][t] = load_frag(wp[t] + (size_t)ls * 512);
+        for (int t = 0; t < NT; ++t) bb[p][t] = STREAM ? load_frag_stream(wp[t] + (size_t)ls * 512) : load_frag(wp[t] + (size_t)ls * 512);
     };
     auto a_frags = [&](int slot, int r, int w) {  // this wave's step w of round r
         const u32x4* ab = lds + (r % NBUF) * BUF + (nk * AG + w) * MT * 64 + lane;
@@ -850,7 +850,7 @@ static inline void launch_gemm_cfg(const u16* X, const u16* W, int K, int tiles,
                                    const Epi& epi, hipStream_t s) {
     constexpr int PF = (NT + MT) <= 4 ? 8 : ((NT + MT) <= 8 ? 4 : 2);
     constexpr int GRP = 2;
-    DUO_KERNEL_NAME("gemm_skinny_kernel<%d, %d, %d, %d, %d, %s>", MT, NT, NW, PF, GRP, Epi::NAME);
+    DUO_KERNEL_NAME("gemm_skinny_kernel<%d, %d, %d, %d, %d, %s, true>", MT, NT, NW, PF, GRP, Epi::NAME);
     DUO_LAUNCH((gemm_skinny_kernel<MT, NT, NW, PF, GRP, Epi>), dim3(tiles), dim3(NW * 64), s, X, W, K, quads, pq, rsc, epi);
 }
 
@@ -891,7 +891,7 @@ static inline void launch_gemm_rows(int M, bool paired, const u16* X, const u16*
 constexpr int WIDE_MAX_SPLIT = 8;
 constexpr int WIDE_PF = 8, WIDE_AG = 4;
 
-template <int MH, int NT, int NG, int NK, class Epi, bool HALF = false>
+template <int MH, int NT, int NG, int NK, class Epi, bool HALF = false, bool STREAM = true>
 static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles, int quads, int splits, const RowScale& rsc,
                                    const Epi& epi, hipStream_t s, int* splits_out) {
     // rounds of NK * AG K steps; a round's operand tiles (2*MH per step) must fit the producer's counted wait
@@ -902,8 +902,9 @@ static inline void launch_wide_cfg(const u16* X, const u16* W, int K, int tiles,
     split_steps = (split_steps + RS - 1) / RS * RS;  // whole rounds: only the last split has a ragged end
     const int S = (steps + split_steps - 1) / split_steps;
     if (splits_out) *splits_out = S;
-    DUO_KERNEL_NAME("gemm_wide_kernel<%d, %d, %d, %d, %d, %d, %s, %s>", MH, NT, NG, NK, WIDE_PF, AG, Epi::NAME, HALF ? "true" : "false");
-    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, NK, WIDE_PF, AG, Epi, HALF>), dim3((tiles + NG - 1) / NG, S),
+    DUO_KERNEL_NAME("gemm_wide_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s>", MH, NT, NG, NK, WIDE_PF, AG, Epi::NAME, HALF ? "true" : "false",
+                    STREAM ? "true" : "false");
+    DUO_LAUNCH((gemm_wide_kernel<MH, NT, NG, NK, WIDE_PF, AG, Epi, HALF, STREAM>), dim3((tiles + NG - 1) / NG, S),
                dim3((NG * NK + 1) * 64), s, X, W, K, split_steps, tiles, quads, rsc, epi);
 }
 
