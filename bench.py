@@ -200,16 +200,19 @@ def main() -> int:
             probe_buf.fill_(1)
             probe_bytes = probe_buf.numel() * 4
             sink = torch.zeros(2048, dtype=torch.int32, device="cuda")
-            B.stream_read_probe(probe_buf, sink)
-            pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
-            for a, b in pe:
-                a.record()
-                B.stream_read_probe(probe_buf, sink)
-                b.record()
-            stream.synchronize()
-            probe_gbps = probe_bytes / (min(a.elapsed_time(b) for a, b in pe) * 1e-3) / 1e9
-            out_extra["stream_read_probe"] = {"GBps": round(probe_gbps, 1), "bytes": probe_bytes,
-                                              "what": "one kernel of plain 16-byte loads over a 4 GiB buffer, best of five"}
+            probe = {}
+            for label, nt in (("GBps", False), ("GBps_nontemporal_loads", True)):
+                B.stream_read_probe(probe_buf, sink, nt)
+                pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+                for a, b in pe:
+                    a.record()
+                    B.stream_read_probe(probe_buf, sink, nt)
+                    b.record()
+                stream.synchronize()
+                probe[label] = round(probe_bytes / (min(a.elapsed_time(b) for a, b in pe) * 1e-3) / 1e9, 1)
+            out_extra["stream_read_probe"] = {**probe, "bytes": probe_bytes,
+                                              "what": "one kernel of 16-byte loads over a 4 GiB buffer, best of five: ordinary loads, and "
+                                                      "loads with the non-temporal hint that the projection kernels give their weight loads"}
 
             # the same step with every cache level evicted first (a 4 GiB read between the steps): the weights are far
             # larger than the last-level cache, so this should read the same as the back-to-back figure

@@ -301,12 +301,13 @@ int duo_block_gemm(const uint16_t *x_packed, const uint16_t *w_packed, float *y,
                    void *hip_stream);
 
 /*
- * Measurement aid: reads `bytes` (rounded down to a multiple of 16) of device memory once with plain 16-byte loads,
+ * Measurement aid: reads `bytes` (rounded down to a multiple of 16) of device memory once with 16-byte loads (ordinary
+ * ones, or with nontemporal != 0 loads that carry the non-temporal hint, as the projection kernels' weight loads do),
  * min(sink_len, 2048) workgroups of 256 lanes, and xors what it read into sink[0 .. min(sink_len, 2048)) (device,
  * uint32, caller-initialised).  Timed over a buffer much larger than the caches it gives the read bandwidth a
  * weight-streaming kernel can reach on the device at hand, next to which the projection kernels' rates are read.
  */
-int duo_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, int sink_len, void *hip_stream);
+int duo_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, int sink_len, int nontemporal, void *hip_stream);
 
 /*
  * Per-kernel timing for the roofline report (the per-iteration time breakdown of Sec. 4.4

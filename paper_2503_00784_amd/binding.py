@@ -113,7 +113,7 @@ def load(dtype: str = "bf16") -> C.CDLL:
                                         C.c_size_t, C.c_void_p]
     lib.duo_skinny_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.duo_block_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
-    lib.duo_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
+    lib.duo_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.duo_stream_read_probe.restype = C.c_int
     lib.duo_packed_elems.argtypes = [C.c_int, C.c_int]
     lib.duo_packed_elems.restype = C.c_size_t
@@ -539,7 +539,8 @@ def block_gemm(hi_bits, lo_bits, w_bits, dtype: str = "bf16"):
     return y
 
 
-def stream_read_probe(buf, sink) -> None:
-    """Enqueue one plain streaming read of the device tensor `buf` (duo_stream_read_probe); `sink` is an int32 tensor."""
+def stream_read_probe(buf, sink, nontemporal: bool = False) -> None:
+    """Enqueue one streaming read of the device tensor `buf` (duo_stream_read_probe), with ordinary loads or loads that
+    carry the non-temporal hint; `sink` is an int32 tensor."""
     _check(load().duo_stream_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), sink.numel(),
-                                        _stream_ptr()), "duo_stream_read_probe")
+                                        1 if nontemporal else 0, _stream_ptr()), "duo_stream_read_probe")

@@ -765,14 +765,15 @@ int duo_block_gemm(const uint16_t* x, const uint16_t* w, float* y, int rows, int
     return hip_ok(hipGetLastError(), "duo_block_gemm launch");
 }
 
-int duo_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int sink_len, void* hip_stream) {
+int duo_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int sink_len, int nontemporal, void* hip_stream) {
     if (!src || !sink) return DUO_ERR_NULL;
     if (bytes < 16 || sink_len < 1) return DUO_ERR_SHAPE;
     if (!aligned16(src)) return DUO_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
     const int grid = sink_len < 2048 ? sink_len : 2048;
-    DUO_LAUNCH(stream_read_kernel, dim3(grid), dim3(256), s, static_cast<const u32x4*>(src), bytes / 16, sink);
+    if (nontemporal) DUO_LAUNCH(stream_read_kernel<true>, dim3(grid), dim3(256), s, static_cast<const u32x4*>(src), bytes / 16, sink);
+    else DUO_LAUNCH(stream_read_kernel<false>, dim3(grid), dim3(256), s, static_cast<const u32x4*>(src), bytes / 16, sink);
     return hip_ok(hipGetLastError(), "duo_stream_read_probe launch");
 }
 

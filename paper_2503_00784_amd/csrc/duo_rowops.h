@@ -201,8 +201,10 @@ __global__ __launch_bounds__(64) void last_row_operand_kernel(const u16* __restr
 }
 
 // Plain streaming read of `chunks` 16-byte chunks (the ceiling a weight stream can reach on the device): every lane
-// keeps eight independent 16-byte loads in flight, 1 KiB per wave and load instruction as in the projection kernels;
+// keeps eight independent 16-byte loads in flight, 1 KiB per wave and load instruction as in the projection kernels,
+// with ordinary loads or (NT) with the non-temporal hint the projection kernels give their weight loads;
 // the xor of everything read goes to sink[workgroup] so that the loads cannot be dropped.
+template <bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t chunks, uint32_t* __restrict__ sink) {
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
     for (; i + 7 * stride < chunks; i += 8 * stride) {
         u32x4 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+        for (int j = 0; j < 8; ++j) v[j] = NT ? __builtin_nontemporal_load(src + i + j * stride) : src[i + j * stride];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc ^= v[j];
     }

@@ -146,8 +146,8 @@ def test_other_entry_points_validate(lib):
     assert lib.duo_pack_gate_up(C.byref(cfg), 0x1000, None, 0x1000, None) == -1
     bg = lambda **kw: lib.duo_block_gemm(kw.get("x", 0x1000), 0x1000, 0x1000, kw.get("rows", 256), 64, kw.get("K", 64), None)
     assert bg(x=None) == -1 and bg(rows=0) == -2 and bg(rows=1025) == -2 and bg(K=48) == -2 and bg(x=0x1002) == -4
-    sp = lambda **kw: lib.duo_stream_read_probe(kw.get("src", 0x1000), kw.get("nbytes", 1 << 20), kw.get("sink", 0x1000), kw.get("n", 64), None)
-    assert sp(src=None) == -1 and sp(sink=None) == -1 and sp(nbytes=8) == -2 and sp(n=0) == -2 and sp(src=0x1004) == -4
+    sp = lambda **kw: lib.duo_stream_read_probe(kw.get("src", 0x1000), kw.get("nbytes", 1 << 20), kw.get("sink", 0x1000), kw.get("n", 64), kw.get("nt", 0), None)
+    assert sp(src=None) == -1 and sp(sink=None, nt=1) == -1 and sp(nbytes=8) == -2 and sp(n=0) == -2 and sp(src=0x1004) == -4
     assert lib.duo_pack_activations(0x1000, 2049, 64, 0x1000, None) == -2 and lib.duo_pack_activations(None, 8, 64, 0x1000, None) == -1
 
 
