@@ -499,14 +499,24 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
 // global -> LDS loads (no registers, no LDS store instructions) into a ring of three buffers, two blocks
 // ahead of the MFMAs; its barriers are bare s_barrier instructions behind a counted wait.  One barrier per
 // block hands a filled buffer over and takes a drained one back.
-template <int D, int MTW, int NWV>
+//
+// With few query tiles (KSPLIT > 1) the NWV consumer waves are KSPLIT teams of TW = NWV / KSPLIT waves and a ring stage
+// holds KSPLIT blocks: team z takes block z of every stage for the workgroup's TW query tiles, so that every SIMD holds
+// KSPLIT waves whose matrix, vector and LDS instructions overlap; the teams' softmax states are merged in team order
+// through LDS at the end (the same rescaled sum the chunk merge uses).
+template <int D, int MTW, int NWV, int KSPLIT = 1>
 __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a) {
     constexpr int KS = D / 32, DT = D / 16;
     constexpr int KT = 2 * KS;      // K tiles per block (2 key halves x KS)
     constexpr int TILES = KT + DT;  // 1 KiB tiles per block
     constexpr int NBUF = 3;
-    static_assert(TILES <= 63, "a block's loads fit the memory counter");
-    __shared__ u32x4 lds_kv[NBUF][TILES * 64];
+    constexpr int TW = NWV / KSPLIT;  // query-tile waves per team
+    constexpr int STL = KSPLIT * TILES;  // tiles per ring stage: one block for every team
+    static_assert(STL <= 63, "a stage's loads fit the producer's memory counter");
+    static_assert(NWV % KSPLIT == 0 && (KSPLIT == 1 || MTW == 1), "teams of equal size; one query tile per wave when the blocks are dealt to teams");
+    __shared__ u32x4 lds_kv[NBUF][STL * 64];
+    __shared__ f32x4 lds_team_o[KSPLIT > 1 ? (KSPLIT - 1) * TW * DT * 64 : 1];
+    __shared__ float lds_team_ml[KSPLIT > 1 ? (KSPLIT - 1) * TW * 2 * 64 : 1];
 
     const int cb = blockIdx.x, hk = blockIdx.y;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar: MFMA ignores EXEC
@@ -521,45 +531,51 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     {
         // No row sees a key behind its own slot: the blocks behind the slot of this workgroup's last query row
         // are masked for all of its rows and are left out (a prompt chunk's early rows skip the chunk's late keys).
-        const int r_last = min(a.plan.M * a.group, (zg + 1) * NWV * MTW * 16) - 1;
+        const int r_last = min(a.plan.M * a.group, (zg + 1) * TW * MTW * 16) - 1;
         const int nb_vis = (a.plan.P + r_last / a.group) / 32 + 1 - b0;
         nb = nb_vis < nb ? (nb_vis < 0 ? 0 : nb_vis) : nb;
     }
 
+    const int nst = (nb + KSPLIT - 1) / KSPLIT;  // ring stages
     if (wave == NWV) {
         // ---- producer.  The cache stores the tiles as they are needed (see k_cache_offset / v_cache_offset):
         // tile j < KT of a block is K tile (t = j / KS, ks = j % KS), otherwise V^T tile dt = j - KT; each is 1 KiB,
         // lane l takes bytes 16*l ..  Blocks past the last one are clamped.
         const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + lane * 8;
         const u16* vbase = a.vc + (size_t)hk * a.max_seq * D + lane * 8;
-        auto issue = [&](int ib) {
-            const int blk = min(b0 + ib, NB - 1);
-            u32x4* dst = lds_kv[ib % NBUF];
+        auto issue = [&](int st) {  // stage st: blocks st * KSPLIT .. + KSPLIT of the chunk
+            u32x4* dst = lds_kv[st % NBUF];
 #pragma unroll
-            for (int j = 0; j < TILES; ++j) {
-                const u16* src = j < KT ? kbase + ((size_t)blk * KT + j) * 512 : vbase + ((size_t)blk * DT + (j - KT)) * 512;
-                // cache policy 2: the non-temporal hint (every key and value byte is read once per pass)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (__attribute__((address_space(3))) void*)(dst + j * 64), 16, 0, 2);
+            for (int z = 0; z < KSPLIT; ++z) {
+                const int blk = min(b0 + st * KSPLIT + z, NB - 1);
+#pragma unroll
+                for (int j = 0; j < TILES; ++j) {
+                    const u16* src = j < KT ? kbase + ((size_t)blk * KT + j) * 512 : vbase + ((size_t)blk * DT + (j - KT)) * 512;
+                    // cache policy 2: the non-temporal hint (every key and value byte is read once per pass)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                     (__attribute__((address_space(3))) void*)(dst + (z * TILES + j) * 64), 16, 0, 2);
+                }
             }
         };
-        // vmcnt(TILES): everything but the youngest block has landed (expcnt, lgkmcnt fields at their maxima)
-        constexpr int WAIT_ALL_BUT_ONE_BLOCK = (TILES & 15) | ((TILES >> 4) << 14) | (7 << 4) | (15 << 8);
+        // vmcnt(STL): everything but the youngest stage has landed (expcnt, lgkmcnt fields at their maxima)
+        constexpr int WAIT_ALL_BUT_ONE_BLOCK = (STL & 15) | ((STL >> 4) << 14) | (7 << 4) | (15 << 8);
         issue(0);
         issue(1);
         __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);
         __builtin_amdgcn_s_barrier();
-        for (int ib = 0; ib < nb; ++ib) {
-            issue(ib + 2);  // its buffer was drained in iteration ib - 1
-            __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);  // block ib + 1 has landed
+        for (int st = 0; st < nst; ++st) {
+            issue(st + 2);  // its buffer was drained in iteration st - 1
+            __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);  // stage st + 1 has landed
             __builtin_amdgcn_s_barrier();
         }
+        if (KSPLIT > 1) __builtin_amdgcn_s_barrier();  // the teams' hand-over
         return;
     }
 
     // ---- consumers
     const int MQ = a.plan.M * a.group;
-    const int tile0 = (zg * NWV + wave) * MTW;  // first query tile of this wave
+    const int team = wave / TW, tw = wave - team * TW;
+    const int tile0 = (zg * TW + tw) * MTW;  // first query tile of this wave
     elem8 qf[MTW][KS], ql[MTW][KS];
     int vis_lo[MTW], vis_hi[MTW];
 #pragma unroll
@@ -673,10 +689,35 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     const int r_wave_last = min(MQ, (tile0 + MTW) * 16) - 1;
     const int kb_last = r_wave_last >= 0 ? a.plan.P + r_wave_last / a.group : -1;  // key slot of that row
     __syncthreads();  // block 0 is in LDS
-    for (int ib = 0; ib < nb; ++ib) {
+    for (int st = 0; st < nst; ++st) {
+        const int ib = st * KSPLIT + team;  // this team's block of the stage
         const int kb = (b0 + ib) * 32;
-        if (kb <= kb_last) use_block(lds_kv[ib % NBUF], kb);  // wave-uniform
-        __syncthreads();  // block ib + 1 is in LDS; block ib's buffer may be refilled
+        if (ib < nb && kb <= kb_last) use_block(lds_kv[st % NBUF] + team * TILES * 64, kb);  // wave-uniform
+        __syncthreads();  // stage st + 1 is in LDS; stage st's buffer may be refilled
+    }
+    if constexpr (KSPLIT > 1) {
+        // teams 1 .. KSPLIT-1 hand their states (running maximum, this lane's part of the sum, output) to team 0
+        if (team > 0) {
+            const int slot = (team - 1) * TW + tw;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) lds_team_o[(slot * DT + dt) * 64 + lane] = o[0][dt];
+            lds_team_ml[(slot * 2 + 0) * 64 + lane] = m_run[0];
+            lds_team_ml[(slot * 2 + 1) * 64 + lane] = l_run[0];
+        }
+        __syncthreads();
+        if (team > 0) return;
+#pragma unroll
+        for (int z = 1; z < KSPLIT; ++z) {  // team order
+            const int slot = (z - 1) * TW + tw;
+            const float mz = lds_team_ml[(slot * 2 + 0) * 64 + lane], lz = lds_team_ml[(slot * 2 + 1) * 64 + lane];
+            const float m_new = fmaxf(m_run[0], mz);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float s0 = exp2f(m_run[0] - m_safe), sz = exp2f(mz - m_safe);  // exp2(-inf) = 0: an empty state adds nothing
+            m_run[0] = m_new;
+            l_run[0] = l_run[0] * s0 + lz * sz;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[0][dt] = o[0][dt] * s0 + lds_team_o[(slot * DT + dt) * 64 + lane] * sz;
+        }
     }
 
 #pragma unroll
