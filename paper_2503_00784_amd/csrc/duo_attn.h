@@ -504,6 +504,10 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
 // holds KSPLIT blocks: team z takes block z of every stage for the workgroup's TW query tiles, so that every SIMD holds
 // KSPLIT waves whose matrix, vector and LDS instructions overlap; the teams' softmax states are merged in team order
 // through LDS at the end (the same rescaled sum the chunk merge uses).
+// 2^x by the hardware instruction alone: results below the normal range come out as zero, which is all a softmax weight
+// that small amounts to; 2^0 is exactly 1 and 2^-inf exactly 0.
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <int D, int MTW, int NWV, int KSPLIT = 1>
 __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a) {
     constexpr int KS = D / 32, DT = D / 16;
@@ -620,15 +624,15 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) kf[ks] = frag(t * KS + ks).v;
 #pragma unroll
-            for (int mt = 0; mt < MTW; ++mt) {  // hi and lo query parts in separate chains: shorter dependent runs
-                f32x4 acc_l = {0.f, 0.f, 0.f, 0.f}, acc_h = {0.f, 0.f, 0.f, 0.f};
+            for (int mt = 0; mt < MTW; ++mt) {  // lo and hi query parts into one accumulator; the scale comes with the exponent
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    acc_l = mfma16(kf[ks], ql[mt][ks], acc_l);
-                    acc_h = mfma16(kf[ks], qf[mt][ks], acc_h);
+                    acc = mfma16(kf[ks], ql[mt][ks], acc);
+                    acc = mfma16(kf[ks], qf[mt][ks], acc);
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) scs[mt][t * 4 + i] = (acc_l[i] + acc_h[i]) * a.scale_log2;
+                for (int i = 0; i < 4; ++i) scs[mt][t * 4 + i] = acc[i];
             }
         }
         Frag8 pf[MTW], pl[MTW];
@@ -649,14 +653,14 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
             for (int j = 1; j < 8; ++j) bm = fmaxf(bm, sc[j]);
             bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
             bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-            const float m_new = fmaxf(m_run[mt], bm);
+            const float m_new = fmaxf(m_run[mt], bm * a.scale_log2);  // the running maximum is kept in scaled units
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            alpha[mt] = exp2f(m_run[mt] - m_safe);
+            alpha[mt] = exp2_raw(m_run[mt] - m_safe);
             m_run[mt] = m_new;
             float pw[8], ps = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                pw[j] = exp2f(sc[j] - m_safe);
+                pw[j] = exp2_raw(fmaf(sc[j], a.scale_log2, -m_safe));
                 ps += pw[j];
             }
             split_elem8(pw, pf[mt].q, pl[mt].q);  // softmax weights as bf16 pairs (hi + lo)
