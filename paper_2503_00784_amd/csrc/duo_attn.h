@@ -508,6 +508,12 @@ __global__ __launch_bounds__(512) void attn_small_kernel(AttnArgs a) {
 // that small amounts to; 2^0 is exactly 1 and 2^-inf exactly 0.
 __device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 
+template <int N>
+__device__ __forceinline__ void wait_vector_loads_but() {  // vmcnt(N); expcnt and lgkmcnt fields at their maxima
+    static_assert(N >= 0 && N <= 63, "the memory counter has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
 template <int D, int MTW, int NWV, int KSPLIT = 1>
 __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a) {
     constexpr int KS = D / 32, DT = D / 16;
@@ -544,14 +550,16 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
     if (wave == NWV) {
         // ---- producer.  The cache stores the tiles as they are needed (see k_cache_offset / v_cache_offset):
         // tile j < KT of a block is K tile (t = j / KS, ks = j % KS), otherwise V^T tile dt = j - KT; each is 1 KiB,
-        // lane l takes bytes 16*l ..  Blocks past the last one are clamped.
+        // lane l takes bytes 16*l ..
         const u16* kbase = a.kc + (size_t)hk * a.max_seq * D + lane * 8;
         const u16* vbase = a.vc + (size_t)hk * a.max_seq * D + lane * 8;
-        auto issue = [&](int st) {  // stage st: blocks st * KSPLIT .. + KSPLIT of the chunk
+        auto issue = [&](int st) {  // stage st: blocks st * KSPLIT .. + KSPLIT of the chunk, as far as it has them
             u32x4* dst = lds_kv[st % NBUF];
 #pragma unroll
             for (int z = 0; z < KSPLIT; ++z) {
-                const int blk = min(b0 + st * KSPLIT + z, NB - 1);
+                const int ib = st * KSPLIT + z;
+                if (ib >= nb) break;  // wave-uniform
+                const int blk = b0 + ib;
 #pragma unroll
                 for (int j = 0; j < TILES; ++j) {
                     const u16* src = j < KT ? kbase + ((size_t)blk * KT + j) * 512 : vbase + ((size_t)blk * DT + (j - KT)) * 512;
@@ -561,15 +569,22 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
                 }
             }
         };
-        // vmcnt(STL): everything but the youngest stage has landed (expcnt, lgkmcnt fields at their maxima)
-        constexpr int WAIT_ALL_BUT_ONE_BLOCK = (STL & 15) | ((STL >> 4) << 14) | (7 << 4) | (15 << 8);
-        issue(0);
-        issue(1);
-        __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);
+        // Only blocks of the chunk are requested, so the wait before a hand-over counts the blocks of the one stage that
+        // may still be in flight: vmcnt(blocks * TILES), everything older has landed (expcnt, lgkmcnt fields at their maxima).
+        static_assert(KSPLIT <= 2, "the waits below know stages of one or two blocks");
+        auto wait_all_but_stage = [&](int st) {
+            const int blocks = st < nst ? min(KSPLIT, nb - st * KSPLIT) : 0;
+            if (blocks == 0) wait_vector_loads_but<0>();
+            else if (blocks == 1) wait_vector_loads_but<TILES>();
+            else wait_vector_loads_but<2 * TILES>();
+        };
+        if (nst > 0) issue(0);
+        if (nst > 1) issue(1);
+        wait_all_but_stage(1);  // stage 0 has landed
         __builtin_amdgcn_s_barrier();
         for (int st = 0; st < nst; ++st) {
-            issue(st + 2);  // its buffer was drained in iteration st - 1
-            __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_BLOCK);  // stage st + 1 has landed
+            if (st + 2 < nst) issue(st + 2);  // its buffer was drained in iteration st - 1
+            wait_all_but_stage(st + 2);       // stage st + 1 has landed
             __builtin_amdgcn_s_barrier();
         }
         if (KSPLIT > 1) __builtin_amdgcn_s_barrier();  // the teams' hand-over
