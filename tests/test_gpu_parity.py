@@ -302,6 +302,22 @@ def test_mid_config_gqa_ragged(B, n, k, mode, root):
         _check_cache(eng, cache, cache.prefix_len)
 
 
+@pytest.mark.parametrize("n,k,root,P", [(1, 8, -1, 1100), (2, 8, -1, 1100), (1, 3, 7, 1100), (2, 6, 4, 1371), (1, 5, -1, 2045)])
+def test_mid_config_long_prefix(B, n, k, root, P):
+    """The MID shape (GQA group of 4, heads of 64) on a long synthetic prefix, so that a head's keys are cut into
+    several chunks: 32, 64, 16, 52 and 20 (row, query head) pairs per KV head = 2, 4, 1, 4 and 2 query tiles, i.e. the
+    attention kernel whose waves form two teams over the key blocks (two and four tiles per workgroup, chunks of an even
+    and an odd number of blocks, a last block that is partly draft slots) and, for one tile, the per-wave kernel; the
+    chunk merge in all of them."""
+    shape = inputs.MID
+    say(f"MID long prefix P={P} n={n} k={k} root={root}")
+    max_seq = (P + 1 + n * k + 31) // 32 * 32
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, max_seq, seed=5, synthetic_cache=True)
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 17 + k, mode=0, root_token=root)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache_rows(B, eng, cache, P, cache.prefix_len, range(shape.n_layers))
+
+
 @pytest.mark.parametrize("mode,root", [(0, -1), (1, 12)])
 def test_mid_config_greedy_step(B, mode, root):
     """A whole step at temperature 0.  The logits are compared as always; the decisions are the arg-max rule applied to
