@@ -257,9 +257,13 @@ def main() -> int:
                   "gate_up_swiglu": 2 * 2 * shape.d_ff * shape.d_model, "down_proj": 2 * shape.d_model * shape.d_ff,
                   "lm_head": 2 * shape.vocab * shape.d_model,
                   "attn": 2 * 2 * shape.kv_dim * P}
+    # each projection's rate also as a fraction of what a read-only kernel with the same loads reaches on this device
+    probe_ceiling = out_extra.get("stream_read_probe", {}).get("GBps_nontemporal_loads")
     for name, b in per_launch.items():
         if name in kernels:
             kernels[name]["algo_GBps"] = round(b / (kernels[name]["avg_us"] * 1e-6) / 1e9, 1)
+            if probe_ceiling:
+                kernels[name]["frac_of_stream_probe"] = round(kernels[name]["algo_GBps"] / probe_ceiling, 4)
     dom = max((nm for nm in per_launch if nm in kernels), key=lambda nm: kernels[nm]["ms_per_step"])
     dom_bytes = per_launch[dom]
     dom_gbps = dom_bytes / (kernels[dom]["avg_us"] * 1e-6) / 1e9
@@ -269,7 +273,8 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "traffic_source": (f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/{args.workload.lower()}_hbm_traffic.md"
                                    if traffic is not None else None),
-                "algo_bytes_per_launch": dom_bytes, "avg_launch_us": kernels[dom]["avg_us"]}
+                "algo_bytes_per_launch": dom_bytes, "avg_launch_us": kernels[dom]["avg_us"],
+                "frac_of_stream_probe": (round(dom_gbps / probe_ceiling, 4) if probe_ceiling else None)}
 
     out = {"metric": "verified_tokens_per_s", "value": round(tok_s, 1), "unit": "tok/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
