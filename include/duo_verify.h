@@ -332,7 +332,8 @@ int duo_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, int sin
 #define DUO_PROF_LMHEAD    8  /* LM head */
 #define DUO_PROF_SAMPLE    9  /* softmax statistics, accept tests, correction/bonus sampling */
 #define DUO_PROF_COMMIT    10 /* sequence selection + KV commit */
-#define DUO_PROF_CLASSES   11
+#define DUO_PROF_QKV_FINISH 11 /* 49 rows and more: sum of the K-split Q/K/V partial results + rotary + KV scatter */
+#define DUO_PROF_CLASSES   12
 int duo_profile_enable(int enable);
 int duo_profile_read(double *ms, int32_t *launches);
 int duo_profile_dropped(void);

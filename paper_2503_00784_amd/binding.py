@@ -32,7 +32,7 @@ EXPORTS = ["duo_workspace_bytes", "duo_verify", "duo_prefill_chunk", "duo_sample
            "duo_pack_activations"]
 NOALLOC_MAX_VOCAB = 131072
 PROF_CLASSES = ["setup", "qkv_rope", "attn", "attn_combine", "o_proj", "residual_reduce", "gate_up_swiglu", "down_proj", "lm_head",
-                "sample", "commit"]
+                "sample", "commit", "qkv_finish"]
 
 _u16p = C.POINTER(C.c_uint16)
 _u16pp = C.POINTER(_u16p)

@@ -4,6 +4,7 @@
 #include "../../include/duo_verify.h"
 
 #include <math.h>
+#include <algorithm>
 #include <stdio.h>
 #include <string.h>
 
@@ -79,7 +80,8 @@ struct Workspace {
     int32_t* acc;
     float* ssq;      // [Mp][d/16] partial sums of squares of the residual stream (for the next RMSNorm)
     float* ssq_full; // [Mp][RowScale::FULL_PARTS] sums of squares over column ranges (written by the few-workgroups-per-row producers)
-    float* split;    // [splits][Mp][d] partial results of the K-split residual projections
+    float* split;    // [splits][Mp][d] partial results of the K-split residual projections; [2][M][Q/K/V columns] of the K-split Q/K/V projection
+    size_t split_floats;
     u16* h_last;     // many-row pass: the last row of h as an operand of its own (one tile per K step)
     size_t q_plane;  // elements between the two query planes
     size_t total;
@@ -141,7 +143,9 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.logits = reinterpret_cast<float*>(take((many ? 16 : Mp) * V * 4));
     ws.ssq = reinterpret_cast<float*>(take(Mp * (d / 16) * 4));
     ws.ssq_full = reinterpret_cast<float*>(take(Mp * RowScale::FULL_PARTS * 4));
-    ws.split = reinterpret_cast<float*>(take((size_t)(many ? block_splits(max_rows, c.d_model) : WIDE_MAX_SPLIT) * Mp * d * 4));
+    ws.split_floats = (size_t)(many ? block_splits(max_rows, c.d_model) : WIDE_MAX_SPLIT) * Mp * d;
+    if (!many) ws.split_floats = std::max(ws.split_floats, (size_t)2 * Mp * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
+    ws.split = reinterpret_cast<float*>(take(ws.split_floats * 4));
     ws.h_last = reinterpret_cast<u16*>(take(16 * d * 2));
     carve_sampler(base, off, c.vocab, ws, lm_head_parts(c.vocab));
     ws.total = off;
@@ -372,13 +376,35 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     // 16 / 32 / 64 / 80 rows; at 384 bands the same or slightly better beyond eight rows).
     const int qkv_bands = (Hq + 2 * Hkv) * (D / 16);
     const int qkv_nt = M > DUO_MAX_ROWS ? 2 : (M <= 8 ? ((qkv_bands > 512 && qkv_bands <= 768) ? 1 : 2) : (qkv_bands <= 768 ? 1 : 2));
+    // the Q/K/V projection as K-split product + finish kernel (see the loop): 49..80 rows, one band per wave, partial results fit
+    const bool qkv_split = M > 48 && M <= DUO_MAX_ROWS && qkv_nt == 1 && (size_t)2 * M * qkv_bands * 16 <= ws.split_floats;
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * c.max_seq * D;
         EpiQKV eq{Hq, Hkv, D, half, D / 16, qkv_nt, ws.q, qd, ws.q_plane, kc, vc, c.max_seq, ws.rope_c, ws.rope_s, plan,
                   cache.prefix_len, 1};
         const RowScale& qkv_norm = (l == 0 || down_split) ? norm_full : norm_part;
-        if (qkv_nt == 1) launch_projection<1>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands, qkv_norm, eq, s);
+        if (qkv_split) {
+            // 49..80 rows: K split two ways over workgroups of twice the bands, each staging half of the operand
+            // (22.1 against 27.1 us for the product at 64 rows x 768 bands), partial results to the workspace, and a
+            // small second kernel that adds them and does the rotary embedding and the cache scatter
+            const int ncols = qkv_bands * 16;
+            EpiStoreF32 ep{ncols, M, 1, ws.split, ncols, (size_t)M * ncols};
+            const int quads = pair_rows_for(M) / 4;
+            int S = 1;
+            prof(DUO_PROF_QKV, s);
+            if (M <= 64) {
+                if (qkv_bands > 512) launch_wide_cfg<4, 1, 6, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
+                else launch_wide_cfg<4, 1, 3, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
+            } else {
+                if (qkv_bands > 512) launch_wide_cfg<5, 1, 6, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
+                else launch_wide_cfg<5, 1, 3, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
+            }
+            QkvFinishArgs fa{ws.split, S, (size_t)M * ncols, ncols, Hq, Hkv, D, ws.q, qd, ws.q_plane, kc, vc, c.max_seq,
+                             ws.rope_c, ws.rope_s, plan, cache.prefix_len};
+            prof(DUO_PROF_QKV_FINISH, s);
+            DUO_LAUNCH(qkv_finish_kernel, dim3(Hq + 2 * Hkv, (M + 7) / 8), dim3(256), s, fa);
+        } else if (qkv_nt == 1) launch_projection<1>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands, qkv_norm, eq, s);
         else launch_projection<2>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands / 2, qkv_norm, eq, s);
 
         AttnArgs aa{ws.q, qd, ws.q_plane, kc, vc, c.max_seq, group, plan, Ktot, bpw, nchunks, mq_pad,

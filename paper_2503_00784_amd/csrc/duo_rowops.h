@@ -139,6 +139,69 @@ static inline void launch_residual_reduce(int M, const float* part, int S, size_
     else DUO_LAUNCH(residual_reduce_kernel<8>, grid, dim3(512), s, part, S, split_stride, x, gain, h, d, pair_rows, tiles, ssq_part, ssq_full);
 }
 
+// Second half of a Q/K/V projection whose K range was split over workgroups (64 rows and more: each workgroup then
+// stages half of the activation operand): adds the S partial results in split order, then does what EpiQKV does: rotates
+// Q and K, stores Q as a pair of planes (hi, lo) and K and V into their cache slots.  `part` is [S][M][ncols] fp32 in the
+// packed column order of the fused matrix (a band = eight channels of a head and, eight columns further on, their rotary
+// partners), already scaled by the rows' RMSNorm factors.
+// grid = (Hq + 2*Hkv heads, groups of eight rows), 256 threads: a wave is 8 rows x 8 channel pairs (lane = row % 8 +
+// 8 * pair), so that a store instruction covers runs of eight channels of a row (Q, K tiles) and of eight slots of a
+// channel (V tiles); wave w takes pairs 8w .. 8w+7 of every 32.
+struct QkvFinishArgs {
+    const float* part;
+    int S;
+    size_t split_stride;
+    int ncols;
+    int Hq, Hkv, D;
+    u16* q_out;
+    int ldq;
+    size_t q_plane;
+    u16* kc;
+    u16* vc;
+    int max_seq;
+    const float* rope_cos;
+    const float* rope_sin;
+    RowPlan plan;
+    const int32_t* dev_prefix_len;  // may be nullptr; a device prefix length other than plan.P: nothing goes to the cache
+};
+
+__global__ __launch_bounds__(256) void qkv_finish_kernel(QkvFinishArgs a) {
+    const int head = blockIdx.x, half = a.D / 2, bph = a.D / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blockIdx.y * 8 + (lane & 7);
+    if (m >= a.plan.M) return;
+    const bool cache_ok = !a.dev_prefix_len || *a.dev_prefix_len == a.plan.P;
+    const float* row = a.part + (size_t)m * a.ncols;
+    for (int dd = wave * 8 + (lane >> 3); dd < half; dd += 32) {
+        const int n_lo = (head * bph + (dd >> 3)) * 16 + (dd & 7);  // channel dd; its partner dd + D/2 sits 8 columns on
+        float x_lo = 0.f, x_hi = 0.f;
+        for (int sp = 0; sp < a.S; ++sp) {
+            x_lo += row[(size_t)sp * a.split_stride + n_lo];
+            x_hi += row[(size_t)sp * a.split_stride + n_lo + 8];
+        }
+        if (head < a.Hq + a.Hkv) {
+            const float cs = a.rope_cos[m * half + dd], sn = a.rope_sin[m * half + dd];
+            const float r_lo = x_lo * cs - x_hi * sn, r_hi = x_hi * cs + x_lo * sn;
+            if (head < a.Hq) {
+                u16* q = a.q_out + (size_t)m * a.ldq + head * a.D;
+                const u16 h_lo = f32_to_elem(r_lo), h_hi = f32_to_elem(r_hi);
+                q[dd] = h_lo;
+                q[half + dd] = h_hi;
+                q[a.q_plane + dd] = f32_to_elem(r_lo - elem_to_f32(h_lo));
+                q[a.q_plane + half + dd] = f32_to_elem(r_hi - elem_to_f32(h_hi));
+            } else if (cache_ok) {
+                u16* kp = a.kc + (size_t)(head - a.Hq) * a.max_seq * a.D;
+                kp[k_cache_offset(a.D, a.plan.slot(m), dd)] = f32_to_elem(r_lo);
+                kp[k_cache_offset(a.D, a.plan.slot(m), half + dd)] = f32_to_elem(r_hi);
+            }
+        } else if (cache_ok) {
+            u16* vp = a.vc + (size_t)(head - a.Hq - a.Hkv) * a.max_seq * a.D;
+            vp[v_cache_offset(a.D, a.plan.slot(m), dd)] = f32_to_elem(x_lo);
+            vp[v_cache_offset(a.D, a.plan.slot(m), half + dd)] = f32_to_elem(x_hi);
+        }
+    }
+}
+
 // cos/sin of pos(m) * theta^(-2d/D), evaluated in double and rounded once to fp32.  As the first kernel of a
 // pass it also clears the status word that the later kernels OR their flags into, and, for a pass that will be
 // followed by sampling from cached root logits (root.logits != nullptr), its last ROOT_STATS_PARTS workgroups leave the
