@@ -289,11 +289,12 @@ def test_tiny_config_prefill_and_verify_chain(B):
 
 @pytest.mark.parametrize("n,k,mode,root", [(3, 5, 1, 17), (1, 16, 0, -1), (4, 16, 0, 3), (8, 8, 1, -1), (2, 1, 0, 5),
                                             (3, 8, 0, -1), (2, 16, 1, 9), (5, 8, 0, -1), (1, 9, 0, -1), (5, 16, 0, -1),
-                                            (1, 1, 0, -1)])
+                                            (1, 1, 0, -1), (7, 7, 0, 3), (6, 8, 1, -1)])
 def test_mid_config_gqa_ragged(B, n, k, mode, root):
     """3 layers, 8 query / 2 KV heads of 64, vocab 4099 (not a multiple of 16), prefix 77.  The row counts
-    (16, 16, 65, 64, 3, 24, 33, 40, 9, 80, 1) cover every row-tile count of both projection kernels, the
-    largest call the library takes (80 rows) and the smallest (one token)."""
+    (16, 16, 65, 64, 3, 24, 33, 40, 9, 80, 1, 50, 48) cover every row-tile count of both projection kernels, the
+    largest call the library takes (80 rows), the smallest (one token) and both sides of the row count from which the
+    Q/K/V projection splits K over workgroups (49)."""
     shape = inputs.MID
     say(f"MID n={n} k={k} mode={mode} root={root}")
     w, oshape, eng, cache = _engine_and_oracle(B, shape, 77, 192, seed=2, synthetic_cache=False)
@@ -421,7 +422,7 @@ def test_other_width_single_layer(B, n, k, root):
         _check_cache(eng, cache, cache.prefix_len)
 
 
-@pytest.mark.parametrize("n,k,root", [(1, 8, -1), (1, 7, 5), (4, 8, -1), (5, 16, -1), (2, 3, -1)])
+@pytest.mark.parametrize("n,k,root", [(1, 8, -1), (1, 7, 5), (4, 8, -1), (5, 16, -1), (2, 3, -1), (7, 7, -1), (8, 8, 11)])
 def test_7b_width_single_layer(B, n, k, root):
     """One layer of 7B width: the launch shapes of the benchmark step (768 independent Q/K/V bands, one per wave up to
     80 rows; gate/up and down at d_ff 11008) at 6, 8, 32 and 80 rows."""
