@@ -303,13 +303,16 @@ def test_mid_config_gqa_ragged(B, n, k, mode, root):
         _check_cache(eng, cache, cache.prefix_len)
 
 
-@pytest.mark.parametrize("n,k,root,P", [(1, 8, -1, 1100), (2, 8, -1, 1100), (1, 3, 7, 1100), (2, 6, 4, 1371), (1, 5, -1, 2045)])
+@pytest.mark.parametrize("n,k,root,P", [(1, 8, -1, 1100), (2, 8, -1, 1100), (1, 3, 7, 1100), (2, 6, 4, 1371), (1, 5, -1, 2045),
+                                        (8, 8, -1, 1100), (7, 7, 3, 1371), (5, 16, -1, 2045), (4, 16, -1, 1056)])
 def test_mid_config_long_prefix(B, n, k, root, P):
     """The MID shape (GQA group of 4, heads of 64) on a long synthetic prefix, so that a head's keys are cut into
     several chunks: 32, 64, 16, 52 and 20 (row, query head) pairs per KV head = 2, 4, 1, 4 and 2 query tiles, i.e. the
     attention kernel whose waves form two teams over the key blocks (two and four tiles per workgroup, chunks of an even
     and an odd number of blocks, a last block that is partly draft slots) and, for one tile, the per-wave kernel; the
-    chunk merge in all of them."""
+    chunk merge in all of them.  The cases of 64, 50, 80 and 64 rows add the K-split Q/K/V projection with its finish
+    kernel and 16 to 20 query tiles per KV head: prefixes that end inside a 32-key block and on a block boundary, with
+    and without a root row, sequences of 7, 8 and 16 tokens."""
     shape = inputs.MID
     say(f"MID long prefix P={P} n={n} k={k} root={root}")
     max_seq = (P + 1 + n * k + 31) // 32 * 32
@@ -317,6 +320,18 @@ def test_mid_config_long_prefix(B, n, k, root, P):
     got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 17 + k, mode=0, root_token=root)
     if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
         _check_cache_rows(B, eng, cache, P, cache.prefix_len, range(shape.n_layers))
+
+
+@pytest.mark.parametrize("n,k,root,P", [(7, 7, -1, 40), (8, 8, 5, 64), (5, 16, -1, 1)])
+def test_mid_config_many_rows_short_prefix(B, n, k, root, P):
+    """49, 65 and 80 rows (the K-split Q/K/V projection) on a prefix of at most two key blocks: one key chunk per head,
+    draft slots in every block."""
+    shape = inputs.MID
+    say(f"MID short prefix P={P} n={n} k={k} root={root}")
+    w, oshape, eng, cache = _engine_and_oracle(B, shape, P, 160, seed=9, synthetic_cache=False)
+    got, res, _ = _check_step(B, shape, w, oshape, eng, cache, n, k, seed=n * 13 + k, mode=0, root_token=root)
+    if (got["selected"], got["commit_len"]) == (res.selected, res.commit_len):
+        _check_cache(eng, cache, cache.prefix_len)
 
 
 @pytest.mark.parametrize("mode,root", [(0, -1), (1, 12)])
