@@ -481,7 +481,24 @@ void enqueue_sampling(const SampleArgs& sa, float top_p, const Workspace& ws, in
     if (mode == DUO_SELECT_INDEPENDENT_LONGEST) {
         // one sequence: nothing to choose and nothing to move, the finish kernel writes the commit itself
         const bool self_commit = sa.n == 1;
-        if (sa.nuc) DUO_LAUNCH(sample_finish_kernel<true>, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
+        if (sa.V >= SPREAD_MIN_VOCAB) {
+            // large vocabulary: row statistics, slice sums and the search as three small kernels over many compute units
+            int G = sa.V / 4096;
+            G = std::min(G, std::min(SPREAD_MAX_SLICES, SPREAD_MAX_GROUPS / sa.n));
+            G = std::max(G, 1);
+            const int chunk = ((sa.V + 16 * G - 1) / (16 * G) + 63) / 64 * 64;
+            static_assert(2 * (DUO_MAX_ROWS + 2) <= 256 && 256 + SPREAD_MAX_GROUPS * 16 * 3 <= SPREAD_MIN_VOCAB, "the records fit p_run");
+            SpreadBuf sb{sa.p_run, sa.p_run + 256, reinterpret_cast<int32_t*>(sa.p_run + 256 + (size_t)sa.n * 16 * G * 2), G, chunk};
+            // (letting every slice merge the statistics of its sequence's rows itself saves this launch and costs more:
+            // 2 x 11.6 against 3 x 6.9 us at 9 rows of 1000 parts)
+            DUO_LAUNCH(sample_row_stats_kernel, dim3(sa.R + sa.n * sa.k + 1), dim3(256), s, sa, sb);
+            prof(DUO_PROF_SAMPLE, s);
+            if (sa.nuc) DUO_LAUNCH(sample_spread_kernel<true>, dim3(sa.n, G), dim3(SAMPLE_THREADS), s, sa, sb);
+            else DUO_LAUNCH(sample_spread_kernel<false>, dim3(sa.n, G), dim3(SAMPLE_THREADS), s, sa, sb);
+            prof(DUO_PROF_SAMPLE, s);
+            if (sa.nuc) DUO_LAUNCH(sample_locate_kernel<true>, dim3(sa.n), dim3(64), s, sa, sb, self_commit ? 1 : 0, prefix_len);
+            else DUO_LAUNCH(sample_locate_kernel<false>, dim3(sa.n), dim3(64), s, sa, sb, self_commit ? 1 : 0, prefix_len);
+        } else if (sa.nuc) DUO_LAUNCH(sample_finish_kernel<true>, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
         else DUO_LAUNCH(sample_finish_kernel<false>, dim3(sa.n), dim3(SAMPLE_THREADS), s, sa, self_commit ? 1 : 0, prefix_len);
         if (self_commit) return;
     } else {

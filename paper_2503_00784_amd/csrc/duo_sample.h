@@ -8,6 +8,9 @@
 //                         epilogue leaves these statistics, one part per 32-column tile, see EpiLogitsStats)
 //   sample_finish_kernel  one workgroup per sequence: accept flags, leading accepts, then the
 //                         correction token from norm(max(0, p - q)) or the bonus token from p
+//   sample_row_stats_kernel, sample_spread_kernel, sample_locate_kernel
+//                         the same rule for vocabularies of SPREAD_MIN_VOCAB entries and more, spread over many
+//                         workgroups (see there)
 //   sample_paper_kernel   the sequential first-token rule over the n sequences, with the
 //                         running distribution replaced by its residual after each rejection
 //   sample_deferred_kernel  Alg. 2 as listed: verify the unverified suffix, then judge only the first
@@ -349,23 +352,26 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_nucleus_kernel(SampleAr
 }
 
 // accept flags of sequence i, positions from..k-1 (one thread each), into acc[]; ends with a barrier
+// the accept test u * q(t) < p(t) of draft (i, j)
+template <bool NUC>
+__device__ __forceinline__ int accept_flag(const SampleArgs& a, const SeqStats& st, int i, int j) {
+    const float* row = a.judge_row(i, j);
+    const int t = a.token(i, j);
+    double p_t;
+    if (a.greedy()) {
+        p_t = t == merged_argmax(st, j) ? 1.0 : 0.0;
+    } else {
+        double zmax, Z;
+        merged_stats(st, j, zmax, Z);
+        p_t = nucleus_of<NUC>(a, i, j).apply(exp((double)row[t] / a.T - zmax) / Z, row[t], t);
+    }
+    const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
+    return lhs < p_t ? 1 : 0;
+}
 template <bool NUC>
 __device__ __forceinline__ void accept_flags(const SampleArgs& a, const SeqStats& st, int i, int from) {
     const int j = from + threadIdx.x;
-    if (j < a.k) {
-        const float* row = a.judge_row(i, j);
-        const int t = a.token(i, j);
-        double p_t;
-        if (a.greedy()) {
-            p_t = t == merged_argmax(st, j) ? 1.0 : 0.0;
-        } else {
-            double zmax, Z;
-            merged_stats(st, j, zmax, Z);
-            p_t = nucleus_of<NUC>(a, i, j).apply(exp((double)row[t] / a.T - zmax) / Z, row[t], t);
-        }
-        const double lhs = (double)a.u[i * (a.k + 1) + j] * (double)a.q[((size_t)i * a.k + j) * a.V + t];
-        a.acc[i * a.k + j] = lhs < p_t ? 1 : 0;
-    }
+    if (j < a.k) a.acc[i * a.k + j] = accept_flag<NUC>(a, st, i, j);
     __threadfence_block();
     __syncthreads();
 }
@@ -509,6 +515,307 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_finish_kernel(SampleArg
     const int tok = finish_token<NUC>(a, st, i, acc_len, sm_d, sm_i);
     if (threadIdx.x == 0) {
         a.accept_len[i] = acc_len;
+        a.next_token[i] = tok;
+        if (self_commit) {
+            if (status_now(a.status) != 0) {
+                write_failed_commit(a.commit, prefix_len, a.P);
+            } else {
+                a.commit[0] = 0;
+                a.commit[1] = acc_len;
+                a.commit[2] = tok;
+                a.commit[3] = a.P + a.R + acc_len;
+                if (prefix_len) *prefix_len = a.P + a.R + acc_len;
+            }
+        }
+    }
+}
+
+// ---- the same rule for large vocabularies, spread over the chip ----------------------------------------------
+// sample_finish_kernel is one workgroup per sequence and bound by its double-precision arithmetic: the merge of the
+// rows' partial statistics (vocab / 32 parts per row after the LM head) and the pass over the vocabulary behind the
+// correction token each evaluate tens of thousands of exponentials on one compute unit (27 us at 32000 entries, 87 us at
+// 128256).  Three small kernels do the same work on many:
+//   sample_row_stats_kernel   one workgroup per judging row: its merged statistics {zmax, Z}
+//   sample_spread_kernel      grid (sequence, slice of the vocabulary): accept flags and leading accepts (every slice
+//                             repeats them: k exponentials), then the sums of the correction weights max(0, p - q)
+//                             and of p over the slice's 16 wave chunks, with the last id of positive weight in each
+//   sample_locate_kernel      one wave per sequence: the chunk in which the running sum crosses u * total (chunk sums
+//                             added in index order), the id inside it, the commit record of a single sequence
+// Their scratch (SpreadBuf) lies in p_run, which this rule does not use otherwise.
+struct SpreadBuf {
+    double* row_stats;  // [R + n*k + 1][2], row judge_index + 1
+    double* sums;       // [n][chunks][2]: correction weights, target probabilities
+    int32_t* last;      // [n][chunks][2]
+    int G, chunk;       // slices per sequence; ids per wave chunk (a multiple of 64); chunks = 16 * G
+    __host__ __device__ int chunks() const { return 16 * G; }
+};
+constexpr int SPREAD_MIN_VOCAB = 8192;   // below: sample_finish_kernel
+constexpr int SPREAD_MAX_GROUPS = 128;   // n * G at most: the records fit SPREAD_MIN_VOCAB doubles
+constexpr int SPREAD_MAX_SLICES = 32;
+
+__global__ __launch_bounds__(256) void sample_row_stats_kernel(SampleArgs a, SpreadBuf b) {
+    __shared__ double sm[16];
+    const int jr = (int)blockIdx.x - 1;
+    if (jr < 0 && a.R) return;  // a root row judges the first tokens: the cached root logits are not in play
+    const double* pt = jr < 0 ? a.stats_root : a.stats_rows + (size_t)jr * a.parts * 2;
+    const int np = jr < 0 ? a.root_parts : a.parts;
+    // a thread's parts stay in registers between the two passes, all of their loads in flight together (up to
+    // 256 * PER parts, i.e. a vocabulary of 131072 behind the LM head; more: the passes re-read them)
+    constexpr int PER = 16;
+    const bool in_regs = np <= 256 * PER;
+    double pm[PER], pz[PER];
+    if (in_regs) {
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int p = threadIdx.x + 256 * e;
+            const int pc = p < np ? p : np - 1;
+            pm[e] = pt[2 * pc];
+            pz[e] = pt[2 * pc + 1];
+            if (p >= np) {
+                pm[e] = -INFINITY;
+                pz[e] = 0.0;
+            }
+        }
+    }
+    double mx = -INFINITY;
+    if (in_regs) {
+#pragma unroll
+        for (int e = 0; e < PER; ++e) mx = fmax(mx, pm[e]);
+    } else {
+#pragma unroll 4
+        for (int p = threadIdx.x; p < np; p += 256) mx = fmax(mx, pt[2 * p]);
+    }
+    mx = block_max_d(mx, sm);
+    double Z;
+    if (a.greedy()) {  // the lowest id among the parts that hold the largest logit
+        double first = 4.0e9;
+        if (in_regs) {
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                if (pm[e] == mx) first = fmin(first, pz[e]);
+        } else {
+            for (int p = threadIdx.x; p < np; p += 256)
+                if (pt[2 * p] == mx) first = fmin(first, pt[2 * p + 1]);
+        }
+        Z = -block_max_d(-first, sm);
+    } else {
+        double sum = 0.0;
+        if (in_regs) {
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                if (pz[e] > 0.0) sum += pz[e] * exp(pm[e] - mx);
+        } else {
+#pragma unroll 4
+            for (int p = threadIdx.x; p < np; p += 256)
+                if (pt[2 * p + 1] > 0.0) sum += pt[2 * p + 1] * exp(pt[2 * p] - mx);
+        }
+        Z = block_sum_d(sum, sm);
+    }
+    if (threadIdx.x == 0) {
+        b.row_stats[2 * blockIdx.x] = mx;
+        b.row_stats[2 * blockIdx.x + 1] = Z;
+    }
+}
+
+// p(v) of judging row (i, j) and the correction weight max(0, p(v) - q(v)) behind a rejection at j < k
+template <bool NUC>
+struct TokenWeights {
+    const float* row;
+    const float* qrow;  // nullptr: no draft distribution at this position (bonus token)
+    double iT, zmax, iZ;
+    int amax;  // greedy: the one-hot id; -1 otherwise
+    Nucleus nc;
+    // row_zmax, row_Z: the row's merged statistics (greedy: row_Z is the arg max)
+    __device__ __forceinline__ TokenWeights(const SampleArgs& a, int i, int j, double row_zmax, double row_Z) {
+        row = a.judge_row(i, j);
+        qrow = j < a.k ? a.q + ((size_t)i * a.k + j) * a.V : nullptr;
+        amax = a.greedy() ? (int)row_Z : -1;
+        iT = a.greedy() ? 0.0 : 1.0 / a.T;  // reciprocals once instead of two divisions per entry (an ulp at most)
+        zmax = row_zmax;
+        iZ = a.greedy() ? 0.0 : 1.0 / row_Z;
+        nc = nucleus_of<NUC>(a, i, j);
+    }
+    __device__ __forceinline__ double p(int v) const {
+        if (amax >= 0) return v == amax ? 1.0 : 0.0;
+        return nc.apply(exp((double)row[v] * iT - zmax) * iZ, row[v], v);
+    }
+    __device__ __forceinline__ double r(double pv, int v) const { return fmax(pv - (double)qrow[v], 0.0); }
+};
+
+template <bool NUC>
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_spread_kernel(SampleArgs a, SpreadBuf b) {
+    __shared__ double sm_st[DUO_MAX_ROWS + 1][2];
+    __shared__ int sm_acc[DUO_MAX_ROWS];
+    const SeqStats st{sm_st};
+    const int i = blockIdx.x, g = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (tid <= a.k) {
+        const double* rs = b.row_stats + 2 * (a.judge_index(i, tid) + 1);
+        sm_st[tid][0] = rs[0];
+        sm_st[tid][1] = rs[1];
+    }
+    __syncthreads();
+    if (tid < a.k) sm_acc[tid] = accept_flag<NUC>(a, st, i, tid);
+    __syncthreads();
+    int acc_len = 0;
+    while (acc_len < a.k && sm_acc[acc_len]) ++acc_len;
+    if (g == 0 && tid == 0) a.accept_len[i] = acc_len;
+    const TokenWeights<NUC> w(a, i, acc_len, sm_st[acc_len][0], sm_st[acc_len][1]);
+    const int c = g * 16 + wave;
+    const int c0 = min(a.V, c * b.chunk), c1 = min(a.V, c0 + b.chunk);
+    double sum_r = 0.0, sum_p = 0.0;
+    int last_r = -1, last_p = -1;
+    if (w.qrow) {
+#pragma unroll 4
+        for (int v = c0 + lane; v < c1; v += 64) {
+            const double pv = w.p(v), rv = w.r(pv, v);
+            sum_p += pv;
+            sum_r += rv;
+            if (pv > 0.0) last_p = v;
+            if (rv > 0.0) last_r = v;
+        }
+    } else {
+#pragma unroll 4
+        for (int v = c0 + lane; v < c1; v += 64) {
+            const double pv = w.p(v);
+            sum_p += pv;
+            if (pv > 0.0) last_p = v;
+        }
+    }
+    sum_r = wave_sum(sum_r);
+    sum_p = wave_sum(sum_p);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        last_r = max(last_r, __shfl_xor(last_r, o, 64));
+        last_p = max(last_p, __shfl_xor(last_p, o, 64));
+    }
+    if (lane == 0) {
+        const size_t e = ((size_t)i * b.chunks() + c) * 2;
+        b.sums[e] = sum_r;
+        b.sums[e + 1] = sum_p;
+        b.last[e] = last_r;
+        b.last[e + 1] = last_p;
+    }
+}
+
+// One wave.  Inverse CDF over the weights whose chunk sums (x[g]: chunk 64 * g + lane, zero beyond the last chunk) and
+// last ids of positive weight (lp[g], -1 for none) were left by sample_spread_kernel: smallest id whose running sum
+// (chunks in index order, then lane segments of the crossing chunk, then single ids) exceeds u * total; the largest id
+// of positive weight where rounding leaves no crossing; -1 if the total is zero.
+constexpr int SPREAD_GROUPS64 = SPREAD_MAX_SLICES * 16 / 64;
+template <class F>
+__device__ int wave_inverse_cdf(F w, int V, double u, const double (&x)[SPREAD_GROUPS64], const int (&lp)[SPREAD_GROUPS64], int chunks,
+                                int chunk) {
+    const int lane = threadIdx.x & 63;
+    // Running sums over the chunks, 64 at a time: an inclusive scan over the lanes on top of the sum of the groups in
+    // front.  The total is the last running sum of the same arithmetic, so the search ends on it.
+    double incl[SPREAD_GROUPS64], front[SPREAD_GROUPS64], total = 0.0;
+    int last_all = -1;
+#pragma unroll
+    for (int g = 0; g < SPREAD_GROUPS64; ++g) {
+        incl[g] = x[g];
+        front[g] = total;
+        if (g * 64 >= chunks) continue;  // wave-uniform: no chunk in this group
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double y = __shfl_up(incl[g], o, 64);
+            if (lane >= o) incl[g] += y;
+        }
+        total += __shfl(incl[g], 63, 64);
+        int l = lp[g];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) l = max(l, __shfl_xor(l, o, 64));
+        last_all = max(last_all, l);
+    }
+    if (!(total > 0.0)) return -1;
+    const double target = u * total;
+    int owner = -1, owner_last = -1;
+    double base = 0.0;
+#pragma unroll
+    for (int g = 0; g < SPREAD_GROUPS64; ++g) {
+        const unsigned long long hit = __ballot(x[g] > 0.0 && front[g] + incl[g] > target);
+        if (owner < 0 && hit) {
+            const int hl = __ffsll((long long)hit) - 1;
+            owner = g * 64 + hl;
+            base = front[g] + __shfl(incl[g] - x[g], hl, 64);  // running sum in front of that chunk
+            owner_last = __shfl(lp[g], hl, 64);
+        }
+    }
+    if (owner < 0) return last_all;
+    const int c0 = min(V, owner * chunk), c1 = min(V, c0 + chunk);
+    const int per = chunk >> 6;
+    const int s0 = min(c1, c0 + lane * per), s1 = min(c1, s0 + per);
+    double seg = 0.0;
+#pragma unroll 4
+    for (int v = s0; v < s1; ++v) seg += w(v);
+    double sincl = seg;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double y = __shfl_up(sincl, o, 64);
+        if (lane >= o) sincl += y;
+    }
+    const unsigned long long hit = __ballot(base + sincl > target);
+    int tok = -1;
+    if (hit) {
+        const int hl = __ffsll((long long)hit) - 1;
+        double before = base + __shfl(sincl - seg, hl, 64);  // running sum in front of that segment
+        const int h0 = min(c1, c0 + hl * per), h1 = min(c1, h0 + per);
+        for (int v0 = h0; v0 < h1 && tok < 0; v0 += 64) {
+            const int v = v0 + lane;
+            const double x = v < h1 ? w(v) : 0.0;
+            double ix = x;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const double y = __shfl_up(ix, o, 64);
+                if (lane >= o) ix += y;
+            }
+            const unsigned long long h2 = __ballot(before + ix > target);
+            if (h2) tok = v0 + __ffsll((long long)h2) - 1;
+            before += __shfl(ix, 63, 64);
+        }
+    }
+    // the chunk sum crossed but, in this summation order, no prefix did: its last positive id
+    return tok >= 0 ? tok : owner_last;
+}
+
+template <bool NUC>
+__global__ __launch_bounds__(64) void sample_locate_kernel(SampleArgs a, SpreadBuf b, int self_commit, int32_t* prefix_len) {
+    const int i = blockIdx.x;
+    // the chunk records of both kinds of weights are requested before anything is known about the sequence
+    const double* sums = b.sums + (size_t)i * b.chunks() * 2;
+    const int32_t* last = b.last + (size_t)i * b.chunks() * 2;
+    double xr[SPREAD_GROUPS64], xp[SPREAD_GROUPS64];
+    int lr[SPREAD_GROUPS64], lq[SPREAD_GROUPS64];
+#pragma unroll
+    for (int g = 0; g < SPREAD_GROUPS64; ++g) {
+        const int c = g * 64 + (int)threadIdx.x;
+        const bool in = c < b.chunks();
+        const int cc = in ? c : 0;
+        xr[g] = sums[cc * 2];
+        xp[g] = sums[cc * 2 + 1];
+        lr[g] = last[cc * 2];
+        lq[g] = last[cc * 2 + 1];
+        if (!in) {
+            xr[g] = 0.0;
+            xp[g] = 0.0;
+            lr[g] = -1;
+            lq[g] = -1;
+        }
+    }
+    const int acc_len = a.accept_len[i];
+    const double* rs = b.row_stats + 2 * (a.judge_index(i, acc_len) + 1);
+    const TokenWeights<NUC> w(a, i, acc_len, rs[0], rs[1]);
+    const double u = (double)a.u[i * (a.k + 1) + a.k];
+    int tok = -1;
+    if (w.qrow) {
+        auto rw = [&](int v) { return w.r(w.p(v), v); };
+        tok = wave_inverse_cdf(rw, a.V, u, xr, lr, b.chunks(), b.chunk);
+    }
+    if (tok < 0) {  // bonus token, or the residual vanished (p == q): draw from p
+        auto pw = [&](int v) { return w.p(v); };
+        tok = wave_inverse_cdf(pw, a.V, u, xp, lq, b.chunks(), b.chunk);
+    }
+    if (threadIdx.x == 0) {
         a.next_token[i] = tok;
         if (self_commit) {
             if (status_now(a.status) != 0) {
