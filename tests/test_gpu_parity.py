@@ -74,9 +74,14 @@ def _sampling_case(V, n, k, seed, has_root, peaked):
 @pytest.mark.parametrize("V,n,k,has_root,peaked", [(32000, 1, 8, False, False), (32000, 4, 8, False, True),
                                                     (32000, 8, 8, True, True), (4099, 3, 5, True, False),
                                                     (128256, 4, 16, False, True), (50, 2, 3, False, False),
-                                                    (1031, 1, 1, False, True), (32000, 1, 16, True, True)])
+                                                    (1031, 1, 1, False, True), (32000, 1, 16, True, True),
+                                                    (8200, 3, 5, False, False), (12345, 80, 1, False, True),
+                                                    (8192, 13, 6, True, True)])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_sampler_bit_exact_on_identical_logits(B, V, n, k, has_root, peaked, mode):
+    """Vocabularies below 8192 entries take the one-workgroup-per-sequence kernel, the others the kernels that cut the
+    vocabulary into slices: 8192 and 8200 (two slices, a ragged last chunk), 12345 with 80 sequences (one slice each),
+    32000 (seven slices), 128256 (thirty-one)."""
     total = ties = 0
     for seed in range(3):
         say(f"sampler V={V} n={n} k={k} root={has_root} peaked={peaked} mode={mode} seed={seed}")
@@ -98,7 +103,7 @@ def test_sampler_bit_exact_on_identical_logits(B, V, n, k, has_root, peaked, mod
 
 
 @pytest.mark.parametrize("V,n,k,has_root", [(32000, 1, 8, False), (32000, 4, 8, True), (4099, 3, 5, False),
-                                            (128256, 2, 16, False), (50, 2, 3, True)])
+                                            (128256, 2, 16, False), (50, 2, 3, True), (8200, 3, 5, True)])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_sampler_greedy_limit_bit_exact(B, V, n, k, has_root, mode):
     """Temperature 0: one-hot target distributions (arg max, lowest id among equal logits) on both sides."""
