@@ -403,7 +403,8 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
             QkvFinishArgs fa{ws.split, S, (size_t)M * ncols, ncols, Hq, Hkv, D, ws.q, qd, ws.q_plane, kc, vc, c.max_seq,
                              ws.rope_c, ws.rope_s, plan, cache.prefix_len};
             prof(DUO_PROF_QKV_FINISH, s);
-            DUO_LAUNCH(qkv_finish_kernel, dim3(Hq + 2 * Hkv, (M + 7) / 8), dim3(256), s, fa);
+            if (D == 128) DUO_LAUNCH(qkv_finish_kernel<128>, dim3(Hq + 2 * Hkv, (M + 7) / 8), dim3(256), s, fa);
+            else DUO_LAUNCH(qkv_finish_kernel<64>, dim3(Hq + 2 * Hkv, (M + 7) / 8), dim3(256), s, fa);
         } else if (qkv_nt == 1) launch_projection<1>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands, qkv_norm, eq, s);
         else launch_projection<2>(DUO_PROF_QKV, M, ws.h, w.wqkv[l], d, qkv_bands / 2, qkv_norm, eq, s);
 

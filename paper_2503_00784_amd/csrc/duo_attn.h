@@ -42,8 +42,8 @@ struct AttnArgs {
 // Merge the chunk partials (at most 64) of one (row, query head), normalise, store as a bf16 pair
 // (hi = operand row m, lo = operand row m + pair_rows).  Called by one wave.  Lane cb takes chunk cb's
 // max and sum (one load each instead of a chain of them), the maximum and the weighted sum are formed by
-// fixed butterflies; the outputs are then added in chunk order, lane handling D/64 channels, four
-// chunks' loads in flight at a time.
+// fixed butterflies; the outputs are then added in chunk order, lane handling D/64 channels; the first eight
+// chunks' outputs are requested together with the statistics, further ones four at a time.
 template <int D>
 __device__ __forceinline__ void attn_merge_row(const AttnArgs& a, int hk, int r, int lane) {
     const int m = r / a.group, gq = r % a.group;
@@ -51,6 +51,16 @@ __device__ __forceinline__ void attn_merge_row(const AttnArgs& a, int hk, int r,
     const bool has = lane < a.nchunks;
     const float mc = has ? pp[(size_t)lane * (D + 4) + D] : -INFINITY;
     const float lc = has ? pp[(size_t)lane * (D + 4) + D + 1] : 0.f;
+    // the first eight chunks' outputs are requested with the statistics (they do not depend on them)
+    constexpr int PRE = 8;
+    float vp[PRE][D / 64];
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const int cb = i < a.nchunks ? i : a.nchunks - 1;
+#pragma unroll
+        for (int e = 0; e < D / 64; ++e) vp[i][e] = pp[(size_t)cb * (D + 4) + lane + e * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
     float mx = mc;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
@@ -61,7 +71,13 @@ __device__ __forceinline__ void attn_merge_row(const AttnArgs& a, int hk, int r,
     float acc[D / 64];
 #pragma unroll
     for (int e = 0; e < D / 64; ++e) acc[e] = 0.f;
-    for (int cb0 = 0; cb0 < a.nchunks; cb0 += 4) {
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const float wc = i < a.nchunks ? __shfl(w, i, 64) : 0.f;
+#pragma unroll
+        for (int e = 0; e < D / 64; ++e) acc[e] += vp[i][e] * wc;
+    }
+    for (int cb0 = PRE; cb0 < a.nchunks; cb0 += 4) {
         float v[4][D / 64], wc[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {

@@ -149,7 +149,7 @@ static inline void launch_residual_reduce(int M, const float* part, int S, size_
 // channel (V tiles); wave w takes pairs 8w .. 8w+7 of every 32.
 struct QkvFinishArgs {
     const float* part;
-    int S;
+    int S;  // one or two splits
     size_t split_stride;
     int ncols;
     int Hq, Hkv, D;
@@ -165,39 +165,62 @@ struct QkvFinishArgs {
     const int32_t* dev_prefix_len;  // may be nullptr; a device prefix length other than plan.P: nothing goes to the cache
 };
 
+// All loads of a thread (its channel pairs x the splits, the rotary factors, the device prefix length) are requested
+// before the first is used: the kernel is one memory round trip and its stores.
+template <int D>
 __global__ __launch_bounds__(256) void qkv_finish_kernel(QkvFinishArgs a) {
-    const int head = blockIdx.x, half = a.D / 2, bph = a.D / 16;
+    constexpr int half = D / 2, bph = D / 16, IT = half / 32, MAXS = 2;
+    const int head = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = blockIdx.y * 8 + (lane & 7);
     if (m >= a.plan.M) return;
-    const bool cache_ok = !a.dev_prefix_len || *a.dev_prefix_len == a.plan.P;
+    const int32_t dev_P = a.dev_prefix_len ? *a.dev_prefix_len : a.plan.P;
     const float* row = a.part + (size_t)m * a.ncols;
-    for (int dd = wave * 8 + (lane >> 3); dd < half; dd += 32) {
+    const bool rotate = head < a.Hq + a.Hkv;
+    float p_lo[IT][MAXS], p_hi[IT][MAXS], cs[IT], sn[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+        const int dd = it * 32 + wave * 8 + (lane >> 3);
         const int n_lo = (head * bph + (dd >> 3)) * 16 + (dd & 7);  // channel dd; its partner dd + D/2 sits 8 columns on
-        float x_lo = 0.f, x_hi = 0.f;
-        for (int sp = 0; sp < a.S; ++sp) {
-            x_lo += row[(size_t)sp * a.split_stride + n_lo];
-            x_hi += row[(size_t)sp * a.split_stride + n_lo + 8];
+#pragma unroll
+        for (int sp = 0; sp < MAXS; ++sp) {  // a split that is not there: split 0 again, not added
+            const float* ps = row + (sp < a.S ? (size_t)sp * a.split_stride : 0);
+            p_lo[it][sp] = ps[n_lo];
+            p_hi[it][sp] = ps[n_lo + 8];
         }
-        if (head < a.Hq + a.Hkv) {
-            const float cs = a.rope_cos[m * half + dd], sn = a.rope_sin[m * half + dd];
-            const float r_lo = x_lo * cs - x_hi * sn, r_hi = x_hi * cs + x_lo * sn;
+        cs[it] = rotate ? a.rope_cos[m * half + dd] : 1.f;
+        sn[it] = rotate ? a.rope_sin[m * half + dd] : 0.f;
+    }
+    const bool cache_ok = dev_P == a.plan.P;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+        const int dd = it * 32 + wave * 8 + (lane >> 3);
+        float x_lo = 0.f, x_hi = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < MAXS; ++sp) {
+            if (sp < a.S) {
+                x_lo += p_lo[it][sp];
+                x_hi += p_hi[it][sp];
+            }
+        }
+        if (rotate) {
+            const float r_lo = x_lo * cs[it] - x_hi * sn[it], r_hi = x_hi * cs[it] + x_lo * sn[it];
             if (head < a.Hq) {
-                u16* q = a.q_out + (size_t)m * a.ldq + head * a.D;
+                u16* q = a.q_out + (size_t)m * a.ldq + head * D;
                 const u16 h_lo = f32_to_elem(r_lo), h_hi = f32_to_elem(r_hi);
                 q[dd] = h_lo;
                 q[half + dd] = h_hi;
                 q[a.q_plane + dd] = f32_to_elem(r_lo - elem_to_f32(h_lo));
                 q[a.q_plane + half + dd] = f32_to_elem(r_hi - elem_to_f32(h_hi));
             } else if (cache_ok) {
-                u16* kp = a.kc + (size_t)(head - a.Hq) * a.max_seq * a.D;
-                kp[k_cache_offset(a.D, a.plan.slot(m), dd)] = f32_to_elem(r_lo);
-                kp[k_cache_offset(a.D, a.plan.slot(m), half + dd)] = f32_to_elem(r_hi);
+                u16* kp = a.kc + (size_t)(head - a.Hq) * a.max_seq * D;
+                kp[k_cache_offset(D, a.plan.slot(m), dd)] = f32_to_elem(r_lo);
+                kp[k_cache_offset(D, a.plan.slot(m), half + dd)] = f32_to_elem(r_hi);
             }
         } else if (cache_ok) {
-            u16* vp = a.vc + (size_t)(head - a.Hq - a.Hkv) * a.max_seq * a.D;
-            vp[v_cache_offset(a.D, a.plan.slot(m), dd)] = f32_to_elem(x_lo);
-            vp[v_cache_offset(a.D, a.plan.slot(m), half + dd)] = f32_to_elem(x_hi);
+            u16* vp = a.vc + (size_t)(head - a.Hq - a.Hkv) * a.max_seq * D;
+            vp[v_cache_offset(D, a.plan.slot(m), dd)] = f32_to_elem(x_lo);
+            vp[v_cache_offset(D, a.plan.slot(m), half + dd)] = f32_to_elem(x_hi);
         }
     }
 }
