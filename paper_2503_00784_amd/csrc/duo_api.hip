@@ -425,8 +425,8 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
         }
         if (nchunks > 1) {
             prof(DUO_PROF_ATTN_COMB, s);
-            if (D == 128) DUO_LAUNCH((attn_combine_kernel<128>), dim3(MQ, Hkv), dim3(64), s, aa);
-            else DUO_LAUNCH((attn_combine_kernel<64>), dim3(MQ, Hkv), dim3(64), s, aa);
+            if (D == 128) DUO_LAUNCH((attn_combine_kernel<128>), dim3((MQ + 3) / 4, Hkv), dim3(256), s, aa);
+            else DUO_LAUNCH((attn_combine_kernel<64>), dim3((MQ + 3) / 4, Hkv), dim3(256), s, aa);
         }
 
         // the residual projections leave x, the next norm's operand u = x * gain and its partial sums

@@ -788,7 +788,8 @@ __global__ __launch_bounds__((NWV + 1) * 64) void attn_shared_kernel(AttnArgs a)
 
 // Merge of the chunk partials when a head was split over several workgroups: one wave per (row, head).
 template <int D>
-__global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
-    attn_merge_row<D>(a, blockIdx.y, blockIdx.x, threadIdx.x);
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);  // four waves, four rows
+    if (r < a.plan.M * a.group) attn_merge_row<D>(a, blockIdx.y, r, threadIdx.x & 63);
 }
 
