@@ -61,6 +61,8 @@ int block_splits(int M, int N) {
 
 // GEMM operand buffers (h, attn, act) hold activations as bf16 pairs: row m = hi, row pair_rows + m = lo,
 // padded to whole 16-row MFMA tiles; rows that carry no activation are never stored from.
+constexpr int QKV_SPLITS = 4;  // most K splits of the Q/K/V projection at 49..80 rows (QkvFinishArgs::MAX_SPLITS)
+
 struct Workspace {
     float* x;        // fp32 residual stream [M][d]
     u16* h;          // normalised activations, operand layout [A_rows][d]
@@ -144,7 +146,7 @@ Workspace carve(const duo_model_config& c, int max_rows, void* base_v) {
     ws.ssq = reinterpret_cast<float*>(take(Mp * (d / 16) * 4));
     ws.ssq_full = reinterpret_cast<float*>(take(Mp * RowScale::FULL_PARTS * 4));
     ws.split_floats = (size_t)(many ? block_splits(max_rows, c.d_model) : WIDE_MAX_SPLIT) * Mp * d;
-    if (!many) ws.split_floats = std::max(ws.split_floats, (size_t)2 * Mp * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
+    if (!many) ws.split_floats = std::max(ws.split_floats, (size_t)QKV_SPLITS * Mp * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
     ws.split = reinterpret_cast<float*>(take(ws.split_floats * 4));
     ws.h_last = reinterpret_cast<u16*>(take(16 * d * 2));
     carve_sampler(base, off, c.vocab, ws, lm_head_parts(c.vocab));
@@ -377,7 +379,7 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
     const int qkv_bands = (Hq + 2 * Hkv) * (D / 16);
     const int qkv_nt = M > DUO_MAX_ROWS ? 2 : (M <= 8 ? ((qkv_bands > 512 && qkv_bands <= 768) ? 1 : 2) : (qkv_bands <= 768 ? 1 : 2));
     // the Q/K/V projection as K-split product + finish kernel (see the loop): 49..80 rows, one band per wave, partial results fit
-    const bool qkv_split = M > 48 && M <= DUO_MAX_ROWS && qkv_nt == 1 && (size_t)2 * M * qkv_bands * 16 <= ws.split_floats;
+    const bool qkv_split = M > 48 && M <= DUO_MAX_ROWS && qkv_nt == 1 && (size_t)QKV_SPLITS * M * qkv_bands * 16 <= ws.split_floats;
     for (int l = 0; l < c.n_layers; ++l) {
         u16* kc = cache.k + (size_t)l * Hkv * c.max_seq * D;
         u16* vc = cache.v + (size_t)l * Hkv * c.max_seq * D;
@@ -385,20 +387,23 @@ void enqueue_forward(const duo_model_config& c, const duo_weights& w, const duo_
                   cache.prefix_len, 1};
         const RowScale& qkv_norm = (l == 0 || down_split) ? norm_full : norm_part;
         if (qkv_split) {
-            // 49..80 rows: K split two ways over workgroups of twice the bands, each staging half of the operand
-            // (22.1 against 27.1 us for the product at 64 rows x 768 bands), partial results to the workspace, and a
+            // 49..80 rows: K split two or four ways over workgroups of as many times the bands, each staging its part of the
+            // operand (22.1 against 27.1 us for the product at 64 rows x 768 bands), partial results to the workspace, and a
             // small second kernel that adds them and does the rotary embedding and the cache scatter
             const int ncols = qkv_bands * 16;
             EpiStoreF32 ep{ncols, M, 1, ws.split, ncols, (size_t)M * ncols};
             const int quads = pair_rows_for(M) / 4;
             int S = 1;
             prof(DUO_PROF_QKV, s);
+            // (measured on one box: 768 bands, two splits of six-band workgroups 24.2 + 4.2 us against four splits of
+            // twelve-band workgroups 26.6 + 5.5 us; 384 bands, four splits of six-band workgroups 15.2 + 4.6 us against
+            // two splits of three-band workgroups 16.7 + 4.1 us)
             if (M <= 64) {
                 if (qkv_bands > 512) launch_wide_cfg<4, 1, 6, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
-                else launch_wide_cfg<4, 1, 3, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
+                else launch_wide_cfg<4, 1, 6, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, QKV_SPLITS, qkv_norm, ep, s, &S);
             } else {
                 if (qkv_bands > 512) launch_wide_cfg<5, 1, 6, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
-                else launch_wide_cfg<5, 1, 3, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, 2, qkv_norm, ep, s, &S);
+                else launch_wide_cfg<5, 1, 6, 1>(ws.h, w.wqkv[l], d, qkv_bands, quads, QKV_SPLITS, qkv_norm, ep, s, &S);
             }
             QkvFinishArgs fa{ws.split, S, (size_t)M * ncols, ncols, Hq, Hkv, D, ws.q, qd, ws.q_plane, kc, vc, c.max_seq,
                              ws.rope_c, ws.rope_s, plan, cache.prefix_len};

@@ -148,8 +148,9 @@ static inline void launch_residual_reduce(int M, const float* part, int S, size_
 // 8 * pair), so that a store instruction covers runs of eight channels of a row (Q, K tiles) and of eight slots of a
 // channel (V tiles); wave w takes pairs 8w .. 8w+7 of every 32.
 struct QkvFinishArgs {
+    static constexpr int MAX_SPLITS = 4;
     const float* part;
-    int S;  // one or two splits
+    int S;  // splits, at most MAX_SPLITS
     size_t split_stride;
     int ncols;
     int Hq, Hkv, D;
@@ -169,7 +170,7 @@ struct QkvFinishArgs {
 // before the first is used: the kernel is one memory round trip and its stores.
 template <int D>
 __global__ __launch_bounds__(256) void qkv_finish_kernel(QkvFinishArgs a) {
-    constexpr int half = D / 2, bph = D / 16, IT = half / 32, MAXS = 2;
+    constexpr int half = D / 2, bph = D / 16, IT = half / 32, MAXS = QkvFinishArgs::MAX_SPLITS;
     const int head = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = blockIdx.y * 8 + (lane & 7);
