@@ -248,10 +248,13 @@ void launch_projection(int cls, int M, const u16* X, const u16* W, int K, int ti
 // second kernel that adds them in split order and does EpiResidual's work.
 static_assert(WIDE_MAX_SPLIT <= 8, "residual_reduce_kernel holds at most eight splits in registers");
 
-// Whether the residual projection over K input channels runs as K-split partial products + reduce kernel.
-bool residual_is_split(int M, int K, int N) {
+// Whether the residual projection over K input channels runs as K-split partial products + reduce kernel: beyond 16
+// rows.  (At 32 rows x 4096 input channels the split form alone is no faster, 10.3 + 4.2 against 14.0 us, but the reduce
+// kernel leaves whole-row sums of squares, which the next projection turns into its factors 2.5 us sooner than the 256
+// partial sums per row of the one-kernel form: 3.62 -> 3.53 ms per step at 32 rows of the 7B shape.)
+bool residual_is_split(int M, int /*K*/, int N) {
     if (M > DUO_MAX_ROWS) return block_splits(M, N) > 1;
-    return !(M <= 16 || (M <= 32 && K <= 6144));
+    return M > 16;
 }
 
 void launch_residual_projection(int M, const u16* X, const u16* W, int K, const EpiResidual& er, float* split,
