@@ -250,6 +250,15 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     static_assert(RED <= NBUF * BUF, "the partial sums fit the ring buffers");
     __shared__ u32x4 lds[NBUF * BUF];
     __shared__ float row_scale[MH * 16];
+    // HALF, factors from partial sums (the producer of the rows was a one-kernel residual projection): the eight rows'
+    // partial sums come in with the producer wave's first global -> LDS loads and every consumer wave adds them up for
+    // itself once round 0 has landed, in the order RowScale::reduce uses.  Fetching them into registers at the top of the
+    // kernel holds up the wave that does it, and with it the first hand-over, by a memory round trip (1.1 us of the Q/K/V
+    // projection's 18.9 us at eight rows).
+    constexpr int RAW16 = HALF ? 8 * 512 / 4 : 1;  // 16-byte pieces: eight rows of at most 512 partial sums
+    __shared__ u32x4 part_raw[RAW16];
+    __shared__ float row_scale_w[HALF ? NG * NK * 8 : 1];
+    const bool raw_part = HALF && rsc.part && !rsc.full;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // scalar: MFMA ignores EXEC
     const int steps = K >> 5;
@@ -261,7 +270,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
 
     if (rsc.full) {
         for (int m = threadIdx.x; m < quads * 4; m += NTH) row_scale[m] = 1.0f / sqrtf(rsc.full_row(m) * rsc.inv_d + rsc.eps);
-    } else if (rsc.part) {
+    } else if (rsc.part && !raw_part) {
         const int nrows = quads * 4;
         f32x4 rsv[RowScale::MAXQ];
         for (int r0 = wave * 8; r0 < nrows; r0 += (NC + 1) * 8) {
@@ -286,6 +295,18 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
         // wait for ALL outstanding loads, including the round just requested.  vmcnt(L) = everything but the
         // youngest round has landed in LDS (expcnt and lgkmcnt fields left at their maxima).
         constexpr int WAIT_ALL_BUT_ONE_ROUND = (L & 15) | ((L >> 4) << 14) | (7 << 4) | (15 << 8);
+        if constexpr (HALF) {
+            // older than every round: the first counted wait below covers them.  No branch around them (a join here makes
+            // the compiler wait for everything in flight): without partial sums to fetch, the pieces re-read the operand.
+            const int n16 = raw_part ? 2 * rsc.n_part : 64;  // eight rows x n_part floats
+            const u32x4* src = raw_part ? reinterpret_cast<const u32x4*>(rsc.part) : reinterpret_cast<const u32x4*>(X);
+#pragma unroll
+            for (int c = 0; c < RAW16 / 64; ++c) {  // pieces past the end repeat the last one
+                const int i = min(c * 64 + lane, n16 - 1);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + i),
+                                                 (__attribute__((address_space(3))) void*)(part_raw + c * 64), 16, 0, 0);
+            }
+        }
         issue(0);
         issue(1);
         __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_ROUND & ~(15 << 8));  // and lgkmcnt(0): this wave's row scales are written
@@ -344,6 +365,24 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     __syncthreads();  // round 0 is in LDS, the row scales are written
     a_frags(0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
+    const float* rsp = row_scale;
+    if constexpr (HALF) {
+        if (raw_part) {  // LDS reads only: the weight stream's memory counter is not involved
+            const int m = lane & 7, seg = lane >> 3;
+            const int nq = rsc.n_part >> 2, len = (nq + 7) >> 3;
+            const int b = seg * len, e = min(nq, b + len);
+            const f32x4* row = reinterpret_cast<const f32x4*>(part_raw) + m * nq;
+            f32x4 rsv[RowScale::MAXQ];
+#pragma unroll
+            for (int q = 0; q < RowScale::MAXQ; ++q) {
+                const int i = b + q;
+                rsv[q] = row[i < e ? i : (e > 0 ? e - 1 : 0)];
+            }
+            rsc.reduce(rsv, row_scale_w + wave * 8, 0, 8, lane);
+            rsp = row_scale_w + wave * 8;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 
     const elem8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int r0 = 0; r0 < rounds; r0 += U) {
@@ -395,7 +434,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) v[t][i] *= row_scale[qi * 4 + i];
+                        for (int i = 0; i < 4; ++i) v[t][i] *= rsp[qi * 4 + i];
                 }
                 epi.store(tile, qi, lane & 15, v, pre, use_pre);
             }
