@@ -136,8 +136,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
     // for the first output quad of each thread, so that its latency hides behind the weight stream.
     typename Epi::Pre pre;
     epi.arm();
-    const bool has_pre = (int)threadIdx.x < quads * 16;
-    if (has_pre) epi.prefetch(tile, threadIdx.x >> 4, threadIdx.x & 15, pre);
+    epi.prefetch(tile, min((int)threadIdx.x >> 4, quads - 1), threadIdx.x & 15, pre);  // every thread: no branch around loads
     // Per-row RMSNorm factors of the operand (see RowScale): the partial sums of the wave's first eight
     // rows are requested before the first weights and added up while those are in flight.
     const int nrows = quads * 4;
@@ -357,8 +356,7 @@ __global__ __launch_bounds__((NG * NK + 1) * 64) void gemm_wide_kernel(const u16
     typename Epi::Pre pre;
     epi.arm();
     const int first_mh = NK > 1 ? nk : 0;  // the first row tile this wave finishes
-    const bool has_pre = HALF && live && first_mh < MH && first_mh * 4 + (lane >> 4) < quads;  // store4 takes none
-    if (has_pre) epi.prefetch(tile, first_mh * 4 + (lane >> 4), lane & 15, pre);
+    if constexpr (HALF) epi.prefetch(tile, min(first_mh * 4 + (lane >> 4), quads - 1), lane & 15, pre);  // store4 takes none; every lane: no branch around loads
 #pragma unroll
     for (int p = 0; p < PF; ++p) w_load(p, p);
     __builtin_amdgcn_sched_barrier(0);
@@ -668,12 +666,14 @@ struct EpiResidual {
     };
     __device__ __forceinline__ void arm() {}
     __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
+        // no branch around a load: behind a join the compiler waits for every load in flight, and the weight stream
+        // would start a memory round trip late (rows past M re-read row M - 1 and are not used)
         const int n = tile * 16 + c;
         p.g = elem_to_f32(gain[n]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = qi * 4 + i;
-            p.x[i] = m < M ? X[(size_t)m * ldx + n] : 0.f;
+            p.x[i] = X[(size_t)(m < M ? m : M - 1) * ldx + n];
         }
     }
     __device__ __forceinline__ void store(int tile, int qi, int c, const f32x4 (&v)[1], const Pre& p, bool use_pre) const {
@@ -791,17 +791,20 @@ struct EpiQKV {
     __device__ __forceinline__ void arm() { cache_ok = !dev_prefix_len || *dev_prefix_len == plan.P; }
     // Column c of band (head, j) is channel 8j + c (c < 8) or its rotary partner D/2 + 8j + c - 8.
     __device__ __forceinline__ void prefetch(int tile, int qi, int c, Pre& p) const {
+        // no branch around a load (see EpiResidual::prefetch): a band that is not there repeats the first, rows past M
+        // re-read row M - 1, and what is not rotated gets the identity afterwards
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            if (t >= nt) break;
-            const int band = tile * nt + t, head = band / bph;
+            const int band = tile * nt + (t < nt ? t : 0), head = band / bph;
             const int d = (band - head * bph) * 8 + (c & 7);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int m = qi * 4 + i;
                 const bool rot = m < plan.M && head < Hq + Hkv;
-                p.cs[t][i] = rot ? rope_cos[m * half + d] : 1.f;
-                p.sn[t][i] = rot ? rope_sin[m * half + d] : 0.f;
+                const int mc = m < plan.M ? m : plan.M - 1;
+                const float cs = rope_cos[mc * half + d], sn = rope_sin[mc * half + d];
+                p.cs[t][i] = rot ? cs : 1.f;
+                p.sn[t][i] = rot ? sn : 0.f;
             }
         }
     }
