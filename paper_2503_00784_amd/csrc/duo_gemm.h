@@ -139,9 +139,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
     epi.prefetch(tile, min((int)threadIdx.x >> 4, quads - 1), threadIdx.x & 15, pre);  // every thread: no branch around loads
     // Per-row RMSNorm factors of the operand (see RowScale): the partial sums of the wave's first eight
     // rows are requested before the first weights and added up while those are in flight.
+    // (compile-time for epilogues whose input takes no factors: every branch between the prefetch and the main loop is a
+    // join at which the compiler waits for most of the prefetch)
+    constexpr bool NORM = Epi::NORMALISED_INPUT;
     const int nrows = quads * 4;
     f32x4 rsv[RowScale::MAXQ];
-    const bool rs_first = rsc.part && wave * 8 < nrows;
+    const bool rs_first = NORM && rsc.part && wave * 8 < nrows;
     if (rs_first) rsc.load(rsv, wave * 8, nrows, lane);
     __builtin_amdgcn_sched_barrier(0);
     if (ni > 0) {
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
     }
     __builtin_amdgcn_sched_barrier(0);
     if (rs_first) rsc.reduce(rsv, row_scale, wave * 8, nrows, lane);
-    if (rsc.part)
+    if (NORM && rsc.part)
         for (int r0 = (wave + NW) * 8; r0 < nrows; r0 += NW * 8) {  // more than 8 * NW rows
             rsc.load(rsv, r0, nrows, lane);
             rsc.reduce(rsv, row_scale, r0, nrows, lane);
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const u16* __restr
                 for (int w = 1; w < NW; ++w) l += red[w * MT * NT * 64 + slot_lo + t * 64];
                 s += l;
             }
-            if (rsc.part) {
+            if (NORM && rsc.part) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) s[i] *= row_scale[qi * 4 + i];
             }
@@ -507,6 +510,7 @@ __device__ __forceinline__ u32x2 pack_elem4(const f32x4& x) {
 
 struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile*NT + t)*16 .. +16 of W
     static constexpr const char* NAME = "EpiStoreF32";
+    static constexpr bool NORMALISED_INPUT = true;
     int N, M, NT;
     float* Y;
     int ldy;
@@ -552,6 +556,7 @@ struct EpiStoreF32 {  // y[m][n] = sum ; band t of a workgroup covers rows (tile
 // attains it.  parts [M][nparts][2], part index = tile; the sampling kernels merge a row's parts in index order.
 struct EpiLogitsStats {
     static constexpr const char* NAME = "EpiLogitsStats";
+    static constexpr bool NORMALISED_INPUT = true;
     int N, M, NT;
     float* Y;
     int ldy;
@@ -654,6 +659,7 @@ struct EpiLogitsStats {
 // operand buffer, and the tile's partial sum of x^2 per row.  One band per workgroup (NT = 1).
 struct EpiResidual {
     static constexpr const char* NAME = "EpiResidual";
+    static constexpr bool NORMALISED_INPUT = false;  // its input is never an RMSNorm operand (attention output, SwiGLU output): the kernels compile the factors out
     int N, M;
     float* X;
     int ldx;
@@ -729,6 +735,7 @@ struct EpiResidual {
 // bf16 pair straight into the down projection's operand buffer (row m hi, row pair_rows + m lo)
 struct EpiSwiGLU {
     static constexpr const char* NAME = "EpiSwiGLU";
+    static constexpr bool NORMALISED_INPUT = true;
     int F, M;
     u16* act;
     int act_tiles, pair_rows;
@@ -769,6 +776,7 @@ struct EpiSwiGLU {
 // into their cache slots (tiled layouts, see k_cache_offset / v_cache_offset).
 struct EpiQKV {
     static constexpr const char* NAME = "EpiQKV";
+    static constexpr bool NORMALISED_INPUT = true;
     int Hq, Hkv, D, half, bph;  // bph = D/16 bands per head
     int nt;                     // bands per workgroup tile of the launch that uses this epilogue (1 or 2)
     u16* q_out;  // hi plane; the lo plane starts q_plane elements further on
